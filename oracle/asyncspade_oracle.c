@@ -1,0 +1,334 @@
+/*
+ * CPU oracle for the KV-selection hot path of AsyncSpade.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64, written from the paper's
+ * definitions; it shares no code with the HIP library and must never be called
+ * from the product path (only tests, the smoke check and the cpu_baseline leg
+ * of the benchmark may load it).
+ *
+ * All pointers are HOST pointers.  bf16 values travel as uint16_t bit patterns.
+ * Values cross stage boundaries in the representation the device path uses
+ * (q_hat fp32, scores fp32, attention output bf16 round-to-nearest-even) so each
+ * stage can be compared in isolation.
+ *
+ * Stages (Sec. 4.2, Sec. 4.3, Appendix C Alg. 1):
+ *   predict  Eq. 2-5: ridge regression of Q_t on its k newest predecessors,
+ *            softmax of the solved weights, applied to the window shifted by
+ *            one token; one candidate per window size k = 1..W; mean over k.
+ *   score    Alg. 1 step 7 with the batched-matmul shapes of Sec. 4.3:
+ *            s[b,j,n] = agg_g <q_hat[b, j*G+g], K[b,j,n]>.
+ *   top-k    Sec. 4.3 item (2): the C highest-scoring tokens per KV head.
+ *   attend   softmax(q K_S^T * scale) V_S over the selected set S (Sec. 4.1;
+ *            Appendix B counts exactly this work, 4*q*h*C flops).
+ *
+ * Pins (tests/test_oracle_*.py): closed forms of the predictor on hand-built
+ * windows, numpy.linalg.solve, brute-force argsort, numpy GEMV, dense attention
+ * from torch's CPU SDPA, and softmax special cases.  Three readings are free
+ * parameters that the paper does not fix and therefore stay "parity unpinned":
+ * the sign beta inside softmax(beta*omega), the value of epsilon, and how the
+ * per-query-head logits of a GQA group are aggregated into one per-KV-head
+ * score (max or sum).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ASO_AGG_MAX 0
+#define ASO_AGG_SUM 1
+
+static double bf16_to_f64(uint16_t h) {
+  uint32_t u = ((uint32_t)h) << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+/* One rounding, double -> bf16 (8 significant bits), ties to even. */
+static uint16_t f64_to_bf16(double d) {
+  if (isnan(d)) return 0x7fc0;
+  if (isinf(d)) return d > 0 ? 0x7f80 : 0xff80;
+  if (d == 0.0) return signbit(d) ? 0x8000 : 0;
+  int e;
+  (void)frexp(fabs(d), &e);                 /* |d| = m * 2^e, m in [0.5,1) */
+  int lsb = e - 8;                          /* exponent of the last kept bit */
+  if (lsb < -133) lsb = -133;               /* bf16 subnormal spacing */
+  double q = nearbyint(ldexp(fabs(d), -lsb)); /* default mode = ties to even */
+  double r = ldexp(q, lsb);
+  float f = (float)(d < 0 ? -r : r);        /* exact unless overflow -> inf */
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  return (uint16_t)(u >> 16);
+}
+
+int aso_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+  return omp_get_max_threads();
+#else
+  (void)n;
+  return 1;
+#endif
+}
+
+/* Solve A x = rhs (n x n, row-major, both destroyed) by Gaussian elimination
+ * with partial pivoting.  Returns 0, or -1 if a pivot vanishes. */
+static int solve_dense(int n, double* A, double* rhs, double* x) {
+  for (int c = 0; c < n; ++c) {
+    int p = c;
+    for (int r = c + 1; r < n; ++r)
+      if (fabs(A[r * n + c]) > fabs(A[p * n + c])) p = r;
+    if (A[p * n + c] == 0.0) return -1;
+    if (p != c) {
+      for (int k = 0; k < n; ++k) { double t = A[c * n + k]; A[c * n + k] = A[p * n + k]; A[p * n + k] = t; }
+      double t = rhs[c]; rhs[c] = rhs[p]; rhs[p] = t;
+    }
+    for (int r = c + 1; r < n; ++r) {
+      double f = A[r * n + c] / A[c * n + c];
+      for (int k = c; k < n; ++k) A[r * n + k] -= f * A[c * n + k];
+      rhs[r] -= f * rhs[c];
+    }
+  }
+  for (int r = n - 1; r >= 0; --r) {
+    double s = rhs[r];
+    for (int k = r + 1; k < n; ++k) s -= A[r * n + k] * x[k];
+    x[r] = s / A[r * n + r];
+  }
+  return 0;
+}
+
+/*
+ * Ridge weights for one window size (Eq. 2 read as the linear problem that
+ * Alg. 1 step 3 solves): omega = (R R^T + eps I)^-1 R T, with R the k newest
+ * predecessors (row i-1 = Q_{t-i}) and T = Q_t.
+ *   R [k][D], T [D] fp64; omega [k] out.
+ */
+int aso_ridge_weights(int k, int D, const double* R, const double* T, double eps, double* omega) {
+  double* G = (double*)malloc(sizeof(double) * k * k);
+  double* b = (double*)malloc(sizeof(double) * k);
+  if (!G || !b) { free(G); free(b); return -2; }
+  for (int i = 0; i < k; ++i) {
+    for (int j = 0; j < k; ++j) {
+      double s = 0.0;
+      for (int d = 0; d < D; ++d) s += R[i * D + d] * R[j * D + d];
+      G[i * k + j] = s + (i == j ? eps : 0.0);
+    }
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) s += R[i * D + d] * T[d];
+    b[i] = s;
+  }
+  int rc = solve_dense(k, G, b, omega);
+  free(G); free(b);
+  return rc;
+}
+
+/*
+ * Predictor, Sec. 4.2 (Eq. 4, Eq. 5) for every (b, h).
+ *   q_win  bf16 [B][Hq][W][D], oldest first (Q_{t-W} .. Q_{t-1})
+ *   q_cur  bf16 [B][Hq][D]      (Q_t)
+ *   q_hat  fp32 [B][Hq][D] out  (prediction of Q_{t+1})
+ *   weights_out  nullable fp64 [B][Hq][W][W]; entry [k-1][i-1] = w^{(k)}_{t-i}
+ *                for i <= k, 0 above.
+ * Returns 0, -1 on bad arguments or a singular system.
+ */
+int aso_predict_query(int B, int Hq, int W, int D, const uint16_t* q_win, const uint16_t* q_cur,
+                      double eps, double beta, float* q_hat, double* weights_out) {
+  if (B < 0 || Hq <= 0 || W < 1 || D <= 0 || !(eps > 0.0)) return -1;
+  int fail = 0;
+#pragma omp parallel for schedule(static)
+  for (int bh = 0; bh < B * Hq; ++bh) {
+    double* R = (double*)malloc(sizeof(double) * W * D);   /* R[i-1] = Q_{t-i}        */
+    double* S = (double*)malloc(sizeof(double) * W * D);   /* S[i-1] = Q_{t+1-i}      */
+    double* T = (double*)malloc(sizeof(double) * D);
+    double* om = (double*)malloc(sizeof(double) * W);
+    double* w = (double*)malloc(sizeof(double) * W);
+    double* acc = (double*)calloc(D, sizeof(double));
+    const uint16_t* win = q_win + (size_t)bh * W * D;
+    const uint16_t* cur = q_cur + (size_t)bh * D;
+    for (int d = 0; d < D; ++d) T[d] = bf16_to_f64(cur[d]);
+    for (int i = 1; i <= W; ++i)
+      for (int d = 0; d < D; ++d) R[(i - 1) * D + d] = bf16_to_f64(win[(size_t)(W - i) * D + d]);
+    /* shifted window: Q_{t+1-i}; i = 1 is Q_t itself, i >= 2 is R_{i-1} */
+    for (int d = 0; d < D; ++d) S[d] = T[d];
+    for (int i = 2; i <= W; ++i)
+      for (int d = 0; d < D; ++d) S[(i - 1) * D + d] = R[(i - 2) * D + d];
+
+    for (int k = 1; k <= W; ++k) {
+      if (aso_ridge_weights(k, D, R, T, eps, om) != 0) {
+#pragma omp atomic write
+        fail = 1;
+        continue;
+      }
+      /* softmax normalisation, Eq. 3 */
+      double mx = beta * om[0];
+      for (int i = 1; i < k; ++i) if (beta * om[i] > mx) mx = beta * om[i];
+      double z = 0.0;
+      for (int i = 0; i < k; ++i) { w[i] = exp(beta * om[i] - mx); z += w[i]; }
+      for (int i = 0; i < k; ++i) w[i] /= z;
+      if (weights_out) {
+        double* wo = weights_out + ((size_t)bh * W + (k - 1)) * W;
+        for (int i = 0; i < W; ++i) wo[i] = i < k ? w[i] : 0.0;
+      }
+      /* candidate for window size k applied to the shifted window (Eq. 4),
+         accumulated into the mean of Eq. 5 */
+      for (int d = 0; d < D; ++d) {
+        double c = 0.0;
+        for (int i = 0; i < k; ++i) c += w[i] * S[i * D + d];
+        acc[d] += c;
+      }
+    }
+    for (int d = 0; d < D; ++d) q_hat[(size_t)bh * D + d] = (float)(acc[d] / (double)W);
+    free(R); free(S); free(T); free(om); free(w); free(acc);
+  }
+  return fail ? -1 : 0;
+}
+
+static const uint16_t* token_ptr(const uint16_t* pool, const int32_t* block_table, int max_pages,
+                                 int Hkv, int P, int D, int b, int j, int n) {
+  int64_t page = block_table[(int64_t)b * max_pages + n / P];
+  int slot = n % P;
+  return pool + ((page * Hkv + j) * P + slot) * (int64_t)D;
+}
+
+/*
+ * Criticality scores (Alg. 1 step 7; shapes of Sec. 4.3).
+ *   k_pool bf16 [num_pages][Hkv][P][D]; block_table [B][max_pages]; ctx_lens [B]
+ *   q_hat fp32 [B][Hq][D]; scores fp32 [B][Hkv][stride]; entries n >= ctx_lens[b]
+ *   are left untouched.  agg: 0 = max over the group, 1 = sum.
+ */
+int aso_score_keys(int B, int Hq, int Hkv, int D, int P, const uint16_t* k_pool,
+                   const int32_t* block_table, int max_pages, const int32_t* ctx_lens,
+                   const float* q_hat, int agg, float* scores, int64_t stride) {
+  if (Hkv <= 0 || Hq % Hkv != 0) return -1;
+  int G = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < Hkv; ++j) {
+      int N = ctx_lens[b];
+      for (int n = 0; n < N; ++n) {
+        const uint16_t* kr = token_ptr(k_pool, block_table, max_pages, Hkv, P, D, b, j, n);
+        double best = 0.0;
+        for (int g = 0; g < G; ++g) {
+          const float* q = q_hat + ((size_t)b * Hq + (size_t)j * G + g) * D;
+          double s = 0.0;
+          for (int d = 0; d < D; ++d) s += (double)q[d] * bf16_to_f64(kr[d]);
+          if (g == 0) best = s;
+          else if (agg == ASO_AGG_SUM) best += s;
+          else if (s > best) best = s;
+        }
+        float f = (float)best;
+        f = f + 0.0f;                     /* -0 -> +0 */
+        scores[((size_t)b * Hkv + j) * stride + n] = f;
+      }
+    }
+  return 0;
+}
+
+typedef struct { float s; int32_t n; } aso_cand;
+
+/* order: score descending (NaN below everything), then index ascending */
+static int cand_cmp(const void* pa, const void* pb) {
+  const aso_cand* a = (const aso_cand*)pa;
+  const aso_cand* b = (const aso_cand*)pb;
+  int an = isnan(a->s), bn = isnan(b->s);
+  if (an != bn) return an ? 1 : -1;
+  if (!an) {
+    if (a->s > b->s) return -1;
+    if (a->s < b->s) return 1;
+  }
+  return (a->n > b->n) - (a->n < b->n);
+}
+static int int_cmp(const void* pa, const void* pb) {
+  int32_t a = *(const int32_t*)pa, b = *(const int32_t*)pb;
+  return (a > b) - (a < b);
+}
+
+/*
+ * Top-k per (b, kv head): full sort, keep min(C, N_b), emit ascending, pad -1.
+ *   scores fp32 [B][Hkv][stride]; sel_idx int32 [B][Hkv][C]; sel_cnt int32 [B][Hkv]
+ */
+int aso_topk_select(int B, int Hkv, int C, const float* scores, int64_t stride,
+                    const int32_t* ctx_lens, int32_t* sel_idx, int32_t* sel_cnt) {
+  if (C < 1) return -1;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < Hkv; ++j) {
+      int N = ctx_lens[b];
+      const float* s = scores + ((size_t)b * Hkv + j) * stride;
+      int32_t* out = sel_idx + ((size_t)b * Hkv + j) * C;
+      aso_cand* c = (aso_cand*)malloc(sizeof(aso_cand) * (N > 0 ? N : 1));
+      for (int n = 0; n < N; ++n) { c[n].s = s[n]; c[n].n = n; }
+      qsort(c, N, sizeof(aso_cand), cand_cmp);
+      int keep = N < C ? N : C;
+      for (int i = 0; i < keep; ++i) out[i] = c[i].n;
+      qsort(out, keep, sizeof(int32_t), int_cmp);
+      for (int i = keep; i < C; ++i) out[i] = -1;
+      sel_cnt[(size_t)b * Hkv + j] = keep;
+      free(c);
+    }
+  return 0;
+}
+
+/*
+ * Sparse decode attention with the real query over S = selected tokens plus
+ * the dense tail [sel_ctx_lens[b], ctx_lens[b]) (tail empty when sel_ctx_lens
+ * is NULL).
+ *   q bf16 [B][Hq][D]; out bf16 [B][Hq][D]; lse nullable fp32 [B][Hq] (natural log)
+ *   Empty S gives out = 0 and lse = -inf.
+ */
+int aso_sparse_decode_attn(int B, int Hq, int Hkv, int D, int P, int C, const uint16_t* k_pool,
+                           const uint16_t* v_pool, const int32_t* block_table, int max_pages,
+                           const int32_t* ctx_lens, const uint16_t* q, const int32_t* sel_idx,
+                           const int32_t* sel_cnt, const int32_t* sel_ctx_lens, double sm_scale,
+                           uint16_t* out, float* lse) {
+  if (Hkv <= 0 || Hq % Hkv != 0) return -1;
+  int G = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < Hq; ++h) {
+      int j = h / G;
+      int N = ctx_lens[b];
+      int cnt = sel_cnt[(size_t)b * Hkv + j];
+      int tail0 = sel_ctx_lens ? sel_ctx_lens[b] : N;
+      if (tail0 > N) tail0 = N;
+      if (tail0 < 0) tail0 = 0;
+      int L = cnt + (N - tail0);
+      uint16_t* o = out + ((size_t)b * Hq + h) * D;
+      if (L <= 0) {
+        for (int d = 0; d < D; ++d) o[d] = 0;
+        if (lse) lse[(size_t)b * Hq + h] = -INFINITY;
+        continue;
+      }
+      int32_t* toks = (int32_t*)malloc(sizeof(int32_t) * L);
+      double* logit = (double*)malloc(sizeof(double) * L);
+      double* acc = (double*)calloc(D, sizeof(double));
+      for (int i = 0; i < cnt; ++i) toks[i] = sel_idx[((size_t)b * Hkv + j) * C + i];
+      for (int n = tail0; n < N; ++n) toks[cnt + (n - tail0)] = n;
+      const uint16_t* qr = q + ((size_t)b * Hq + h) * D;
+      double m = -INFINITY;
+      for (int i = 0; i < L; ++i) {
+        const uint16_t* kr = token_ptr(k_pool, block_table, max_pages, Hkv, P, D, b, j, toks[i]);
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s += bf16_to_f64(qr[d]) * bf16_to_f64(kr[d]);
+        logit[i] = s * sm_scale;
+        if (logit[i] > m) m = logit[i];
+      }
+      double z = 0.0;
+      for (int i = 0; i < L; ++i) {
+        double p = exp(logit[i] - m);
+        z += p;
+        const uint16_t* vr = token_ptr(v_pool, block_table, max_pages, Hkv, P, D, b, j, toks[i]);
+        for (int d = 0; d < D; ++d) acc[d] += p * bf16_to_f64(vr[d]);
+      }
+      for (int d = 0; d < D; ++d) o[d] = f64_to_bf16(acc[d] / z);
+      if (lse) lse[(size_t)b * Hq + h] = (float)(m + log(z));
+      free(toks); free(logit); free(acc);
+    }
+  return 0;
+}
+
+/* exposed for tests of the rounding helper */
+uint16_t aso_f64_to_bf16(double d) { return f64_to_bf16(d); }
