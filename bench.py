@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-selection hot path on one MI355X.
+
+A "step" is one decode step of the workload: for every layer, selection (predict -> score ->
+top-k) for the NEXT step on its own HIP stream, overlapped with sparse decode attention of the
+current step (over the selection made one step earlier) on another stream; event hand-off per
+layer.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: metric = select + sparse-attention microseconds per layer-step (lower is
+better), plus the K-scoring kernel's achieved HBM GB/s against the 8 TB/s peak ("roofline"), the
+serial (single-stream) time, and the CPU oracle timed on a bounded sample ("cpu_baseline").
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", help="c1..c5 (BASELINE configs[0..4]); default c3 = Qwen3-8B shape, "
+                    "batch 32, context 32768, budget 2048, 36 layers")
+    ap.add_argument("--layers", type=int, default=0, help="resident layers (0 = the workload's own count)")
+    ap.add_argument("--budget", type=int, default=0)
+    ap.add_argument("--score-variant", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-seqs", type=int, default=4)
+    ap.add_argument("--serial-only", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; nothing is split across GPUs, so --gpus must be 1 "
+              f"(got {a.gpus}).", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2510_07486_amd import api, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    api.lib()                                       # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+
+    w = wl.CONFIGS[a.workload]
+    if a.budget:
+        w = wl.scaled(w, budget=a.budget)
+    n_layers = a.layers or w.layers
+    # shrink the resident set if HBM cannot hold every layer (each layer is identical work)
+    free, total = torch.cuda.mem_get_info()
+    ctx_lens_cpu = wl.draw_ctx_lens(w)
+    bt_cpu, num_pages = wl.make_page_table(w, ctx_lens_cpu)
+    per_layer = 2 * num_pages * w.n_kv_heads * wl.PAGE * wl.HEAD_DIM * 2
+    fit = max(1, int((free - (6 << 30)) // per_layer))
+    resident = min(n_layers, fit)
+
+    t0 = time.time()
+    layers = []
+    for l in range(resident):
+        k, v = wl.make_kv(w, num_pages, dev, l)
+        qw, qc, qr = wl.make_queries(w, dev, l)
+        layers.append(dict(k=k, v=v, qw=qw, qc=qc, qr=qr))
+    bt = bt_cpu.to(dev)
+    ctx_lens = ctx_lens_cpu.to(dev)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    eps = float(np.float32(1e-2))
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1], ridge_eps=eps,
+                        sm_scale=float(np.float32(1 / math.sqrt(128))))
+    ctx_sel, ctx_att = api.Context(p), api.Context(p)
+    if a.score_variant >= 0:
+        ctx_sel.set_score_variant(a.score_variant)
+    kvs = [api.kv_view(L["k"], L["v"], bt, ctx_lens) for L in layers]
+    B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
+    stride = bt.shape[1] * wl.PAGE
+    q_hat = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+    scores = torch.empty((B, Hkv, stride), dtype=torch.float32, device=dev)
+    # double-buffered selections: step t attends over sel[t % 2], selection writes sel[(t+1) % 2]
+    sel = [[(torch.empty((B, Hkv, C), dtype=torch.int32, device=dev),
+             torch.empty((B, Hkv), dtype=torch.int32, device=dev)) for _ in range(n_layers)] for _ in range(2)]
+    out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
+    s_sel, s_att = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def select(l, dst, stream, ev_pair=None):
+        """The three launches of as_select_step, issued separately so the scoring kernel can be bracketed
+        by events on its own stream."""
+        L = layers[l % resident]
+        kv = kvs[l % resident]
+        api.as_predict_query(ctx_sel, p, L["qw"], L["qc"], q_hat, stream=stream)
+        if ev_pair is not None:
+            ev_pair[0].record(stream)
+        api.as_score_keys(ctx_sel, p, kv, q_hat, scores, stream=stream)
+        if ev_pair is not None:
+            ev_pair[1].record(stream)
+        api.as_topk_select(ctx_sel, p, scores, ctx_lens, dst[0], dst[1], stream=stream)
+
+    def attend(l, src, stream):
+        L = layers[l % resident]
+        api.as_sparse_decode_attn(ctx_att, p, kvs[l % resident], L["qr"], src[0], src[1], out=out, stream=stream,
+                                  want_lse=False)
+
+    # prime both selection buffers
+    for t in range(2):
+        for l in range(n_layers):
+            select(l, sel[t][l], s_sel)
+    torch.cuda.synchronize()
+
+    def step_overlapped(t, score_events=None):
+        cur, nxt = sel[t % 2], sel[(t + 1) % 2]
+        for l in range(n_layers):
+            ev = torch.cuda.Event()
+            ev.record(s_att)                       # layer l's step-t query/key/value exist from here on
+            s_sel.wait_event(ev)
+            pair = None
+            if score_events is not None:
+                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                score_events.append(pair)
+            select(l, nxt[l], s_sel, pair)
+            attend(l, cur[l], s_att)
+        done = torch.cuda.Event()
+        done.record(s_sel)
+        s_att.wait_event(done)                     # the next step's attention needs every new selection
+
+    def step_serial(t, score_events=None):
+        cur, nxt = sel[t % 2], sel[(t + 1) % 2]
+        for l in range(n_layers):
+            pair = None
+            if score_events is not None:
+                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                score_events.append(pair)
+            select(l, nxt[l], s_att, pair)
+            attend(l, cur[l], s_att)
+
+    def timed(step_fn):
+        for t in range(a.warmup):
+            step_fn(t)
+        torch.cuda.synchronize()
+        evs = []
+        t_start = time.perf_counter()
+        for t in range(a.steps):
+            step_fn(a.warmup + t, evs)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_start
+        score_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+        return dt, score_ms
+
+    dt_serial, score_ms_serial = timed(step_serial)
+    if a.serial_only:
+        dt_ovl, score_ms_ovl = dt_serial, score_ms_serial
+    else:
+        dt_ovl, score_ms_ovl = timed(step_overlapped)
+
+    ms_step = dt_ovl / a.steps * 1e3
+    us_layer = ms_step * 1e3 / n_layers
+    us_layer_serial = dt_serial / a.steps * 1e6 / n_layers
+    tokens = int(ctx_lens_cpu.sum())
+    k_bytes = tokens * Hkv * 256                                   # algorithmic bytes of one scoring launch
+    kv_gather = int(torch.clamp(ctx_lens_cpu, max=C).sum()) * Hkv * 512
+    score_ms = float(np.mean(score_ms_ovl))
+    score_ms_alone = float(np.mean(score_ms_serial))
+    achieved = k_bytes / (score_ms * 1e-3) / 1e9
+    step_roofline_us = (k_bytes + kv_gather) / (HBM_PEAK_GBS * 1e9) * 1e6
+
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tf):
+        try:
+            traffic = json.load(open(tf)).get(a.workload, {}).get("score_keys_hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    res = {
+        "metric": "select+sparse-attn us per layer-step",
+        "value": round(us_layer, 2), "unit": "us/layer-step",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: Qwen3-8B attention shape" if a.workload in ("c2", "c3", "c5") else a.workload,
+                   "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128, "context": w.ctx,
+                   "window": w.window, "budget": C, "page_size": 16, "layers_per_step": n_layers,
+                   "layers_resident": resident, "streams": 1 if a.serial_only else 2},
+        "serial_us_per_layer_step": round(us_layer_serial, 2),
+        "step_roofline_us": round(step_roofline_us, 2),
+        "step_roofline_frac": round(step_roofline_us / us_layer, 4),
+        "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
+        "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+        "score_keys_gbs_serial": round(k_bytes / (score_ms_alone * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "score_keys", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4)},
+        "input_gen_s": round(gen_s, 1),
+    }
+
+    if not a.no_cpu_baseline:
+        import oracle
+        nthreads = oracle.set_threads(0)
+        ns = min(a.cpu_sample_seqs, B)
+        L0 = layers[0]
+        inp = wl.Inputs(w, L0["k"], L0["v"], bt, ctx_lens, L0["qw"], L0["qc"], L0["qr"])
+        subs = [wl.extract_sequence(inp, b) for b in range(ns)]
+        t1 = time.perf_counter()
+        for s in subs:
+            q_h, sc, ridx, rcnt = oracle.select_step(s.k_pool, s.block_table, s.ctx_lens, s.q_win, s.q_cur, C, eps)
+            oracle.sparse_decode_attn(s.k_pool, s.v_pool, s.block_table, s.ctx_lens, s.q_real, ridx, rcnt,
+                                      float(np.float32(1 / math.sqrt(128))))
+        cpu_s = time.perf_counter() - t1
+        res["cpu_baseline"] = {"value": round(cpu_s / ns * B * 1e6, 1), "unit": "us/layer-step", "cores": nthreads,
+                               "kind": "oracle", "sample": f"{ns} of {B} sequences of one layer (full context), "
+                               f"{cpu_s:.2f} s measured, scaled by {B}/{ns}"}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,141 @@
+/*
+ * asyncspade.h -- C ABI of the MI355X (gfx950) KV-selection hot path of AsyncSpade.
+ *
+ * One decode step of token-level, query-aware KV-cache selection:
+ *   predict  the next-step query from a sliding window of recent queries
+ *            (Sec. 4.2: Eq. 2-3 ridge regression + softmax, Eq. 4 single-token shift,
+ *            Eq. 5 mean over window sizes; Appendix C Alg. 1 steps 1-6),
+ *   score    every cached key against the predicted query (Alg. 1 step 7; shapes of
+ *            Sec. 4.3 "Batched Matmul"), aggregated over each GQA group,
+ *   top-k    keep a per-KV-head budget of the highest-scoring tokens (Sec. 4.3,
+ *            cache-rank item (2)),
+ *   attend   decode attention with the REAL query over only the selected tokens
+ *            (Sec. 4.1; Appendix B counts 4*q*h*C flops for exactly this).
+ *
+ * Conventions
+ *   - Every pointer except as_ctx* / as_params* / as_kv_view* is a DEVICE pointer owned
+ *     by the caller.  The library allocates device memory only in as_create (the ctx
+ *     workspace), frees it in as_destroy, and never synchronises the host: all work is
+ *     enqueued on the hipStream_t passed (as void*; NULL = the default stream).
+ *   - One ctx per concurrently used stream (the workspace is per ctx).
+ *   - bf16 = raw 16-bit brain-float bit patterns.  head_dim must be 128 and page_size 16.
+ *   - KV layout: token n of sequence b lives in page block_table[b][n / 16], slot n % 16;
+ *     element offset ((page * n_kv_heads + j) * 16 + slot) * 128 in the pool (64-bit).
+ *   - Query head h belongs to KV head h / G with G = n_q_heads / n_kv_heads.
+ *   - Return codes only; nothing throws or aborts across this boundary.  Arguments are
+ *     validated on the host before any launch: AS_ERR_INVALID_ARG for null pointers,
+ *     non-positive sizes, n_q_heads % n_kv_heads != 0, ridge_eps <= 0;
+ *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 16,
+ *     budget > 65536; AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
+ *     Contents of device arrays (page ids in range, indices unique and in range) are
+ *     the caller's contract.
+ */
+#ifndef ASYNCSPADE_H
+#define ASYNCSPADE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct as_ctx as_ctx; /* opaque: device id + scratch workspace */
+
+typedef enum {
+  AS_OK = 0,
+  AS_ERR_INVALID_ARG = 1,
+  AS_ERR_UNSUPPORTED = 2,
+  AS_ERR_WORKSPACE = 3,
+  AS_ERR_HIP = 4
+} as_status;
+
+typedef enum { AS_AGG_MAX = 0, AS_AGG_SUM = 1 } as_agg;
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128                          */
+  int32_t page_size;                              /* must be 16                                    */
+  int32_t window;                                 /* W >= 1 predecessors in q_win (<= 64)          */
+  int32_t budget;                                 /* C >= 1 tokens kept per (sequence, kv head)    */
+  int32_t max_pages_per_seq;                      /* row stride of block_table; bounds every ctx   */
+  float ridge_eps;                                /* eps > 0 added to the Gram diagonal (absolute) */
+  float softmax_beta;                             /* weights = softmax(beta * omega); +1 default,  */
+                                                  /* -1 is the sign printed in Alg. 1 step 3       */
+  float sm_scale;                                 /* attention logit scale, e.g. 1/sqrt(128)       */
+  int32_t agg;                                    /* as_agg: group aggregation of the scores       */
+} as_params;
+
+typedef struct {            /* caller-owned device memory, never freed by the library */
+  const void* k_pool;       /* bf16 [num_pages][n_kv_heads][16][128]                  */
+  const void* v_pool;       /* same shape (may be NULL for calls that only score)     */
+  const int32_t* block_table; /* [batch][max_pages_per_seq] physical page ids         */
+  const int32_t* ctx_lens;  /* [batch] tokens currently cached, <= 16*max_pages_per_seq */
+  int64_t num_pages;
+} as_kv_view;
+
+/* Bytes of ctx workspace that every call with these parameters fits in
+ * (as_select_step's q_hat + score rows, and the attention split partials). */
+size_t as_workspace_bytes(const as_params* p);
+
+/* Creates a ctx on `device` with a workspace of `workspace_bytes` (hipMalloc).  */
+as_status as_create(as_ctx** out, int device, size_t workspace_bytes);
+as_status as_destroy(as_ctx* ctx);
+const char* as_status_str(as_status s);
+
+/*
+ * Query predictor (Sec. 4.2, Eq. 2-5).  For every (b, h): for each window size k = 1..W
+ * solve (R_k R_k^T + eps I) omega = R_k Q_t over the k newest predecessors, take
+ * w = softmax(beta * omega), apply w to the window shifted by one token (Q_t, Q_{t-1}, ...),
+ * and average the W candidates.  fp64 inside, fp32 out.
+ *   q_win  bf16 [B][Hq][W][128], oldest first (Q_{t-W} .. Q_{t-1})
+ *   q_cur  bf16 [B][Hq][128]     (Q_t: regression target and newest shifted element)
+ *   q_hat  fp32 [B][Hq][128]     out
+ */
+as_status as_predict_query(as_ctx* ctx, const as_params* p, const void* q_win, const void* q_cur,
+                           float* q_hat, void* stream);
+
+/*
+ * Criticality scores (Alg. 1 step 7 with the (bs, N_kv, N_q/N_kv, D_h) x (bs, N_kv, N_t, D_h)
+ * shapes of Sec. 4.3):  scores[b][j][n] = agg_g <q_hat[b][j*G+g], K[b][j][n]> for n < ctx_lens[b],
+ * fp32, with -0 written as +0.  Entries n >= ctx_lens[b] are left untouched.
+ *   scores fp32 [B][Hkv][score_stride], score_stride >= 16 * max_pages_per_seq
+ */
+as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
+                        float* scores, int64_t score_stride, void* stream);
+
+/*
+ * Top-k (Sec. 4.3 item (2)).  Per (b, j): the min(C, ctx_lens[b]) tokens with the largest
+ * score; equal scores resolve to the lowest index; NaN ranks below -inf; -0 == +0.
+ *   sel_idx int32 [B][Hkv][C]  ascending token indices, padded with -1
+ *   sel_cnt int32 [B][Hkv]
+ */
+as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, int64_t score_stride,
+                         const int32_t* ctx_lens, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
+
+/*
+ * Sparse decode attention (Sec. 4.1).  For query head h (KV head j = h / G), over
+ * S = sel_idx[b][j][0 .. sel_cnt) plus the dense tail [sel_ctx_lens[b], ctx_lens[b]):
+ *   out = sum_{n in S} softmax_n(sm_scale * <q, K_n>) V_n      (fp32 inside, bf16 out)
+ *   lse = log sum_{n in S} exp(sm_scale * <q, K_n>)            (natural log)
+ * The tail lets a step attend to tokens appended after its selection was made
+ * (selection for step t+1 happens at step t); pass NULL for no tail.
+ * Empty S gives out = 0, lse = -inf.
+ *   q    bf16 [B][Hq][128];  out bf16 [B][Hq][128];  lse nullable fp32 [B][Hq]
+ */
+as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q,
+                                const int32_t* sel_idx, const int32_t* sel_cnt,
+                                const int32_t* sel_ctx_lens, void* out, float* lse, void* stream);
+
+/*
+ * Fused selection for one layer-step: predict -> score -> top-k enqueued back to back on
+ * `stream`, with q_hat and the score rows kept in the ctx workspace.  This is the work
+ * the paper's Cache Rank does per layer (Sec. 4.1, Sec. 4.3); run it on its own stream
+ * to overlap it with another layer's attention.
+ */
+as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win,
+                         const void* q_cur, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASYNCSPADE_H */

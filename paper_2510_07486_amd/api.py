@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libasyncspade.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI (include/asyncspade.h);
+torch is used for device memory and streams.  There is no CPU fallback: if the library is
+missing or a call fails this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libasyncspade.so")
+_lib = None
+
+AS_AGG_MAX, AS_AGG_SUM = 0, 1
+EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
+           "as_topk_select", "as_sparse_decode_attn", "as_select_step"]
+
+
+class AsParams(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_size", C.c_int32), ("window", C.c_int32), ("budget", C.c_int32),
+                ("max_pages_per_seq", C.c_int32), ("ridge_eps", C.c_float), ("softmax_beta", C.c_float),
+                ("sm_scale", C.c_float), ("agg", C.c_int32)]
+
+
+class AsKvView(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_table", C.c_void_p),
+                ("ctx_lens", C.c_void_p), ("num_pages", C.c_int64)]
+
+
+class AsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().as_status_str(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (status {code})")
+
+
+def lib():
+    """Loads the built library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2510_07486_amd.build` first")
+        L = C.CDLL(LIB_PATH)
+        L.as_workspace_bytes.restype = C.c_size_t
+        L.as_workspace_bytes.argtypes = [C.POINTER(AsParams)]
+        L.as_create.restype = C.c_int
+        L.as_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_size_t]
+        L.as_destroy.restype = C.c_int
+        L.as_destroy.argtypes = [C.c_void_p]
+        L.as_status_str.restype = C.c_char_p
+        L.as_status_str.argtypes = [C.c_int]
+        vp = C.c_void_p
+        PP, KP = C.POINTER(AsParams), C.POINTER(AsKvView)
+        L.as_predict_query.restype = C.c_int
+        L.as_predict_query.argtypes = [vp, PP, vp, vp, vp, vp]
+        L.as_score_keys.restype = C.c_int
+        L.as_score_keys.argtypes = [vp, PP, KP, vp, vp, C.c_int64, vp]
+        L.as_topk_select.restype = C.c_int
+        L.as_topk_select.argtypes = [vp, PP, vp, C.c_int64, vp, vp, vp, vp]
+        L.as_sparse_decode_attn.restype = C.c_int
+        L.as_sparse_decode_attn.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp, vp, vp]
+        L.as_select_step.restype = C.c_int
+        L.as_select_step.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp]
+        L.as_debug_set_score_variant.restype = C.c_int
+        L.as_debug_set_score_variant.argtypes = [vp, C.c_int]
+        _lib = L
+    return _lib
+
+
+def make_params(batch, n_q_heads, n_kv_heads, window, budget, max_pages_per_seq, ridge_eps=1e-2, softmax_beta=1.0,
+                sm_scale=None, agg=AS_AGG_MAX, head_dim=128, page_size=16) -> AsParams:
+    if sm_scale is None:
+        sm_scale = 1.0 / math.sqrt(head_dim)
+    return AsParams(batch, n_q_heads, n_kv_heads, head_dim, page_size, window, budget, max_pages_per_seq,
+                    ridge_eps, softmax_beta, sm_scale, agg)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def kv_view(k_pool, v_pool, block_table, ctx_lens) -> AsKvView:
+    assert k_pool.dtype == torch.bfloat16 and block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    return AsKvView(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(ctx_lens), k_pool.shape[0])
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise AsError(code, where)
+
+
+def as_workspace_bytes(p: AsParams) -> int:
+    return int(lib().as_workspace_bytes(C.byref(p)))
+
+
+class Context:
+    """Owns one as_ctx (device workspace).  One per concurrently used stream."""
+
+    def __init__(self, p: AsParams, device: int = 0, workspace_bytes: Optional[int] = None):
+        self.handle = C.c_void_p()
+        nbytes = as_workspace_bytes(p) if workspace_bytes is None else workspace_bytes
+        _check(lib().as_create(C.byref(self.handle), device, nbytes), "as_create")
+        self.workspace_bytes = nbytes
+
+    def close(self):
+        if self.handle:
+            _check(lib().as_destroy(self.handle), "as_destroy")
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_score_variant(self, v: int):
+        _check(lib().as_debug_set_score_variant(self.handle, v), "as_debug_set_score_variant")
+
+
+def as_predict_query(ctx: Context, p: AsParams, q_win, q_cur, q_hat=None, stream=None):
+    if q_hat is None:
+        q_hat = torch.empty((p.batch, p.n_q_heads, p.head_dim), dtype=torch.float32, device=q_win.device)
+    _check(lib().as_predict_query(ctx.handle, C.byref(p), _ptr(q_win), _ptr(q_cur), _ptr(q_hat), _stream(stream)),
+           "as_predict_query")
+    return q_hat
+
+
+def as_score_keys(ctx: Context, p: AsParams, kv: AsKvView, q_hat, scores=None, stream=None, fill=None):
+    if scores is None:
+        stride = p.max_pages_per_seq * p.page_size
+        scores = torch.empty((p.batch, p.n_kv_heads, stride), dtype=torch.float32, device=q_hat.device)
+        if fill is not None:
+            scores.fill_(fill)
+    _check(lib().as_score_keys(ctx.handle, C.byref(p), C.byref(kv), _ptr(q_hat), _ptr(scores), scores.shape[2],
+                               _stream(stream)), "as_score_keys")
+    return scores
+
+
+def as_topk_select(ctx: Context, p: AsParams, scores, ctx_lens, sel_idx=None, sel_cnt=None, stream=None):
+    if sel_idx is None:
+        sel_idx = torch.empty((p.batch, p.n_kv_heads, p.budget), dtype=torch.int32, device=scores.device)
+    if sel_cnt is None:
+        sel_cnt = torch.empty((p.batch, p.n_kv_heads), dtype=torch.int32, device=scores.device)
+    _check(lib().as_topk_select(ctx.handle, C.byref(p), _ptr(scores), scores.shape[2], _ptr(ctx_lens), _ptr(sel_idx),
+                                _ptr(sel_cnt), _stream(stream)), "as_topk_select")
+    return sel_idx, sel_cnt
+
+
+def as_sparse_decode_attn(ctx: Context, p: AsParams, kv: AsKvView, q, sel_idx, sel_cnt, sel_ctx_lens=None, out=None,
+                          lse=None, stream=None, want_lse=True):
+    if out is None:
+        out = torch.empty((p.batch, p.n_q_heads, p.head_dim), dtype=torch.bfloat16, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((p.batch, p.n_q_heads), dtype=torch.float32, device=q.device)
+    _check(lib().as_sparse_decode_attn(ctx.handle, C.byref(p), C.byref(kv), _ptr(q), _ptr(sel_idx), _ptr(sel_cnt),
+                                       _ptr(sel_ctx_lens), _ptr(out), _ptr(lse), _stream(stream)),
+           "as_sparse_decode_attn")
+    return out, lse
+
+
+def as_select_step(ctx: Context, p: AsParams, kv: AsKvView, q_win, q_cur, sel_idx=None, sel_cnt=None, stream=None):
+    if sel_idx is None:
+        sel_idx = torch.empty((p.batch, p.n_kv_heads, p.budget), dtype=torch.int32, device=q_win.device)
+    if sel_cnt is None:
+        sel_cnt = torch.empty((p.batch, p.n_kv_heads), dtype=torch.int32, device=q_win.device)
+    _check(lib().as_select_step(ctx.handle, C.byref(p), C.byref(kv), _ptr(q_win), _ptr(q_cur), _ptr(sel_idx),
+                                _ptr(sel_cnt), _stream(stream)), "as_select_step")
+    return sel_idx, sel_cnt

@@ -1,0 +1,173 @@
+// C ABI of the KV-selection hot path: argument validation, workspace carving, launches.
+// No device allocation outside as_create / as_destroy and no host synchronisation.
+#include <new>
+
+#include "common.hpp"
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct ws_layout {
+  size_t q_hat, scores, attn, total;
+  int64_t score_stride;
+};
+
+ws_layout layout_of(const as_params* p) {
+  ws_layout l;
+  l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
+  l.q_hat = 0;
+  size_t qh = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
+  l.scores = l.q_hat + qh;
+  size_t sc = align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
+  l.attn = l.scores + sc;
+  l.total = l.attn + align_up(asx::attn_workspace_bytes(p));
+  return l;
+}
+
+as_status check_params(const as_params* p) {
+  if (!p) return AS_ERR_INVALID_ARG;
+  if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->head_dim <= 0 || p->page_size <= 0 ||
+      p->window < 1 || p->budget < 1 || p->max_pages_per_seq < 0)
+    return AS_ERR_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return AS_ERR_INVALID_ARG;
+  if (!(p->ridge_eps > 0.f)) return AS_ERR_INVALID_ARG;
+  if (p->agg != AS_AGG_MAX && p->agg != AS_AGG_SUM) return AS_ERR_INVALID_ARG;
+  if (p->head_dim != AS_HEAD_DIM || p->page_size != AS_PAGE) return AS_ERR_UNSUPPORTED;
+  if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
+  if (p->n_q_heads / p->n_kv_heads > AS_MAX_GROUP) return AS_ERR_UNSUPPORTED;
+  if (p->batch > 65535 || p->n_kv_heads > 65535) return AS_ERR_UNSUPPORTED;
+  if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 30) return AS_ERR_UNSUPPORTED;
+  return AS_OK;
+}
+
+as_status check_kv(const as_kv_view* kv, bool need_v) {
+  if (!kv || !kv->k_pool || !kv->block_table || !kv->ctx_lens) return AS_ERR_INVALID_ARG;
+  if (need_v && !kv->v_pool) return AS_ERR_INVALID_ARG;
+  if (kv->num_pages < 0) return AS_ERR_INVALID_ARG;
+  return AS_OK;
+}
+
+inline as_status hip_status(hipError_t e) { return e == hipSuccess ? AS_OK : AS_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t as_workspace_bytes(const as_params* p) {
+  if (check_params(p) != AS_OK) return 0;
+  return layout_of(p).total;
+}
+
+as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
+  if (!out) return AS_ERR_INVALID_ARG;
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return AS_ERR_HIP;
+  if (hipSetDevice(device) != hipSuccess) return AS_ERR_HIP;
+  as_ctx* c = new (std::nothrow) as_ctx();
+  if (!c) return AS_ERR_HIP;
+  c->device = device;
+  c->ws = nullptr;
+  c->ws_bytes = workspace_bytes;
+  c->score_variant = 0;
+  if (workspace_bytes > 0 && hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
+    delete c;
+    return AS_ERR_HIP;
+  }
+  *out = c;
+  return AS_OK;
+}
+
+as_status as_destroy(as_ctx* ctx) {
+  if (!ctx) return AS_ERR_INVALID_ARG;
+  hipError_t e = hipSuccess;
+  if (ctx->ws) e = hipFree(ctx->ws);
+  delete ctx;
+  return hip_status(e);
+}
+
+const char* as_status_str(as_status s) {
+  switch (s) {
+    case AS_OK: return "ok";
+    case AS_ERR_INVALID_ARG: return "invalid argument";
+    case AS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case AS_ERR_WORKSPACE: return "ctx workspace too small";
+    case AS_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+as_status as_predict_query(as_ctx* ctx, const as_params* p, const void* q_win, const void* q_cur, float* q_hat,
+                           void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !q_win || !q_cur || !q_hat) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
+                                        q_hat, static_cast<hipStream_t>(stream)));
+}
+
+as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
+                        int64_t score_stride, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, false)) != AS_OK) return st;
+  if (!ctx || !q_hat || !scores) return AS_ERR_INVALID_ARG;
+  if (score_stride < (int64_t)p->max_pages_per_seq * AS_PAGE) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, score_stride,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, int64_t score_stride,
+                         const int32_t* ctx_lens, int32_t* sel_idx, int32_t* sel_cnt, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !scores || !ctx_lens || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  if (score_stride < (int64_t)p->max_pages_per_seq * AS_PAGE) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_topk(p, scores, score_stride, ctx_lens, sel_idx, sel_cnt,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q,
+                                const int32_t* sel_idx, const int32_t* sel_cnt, const int32_t* sel_ctx_lens,
+                                void* out, float* lse, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, true)) != AS_OK) return st;
+  if (!ctx || !q || !sel_idx || !sel_cnt || !out) return AS_ERR_INVALID_ARG;
+  const ws_layout l = layout_of(p);
+  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), sel_idx, sel_cnt, sel_ctx_lens,
+                                     static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
+                         int32_t* sel_idx, int32_t* sel_cnt, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, false)) != AS_OK) return st;
+  if (!ctx || !q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  const ws_layout l = layout_of(p);
+  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(ctx->ws);
+  float* q_hat = reinterpret_cast<float*>(ws + l.q_hat);
+  float* scores = reinterpret_cast<float*>(ws + l.scores);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
+                                     q_hat, s);
+  if (e != hipSuccess) return AS_ERR_HIP;
+  e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, l.score_stride, s);
+  if (e != hipSuccess) return AS_ERR_HIP;
+  e = asx::launch_topk(p, scores, l.score_stride, kv->ctx_lens, sel_idx, sel_cnt, s);
+  return hip_status(e);
+}
+
+// Development knob (not part of the documented ABI): picks the key-scoring kernel variant.
+as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
+  if (!ctx) return AS_ERR_INVALID_ARG;
+  ctx->score_variant = variant;
+  return AS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Internal declarations shared by the gfx950 kernels of the KV-selection hot path.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "asyncspade.h"
+
+#define AS_HEAD_DIM 128
+#define AS_PAGE 16
+#define AS_MAX_WINDOW 64
+#define AS_MAX_GROUP 16
+#define AS_MAX_BUDGET 65536
+#define AS_ATTN_CHUNK 128 /* tokens per attention split */
+
+struct as_ctx {
+  int device;
+  void* ws;
+  size_t ws_bytes;
+  int score_variant; /* which key-scoring kernel as_score_keys launches */
+};
+
+namespace asx {
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t lo16) { return __uint_as_float(lo16 << 16); }
+// low / high bf16 of a packed dword -> fp32
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// element offset of token `slot` of (page, kv head j) in a [pages][Hkv][16][128] pool
+__device__ __forceinline__ int64_t chunk_offset(int32_t page, int Hkv, int j) {
+  return ((int64_t)page * Hkv + j) * (int64_t)(AS_PAGE * AS_HEAD_DIM);
+}
+
+// ---- launchers (host) -------------------------------------------------------------
+hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
+                          hipStream_t s);
+hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
+                        int64_t stride, hipStream_t s);
+hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,
+                       int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
+// partial buffers live in the ctx workspace
+size_t attn_workspace_bytes(const as_params* p);
+hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
+                       const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
+                       hipStream_t s);
+
+}  // namespace asx

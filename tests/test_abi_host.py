@@ -1,0 +1,48 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_07486_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    hdr = open(os.path.join(ROOT, "include", "asyncspade.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    return sorted(set(re.findall(r"\b(as_[a-z_]+)\s*\(", hdr)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = api.lib()
+    names = declared_symbols()
+    assert set(api.EXPORTS) == set(names)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_workspace_bytes_and_param_validation():
+    p = api.make_params(32, 32, 8, 16, 2048, 2048)
+    n = api.as_workspace_bytes(p)
+    # q_hat + score rows + attention partials
+    assert n >= 32 * 32 * 128 * 4 + 32 * 8 * 32768 * 4 + 32 * 32 * 17 * 130 * 4
+    bad = api.make_params(1, 6, 4, 16, 64, 8)            # 6 % 4 != 0
+    assert api.as_workspace_bytes(bad) == 0
+    L = api.lib()
+    dummy = C.c_void_p(0)
+    for kw, code in [(dict(n_q_heads=6, n_kv_heads=4), 1), (dict(ridge_eps=0.0), 1), (dict(window=0), 1),
+                     (dict(budget=0), 1), (dict(head_dim=64), 2), (dict(page_size=32), 2), (dict(window=65), 2),
+                     (dict(budget=65537), 2), (dict(n_q_heads=32, n_kv_heads=1), 2), (dict(agg=7), 1)]:
+        args = dict(batch=1, n_q_heads=8, n_kv_heads=2, window=4, budget=16, max_pages_per_seq=4)
+        args.update(kw)
+        q = api.make_params(**args)
+        assert L.as_predict_query(dummy, C.byref(q), dummy, dummy, dummy, dummy) == code, kw
+    ok = api.make_params(1, 8, 2, 4, 16, 4)
+    # null ctx / null pointers are invalid arguments, reported without touching the device
+    assert L.as_predict_query(None, C.byref(ok), None, None, None, None) == 1
+    assert L.as_select_step(None, C.byref(ok), None, None, None, None, None, None) == 1
+    assert L.as_status_str(3).decode() == "ctx workspace too small"
