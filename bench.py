@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=4)
     ap.add_argument("--serial-only", action="store_true")
+    ap.add_argument("--unfused", action="store_true", help="score and top-k as separate kernels through HBM scores")
     return ap.parse_args()
 
 
@@ -99,17 +100,22 @@ def main():
     s_sel, s_att = torch.cuda.Stream(), torch.cuda.Stream()
 
     def select(l, dst, stream, ev_pair=None):
-        """The three launches of as_select_step, issued separately so the scoring kernel can be bracketed
-        by events on its own stream."""
+        """The two calls as_select_step makes (as_predict_query, as_score_topk), issued separately so that the
+        K-streaming part can be bracketed by events on its own stream."""
         L = layers[l % resident]
         kv = kvs[l % resident]
         api.as_predict_query(ctx_sel, p, L["qw"], L["qc"], q_hat, stream=stream)
         if ev_pair is not None:
             ev_pair[0].record(stream)
-        api.as_score_keys(ctx_sel, p, kv, q_hat, scores, stream=stream)
-        if ev_pair is not None:
-            ev_pair[1].record(stream)
-        api.as_topk_select(ctx_sel, p, scores, ctx_lens, dst[0], dst[1], stream=stream)
+        if a.unfused:
+            api.as_score_keys(ctx_sel, p, kv, q_hat, scores, stream=stream)
+            if ev_pair is not None:
+                ev_pair[1].record(stream)
+            api.as_topk_select(ctx_sel, p, scores, ctx_lens, dst[0], dst[1], stream=stream)
+        else:
+            api.as_score_topk(ctx_sel, p, kv, q_hat, dst[0], dst[1], stream=stream)
+            if ev_pair is not None:
+                ev_pair[1].record(stream)
 
     def attend(l, src, stream):
         L = layers[l % resident]
@@ -202,7 +208,7 @@ def main():
         "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
         "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "score_keys_gbs_serial": round(k_bytes / (score_ms_alone * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "score_keys", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "score_keys" if a.unfused else "score_topk (slice + merge kernels)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4)},
         "input_gen_s": round(gen_s, 1),

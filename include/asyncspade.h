@@ -127,8 +127,17 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
                                 const int32_t* sel_ctx_lens, void* out, float* lse, void* stream);
 
 /*
- * Fused selection for one layer-step: predict -> score -> top-k enqueued back to back on
- * `stream`, with q_hat and the score rows kept in the ctx workspace.  This is the work
+ * Scoring and top-k in one pass (Alg. 1 step 7 + Sec. 4.3 item (2)): same result as
+ * as_score_keys followed by as_topk_select, but the per-token scores never leave the chip
+ * (rows are scored in slices whose keys stay in LDS; only per-slice candidates, 8 B each,
+ * go through the ctx workspace).  This is the kernel pair as_select_step runs.
+ */
+as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
+                        int32_t* sel_idx, int32_t* sel_cnt, void* stream);
+
+/*
+ * Fused selection for one layer-step: as_predict_query then as_score_topk enqueued back to
+ * back on `stream`, with q_hat and the candidates kept in the ctx workspace.  This is the work
  * the paper's Cache Rank does per layer (Sec. 4.1, Sec. 4.3); run it on its own stream
  * to overlap it with another layer's attention.
  */

@@ -19,7 +19,7 @@ _lib = None
 
 AS_AGG_MAX, AS_AGG_SUM = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
-           "as_topk_select", "as_sparse_decode_attn", "as_select_step"]
+           "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step"]
 
 
 class AsParams(C.Structure):
@@ -66,10 +66,14 @@ def lib():
         L.as_topk_select.argtypes = [vp, PP, vp, C.c_int64, vp, vp, vp, vp]
         L.as_sparse_decode_attn.restype = C.c_int
         L.as_sparse_decode_attn.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp, vp, vp]
+        L.as_score_topk.restype = C.c_int
+        L.as_score_topk.argtypes = [vp, PP, KP, vp, vp, vp, vp]
         L.as_select_step.restype = C.c_int
         L.as_select_step.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp]
         L.as_debug_set_score_variant.restype = C.c_int
         L.as_debug_set_score_variant.argtypes = [vp, C.c_int]
+        L.as_debug_set_select_mode.restype = C.c_int
+        L.as_debug_set_select_mode.argtypes = [vp, C.c_int]
         _lib = L
     return _lib
 
@@ -132,6 +136,10 @@ class Context:
     def set_score_variant(self, v: int):
         _check(lib().as_debug_set_score_variant(self.handle, v), "as_debug_set_score_variant")
 
+    def set_select_mode(self, m: int):
+        """0 = as_select_step fuses scoring with top-k (default), 1 = separate kernels through HBM scores."""
+        _check(lib().as_debug_set_select_mode(self.handle, m), "as_debug_set_select_mode")
+
 
 def as_predict_query(ctx: Context, p: AsParams, q_win, q_cur, q_hat=None, stream=None):
     if q_hat is None:
@@ -172,6 +180,16 @@ def as_sparse_decode_attn(ctx: Context, p: AsParams, kv: AsKvView, q, sel_idx, s
                                        _ptr(sel_ctx_lens), _ptr(out), _ptr(lse), _stream(stream)),
            "as_sparse_decode_attn")
     return out, lse
+
+
+def as_score_topk(ctx: Context, p: AsParams, kv: AsKvView, q_hat, sel_idx=None, sel_cnt=None, stream=None):
+    if sel_idx is None:
+        sel_idx = torch.empty((p.batch, p.n_kv_heads, p.budget), dtype=torch.int32, device=q_hat.device)
+    if sel_cnt is None:
+        sel_cnt = torch.empty((p.batch, p.n_kv_heads), dtype=torch.int32, device=q_hat.device)
+    _check(lib().as_score_topk(ctx.handle, C.byref(p), C.byref(kv), _ptr(q_hat), _ptr(sel_idx), _ptr(sel_cnt),
+                               _stream(stream)), "as_score_topk")
+    return sel_idx, sel_cnt
 
 
 def as_select_step(ctx: Context, p: AsParams, kv: AsKvView, q_win, q_cur, sel_idx=None, sel_cnt=None, stream=None):

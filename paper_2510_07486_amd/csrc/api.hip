@@ -9,7 +9,7 @@ namespace {
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct ws_layout {
-  size_t q_hat, scores, attn, total;
+  size_t q_hat, scores, cand, attn, total;
   int64_t score_stride;
 };
 
@@ -20,7 +20,8 @@ ws_layout layout_of(const as_params* p) {
   size_t qh = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
   l.scores = l.q_hat + qh;
   size_t sc = align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
-  l.attn = l.scores + sc;
+  l.cand = l.scores + sc;
+  l.attn = l.cand + align_up(asx::select_workspace_bytes(p));
   l.total = l.attn + align_up(asx::attn_workspace_bytes(p));
   return l;
 }
@@ -37,7 +38,7 @@ as_status check_params(const as_params* p) {
   if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
   if (p->n_q_heads / p->n_kv_heads > AS_MAX_GROUP) return AS_ERR_UNSUPPORTED;
   if (p->batch > 65535 || p->n_kv_heads > 65535) return AS_ERR_UNSUPPORTED;
-  if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 30) return AS_ERR_UNSUPPORTED;
+  if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 26) return AS_ERR_UNSUPPORTED;
   return AS_OK;
 }
 
@@ -70,7 +71,8 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->device = device;
   c->ws = nullptr;
   c->ws_bytes = workspace_bytes;
-  c->score_variant = 0;
+  c->score_variant = 12;
+  c->select_mode = 0;
   if (workspace_bytes > 0 && hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
     delete c;
     return AS_ERR_HIP;
@@ -142,6 +144,18 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
                                      static_cast<hipStream_t>(stream)));
 }
 
+as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat, int32_t* sel_idx,
+                        int32_t* sel_cnt, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, false)) != AS_OK) return st;
+  if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  const ws_layout l = layout_of(p);
+  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  return hip_status(asx::launch_select_fused(p, kv, q_hat, static_cast<char*>(ctx->ws) + l.cand, sel_idx, sel_cnt,
+                                             static_cast<hipStream_t>(stream)));
+}
+
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
                          int32_t* sel_idx, int32_t* sel_cnt, void* stream) {
   as_status st = check_params(p);
@@ -157,16 +171,24 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
                                      q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
+  if (ctx->select_mode == 0)
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
   e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, l.score_stride, s);
   if (e != hipSuccess) return AS_ERR_HIP;
   e = asx::launch_topk(p, scores, l.score_stride, kv->ctx_lens, sel_idx, sel_cnt, s);
   return hip_status(e);
 }
 
-// Development knob (not part of the documented ABI): picks the key-scoring kernel variant.
+// Development knobs (not part of the documented ABI): pick the key-scoring kernel variant of
+// as_score_keys, and whether as_select_step fuses scoring with top-k (0) or not (1).
 as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
   if (!ctx) return AS_ERR_INVALID_ARG;
   ctx->score_variant = variant;
+  return AS_OK;
+}
+as_status as_debug_set_select_mode(as_ctx* ctx, int mode) {
+  if (!ctx) return AS_ERR_INVALID_ARG;
+  ctx->select_mode = mode;
   return AS_OK;
 }
 

@@ -17,6 +17,7 @@ struct as_ctx {
   void* ws;
   size_t ws_bytes;
   int score_variant; /* which key-scoring kernel as_score_keys launches */
+  int select_mode;   /* 0: fused score+top-k in as_select_step, 1: separate kernels via HBM scores */
 };
 
 namespace asx {
@@ -45,6 +46,12 @@ hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, c
                         int64_t stride, hipStream_t s);
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,
                        int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
+// fused scoring + top-k (select_fused.hip): rows are cut into slices of `slice_len` tokens
+struct select_plan { int slice_len, nslices, ccap; };
+select_plan plan_select(const as_params* p);
+size_t select_workspace_bytes(const as_params* p);
+hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
+                               int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // partial buffers live in the ctx workspace
 size_t attn_workspace_bytes(const as_params* p);
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,

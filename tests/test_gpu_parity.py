@@ -210,6 +210,44 @@ def end_to_end(w, eps=1e-2, beta=1.0, agg=0, streams=False):
     return swaps, (gidx, gcnt, out)
 
 
+def fused_vs_separate(w):
+    """as_select_step's fused scoring + top-k against the separate kernels: identical index sets."""
+    cpu = wl.make_inputs(w)
+    dev = to_dev(cpu)
+    p = params_for(cpu)
+    ctx = api.Context(p)
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    a_idx, a_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    ctx.set_select_mode(1)
+    b_idx, b_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    assert torch.equal(a_cnt, b_cnt)
+    assert torch.equal(a_idx, b_idx)
+    # stage-isolated: the fused kernel fed the oracle's q_hat reproduces the oracle's selection of its own scores
+    q_hat = oracle.predict_query(cpu.q_win, cpu.q_cur, f32(1e-2))
+    sc = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q_hat, w.n_kv_heads)
+    ridx, rcnt = oracle.topk_select(sc, cpu.ctx_lens, w.budget)
+    c_idx, c_cnt = api.as_score_topk(ctx, p, kv, q_hat.cuda())
+    swaps = compare_selection(c_idx, c_cnt, ridx, rcnt, sc, cpu.ctx_lens, w.budget)
+    note("  tie swaps vs oracle:", swaps)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(batch=64, n_q_heads=32, n_kv_heads=8, ctx=1000, ctx_min=1, budget=300),     # one slice per row
+    dict(batch=64, n_q_heads=32, n_kv_heads=8, ctx=1000, ctx_min=1, budget=2048),    # budget above every context
+    dict(batch=2, n_q_heads=8, n_kv_heads=2, ctx=5000, ctx_min=3000, budget=700),    # many short slices
+    dict(batch=40, n_q_heads=16, n_kv_heads=8, ctx=20000, ctx_min=15000, budget=2048),  # long slices, two per row
+    dict(batch=9, n_q_heads=64, n_kv_heads=4, ctx=3333, ctx_min=100, budget=64),     # group of 16
+])
+def test_fused_select_equals_separate_kernels(kw):
+    note("fused-vs-separate", kw)
+    fused_vs_separate(wl.Workload("f", window=8, page_table="scatter", pool_slack=1.1, seed=17, **kw))
+
+
+def test_end_to_end_single_slice_rows_and_long_slices():
+    end_to_end(wl.Workload("f1", 64, 32, 8, 16, 300, 1000, ctx_min=1, page_table="scatter", pool_slack=1.1, seed=5))
+    end_to_end(wl.Workload("f2", 33, 32, 8, 16, 2048, 20000, ctx_min=9000, page_table="permute", seed=6))
+
+
 def test_end_to_end_c1():
     end_to_end(wl.CONFIGS["c1"])
 
