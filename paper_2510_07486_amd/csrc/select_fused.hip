@@ -1,37 +1,48 @@
 // Fused key scoring + top-k for one layer-step (Alg. 1 step 7 followed by the cache rank's
 // top-k, Sec. 4.3 items (1)-(2)), without ever writing the per-token scores to HBM.
 //
-// Each (sequence, KV head) row is cut into slices of at most 16384 tokens.  One 1024-thread
+// Each (sequence, KV head) row is cut into slices of at most 8192 tokens.  One 512-thread
 // workgroup streams the slice's K pages (coalesced non-temporal 128-bit loads, transposed
 // through a per-wave 4 KB LDS image into the MFMA operand layout, see score_common.hpp),
-// keeps the 32-bit order-preserving keys of its scores in LDS (64 KB) and accumulates the first
+// keeps the 32-bit order-preserving keys of its scores in LDS (32 KB) and accumulates the first
 // radix histogram while it streams.  It then radix-selects its local top-min(C, slice) in LDS
 // and emits them in ascending token order: straight into sel_idx when the row has a single
 // slice, otherwise as (key, index) candidates that a small merge kernel reduces to the row's
-// top-C.  The global top-C is contained in the union of the per-slice top-C, and both levels
+// top-C.  72 KB of LDS per workgroup lets two share a compute unit, so one workgroup's
+// latency-bound phases (table and query fetch, radix select) hide behind the other's streaming.  The global top-C is contained in the union of the per-slice top-C, and both levels
 // resolve equal keys to the lowest index, so the result equals a full sort of the row.
 // HBM traffic: one read of K, 8 B per candidate instead of 4 B per token.
+#include <cstdlib>
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
 
 namespace asx {
 
-static constexpr int FS_SMAX = 16384;  // tokens per slice whose keys fit LDS next to the staging
-static constexpr int FS_WAVES = TK_THREADS / 64;
-static constexpr int FS_MAX_SLICES = 4096;
-static constexpr int FS_TARGET_WGS = 512;  // two workgroups per compute unit
+// Two shapes of the slice workgroup: 512 threads / 8192 tokens / 72 KB LDS (two per compute
+// unit) and 1024 threads / 16384 tokens / 144 KB (one per compute unit, half the candidates).
+template <int THREADS> struct fs_shape {
+  static constexpr int WAVES = THREADS / 64;
+  static constexpr int SMAX = THREADS * 16;               // tokens per slice (keys: 4 B each)
+  static constexpr int B0 = THREADS == 1024 ? 12 : 11;    // bits of the histogram built while streaming
+  static constexpr int BINS = 1 << B0;
+};
+static constexpr int FS_MAX_SLICES = 8192;
+static int g_fs_threads = 512;   // development knob
+extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 1024) ? 1024 : 512; }
 
 select_plan plan_select(const as_params* p) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  int64_t st = rows > 0 ? (FS_TARGET_WGS + rows - 1) / rows : 1;
+  const int smax = g_fs_threads * 16;
+  const int target_wgs = g_fs_threads == 1024 ? 512 : 1024;   // two rounds per compute unit
+  int64_t st = rows > 0 ? (target_wgs + rows - 1) / rows : 1;
   if (st < 1) st = 1;
   int64_t sl = (max_ctx + st - 1) / st;
   sl = (sl + 63) / 64 * 64;
   if (sl < 256) sl = 256;
-  if (sl > FS_SMAX) sl = FS_SMAX;
+  if (sl > smax) sl = smax;
   pl.slice_len = (int)sl;
   pl.nslices = (int)((max_ctx + sl - 1) / sl);
   if (pl.nslices < 1) pl.nslices = 1;
@@ -46,17 +57,19 @@ size_t select_workspace_bytes(const as_params* p) {
   return rows * pl.nslices * ((size_t)pl.ccap * 8 + 4);
 }
 
-template <int NSET>
-__global__ __launch_bounds__(TK_THREADS) void select_slice_kernel(
+template <int NSET, int FS_THREADS>
+__global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const uint16_t* __restrict__ k_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
     int max_pages, int slice_len, int nslices, int C, int ccap, uint32_t* __restrict__ cand_key,
     int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt, int32_t* __restrict__ sel_idx,
-    int32_t* __restrict__ sel_cnt) {
-  __shared__ uint32_t keys[FS_SMAX];
-  __shared__ uint4 stage[FS_WAVES][256];
-  __shared__ uint32_t hist[TK_BINS];
-  __shared__ uint32_t wave_tot[TK_WAVES], wave_eq[TK_WAVES], wave_gt[TK_WAVES], found[2];
+    int32_t* __restrict__ sel_cnt, int dbg) {
+  constexpr int FS_WAVES = fs_shape<FS_THREADS>::WAVES, FS_SMAX = fs_shape<FS_THREADS>::SMAX;
+  constexpr int FS_B0 = fs_shape<FS_THREADS>::B0, FS_BINS = fs_shape<FS_THREADS>::BINS;
+  __shared__ __attribute__((aligned(16))) uint32_t keys[FS_SMAX];
+  __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images; output staging after streaming
+  __shared__ uint32_t hist[FS_BINS];
+  __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
   const int b = blockIdx.z, j = blockIdx.y, sl = blockIdx.x;
   const int64_t row = (int64_t)b * Hkv + j;
@@ -69,16 +82,16 @@ __global__ __launch_bounds__(TK_THREADS) void select_slice_kernel(
   const bool final_out = (nslices == 1);
   if (n_loc == 0) {
     if (final_out) {
-      for (int i = tid; i < C; i += TK_THREADS) sel_idx[row * C + i] = -1;
+      for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = -1;
       if (tid == 0) sel_cnt[row] = 0;
     } else if (tid == 0) {
       cand_cnt[row * nslices + sl] = 0;
     }
     return;
   }
-  for (int i = tid; i < TK_BINS; i += TK_THREADS) hist[i] = 0;
+  for (int i = tid; i < FS_BINS; i += FS_THREADS) hist[i] = 0;
 
-  // ---- stream the slice: wave w owns page quads w, w+16, ...; lane l keeps the page id of
+  // ---- stream the slice: wave w owns page quads w, w+8, ...; lane l keeps the page id of
   //      (iteration l>>2, page l&3), one table load per wave for the whole slice ----
   const int npages_loc = (n_loc + AS_PAGE - 1) / AS_PAGE;
   const int page0 = tok0 / AS_PAGE;
@@ -130,32 +143,49 @@ __global__ __launch_bounds__(TK_THREADS) void select_slice_kernel(
     if (tl < n_loc) {
       const uint32_t key = score_key(outv + 0.0f);
       keys[tl] = key;
-      atomicAdd(&hist[key >> 20], 1u);
+      atomicAdd(&hist[key >> (32 - FS_B0)], 1u);
     }
   }
   __syncthreads();
 
-  // ---- local top-min(C, n_loc), ascending token order ----
+  if (dbg == 1) return;
+  // ---- local top-min(C, n_loc), ascending token order; results are staged in LDS (the page
+  //      images are dead by now) and written out with coalesced stores ----
   const int keep = n_loc < C ? n_loc : C;
   const int64_t cbase = (row * nslices + sl) * (int64_t)ccap;
-  auto key_of = [&](int i, bool& valid) -> uint32_t {
-    valid = true;
-    return keys[i];
+  uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);          // [FS_SMAX / 2]
+  int32_t* o_idx = reinterpret_cast<int32_t*>(o_key + FS_SMAX / 2);      // [FS_SMAX / 2]
+  const bool staged = final_out || keep <= FS_SMAX / 2;
+  auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
+    const uint4 u = (i4 < n_loc) ? *reinterpret_cast<const uint4*>(&keys[i4]) : make_uint4(0, 0, 0, 0);
+    k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = i4 + e < n_loc;
   };
   auto emit = [&](uint32_t pos, int i, uint32_t key) {
     if (final_out) {
-      sel_idx[row * C + pos] = tok0 + i;
+      reinterpret_cast<int32_t*>(o_key)[pos] = tok0 + i;           // up to FS_SMAX indices
+    } else if (staged) {
+      o_key[pos] = key;
+      o_idx[pos] = tok0 + i;
     } else {
       cand_key[cbase + pos] = key;
       cand_idx[cbase + pos] = tok0 + i;
     }
   };
-  block_select(n_loc, n_loc, keep, true, key_of, emit, hist, wave_tot, wave_eq, wave_gt, found);
+  block_select<FS_THREADS, FS_B0>(n_loc, n_loc, keep, true, key4_of, emit, hist, xch);
+  __syncthreads();
   if (final_out) {
-    for (int i = keep + tid; i < C; i += TK_THREADS) sel_idx[row * C + i] = -1;
+    const int32_t* src = reinterpret_cast<const int32_t*>(o_key);
+    for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? src[i] : -1;
     if (tid == 0) sel_cnt[row] = keep;
-  } else if (tid == 0) {
-    cand_cnt[row * nslices + sl] = keep;
+  } else {
+    if (staged && dbg != 3)
+      for (int i = tid; i < keep; i += FS_THREADS) {
+        cand_key[cbase + i] = o_key[i];
+        cand_idx[cbase + i] = o_idx[i];
+      }
+    if (tid == 0) cand_cnt[row * nslices + sl] = keep;
   }
 }
 
@@ -168,7 +198,7 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t
                                                                   int32_t* __restrict__ sel_cnt) {
   __shared__ int32_t cnt_sh[FS_MAX_SLICES];
   __shared__ uint32_t hist[TK_BINS];
-  __shared__ uint32_t wave_tot[TK_WAVES], wave_eq[TK_WAVES], wave_gt[TK_WAVES], found[2];
+  __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
   __shared__ int total_sh;
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x;
@@ -192,7 +222,8 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t
   };
   auto emit = [&](uint32_t pos, int v, uint32_t) { sel_idx[row * C + pos] = cand_idx[cbase + v]; };
   if (keep > 0)
-    block_select(nslices * ccap, total, keep, false, key_of, emit, hist, wave_tot, wave_eq, wave_gt, found);
+    block_select<TK_THREADS, 12>(nslices * ccap, total, keep, false, key4_from_scalar(nslices * ccap, key_of), emit, hist,
+                                 xch);
   for (int i = keep + tid; i < C; i += TK_THREADS) sel_idx[row * C + i] = -1;
   if (tid == 0) sel_cnt[row] = keep;
 }
@@ -212,16 +243,19 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
     cand_cnt = cand_idx + n;
   }
   dim3 grid(pl.nslices, p->n_kv_heads, p->batch);
+  static const int dbg = getenv("AS_DBG") ? atoi(getenv("AS_DBG")) : 0;
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
-  if (two)
-    hipLaunchKernelGGL(select_slice_kernel<2>, grid, dim3(TK_THREADS), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat,
-                       p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices,
-                       p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt);
-  else
-    hipLaunchKernelGGL(select_slice_kernel<1>, grid, dim3(TK_THREADS), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat,
-                       p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices,
-                       p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt);
+#define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
+                     q_hat, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, \
+                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt, dbg)
+  if (g_fs_threads == 1024) {
+    if (two) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
+  } else {
+    if (two) AS_SLICE_LAUNCH(2, 512); else AS_SLICE_LAUNCH(1, 512);
+  }
+#undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || pl.nslices == 1) return e;
   hipLaunchKernelGGL(select_merge_kernel, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, cand_key, cand_idx, cand_cnt,

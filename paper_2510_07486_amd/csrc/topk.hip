@@ -1,12 +1,10 @@
 // Per-(sequence, KV head) top-k over the fp32 score row (Sec. 4.3, cache-rank item (2)).
 //
 // Exact radix select, no sort: scores map to order-preserving 32-bit keys; three LDS
-// histogram passes (12 + 12 + 8 bits, most significant first) find the key T of the
+// histogram passes (12 + 10 + 10 bits, most significant first) find the key T of the
 // C-th largest score and r, the number of tokens equal to T still to be taken; one
 // ordered pass then emits, ascending by token index, every token with key > T and the
-// first r tokens with key == T (so ties resolve to the lowest index).  The output slot of
-// a token is (#greater before it) + min(#equal before it, r), which needs only wavefront
-// ballots and one 16-entry cross-wave prefix per 1024-token chunk.
+// first r tokens with key == T (so ties resolve to the lowest index).  See block_select.
 // One 1024-thread workgroup per row; the row is re-read from L2 each pass.  This is the
 // stand-alone stage; the fused selection keeps the keys in LDS instead (select_fused.hip).
 #include "common.hpp"
@@ -20,7 +18,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float* __restric
                                                           int32_t* __restrict__ sel_idx,
                                                           int32_t* __restrict__ sel_cnt, int Hkv, int C) {
   __shared__ uint32_t hist[TK_BINS];
-  __shared__ uint32_t wave_tot[TK_WAVES], wave_eq[TK_WAVES], wave_gt[TK_WAVES], found[2];
+  __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
   const int row = blockIdx.x;
   const int b = row / Hkv;
@@ -37,7 +35,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float* __restric
     return score_key(s[i]);
   };
   auto emit = [&](uint32_t pos, int i, uint32_t) { out[pos] = i; };
-  block_select(N, N, keep, false, key_of, emit, hist, wave_tot, wave_eq, wave_gt, found);
+  block_select<TK_THREADS, 12>(N, N, keep, false, key4_from_scalar(N, key_of), emit, hist, xch);
 }
 
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,

@@ -1,13 +1,13 @@
-// Device helpers shared by the top-k kernels: order-preserving score keys and the
-// block-wide histogram search of the radix select (1024-thread workgroups).
+// Device helpers shared by the top-k kernels: order-preserving score keys and an exact
+// block-wide radix select with ordered emission (1024-thread workgroups).
 #pragma once
 #include "common.hpp"
 
 namespace asx {
 
-static constexpr int TK_THREADS = 1024;
-static constexpr int TK_WAVES = TK_THREADS / 64;
-static constexpr int TK_BINS = 4096;
+static constexpr int TK_THREADS = 1024;   // workgroup size of the stand-alone top-k and merge kernels
+static constexpr int TK_BINS = 4096;      // histogram bins they need (12-bit first pass)
+static constexpr int TK_XCH = 16 + 128 + 2; // words of LDS exchange space block_select needs
 
 // larger float -> larger key; -0 == +0; NaN -> 0 (below -inf)
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -17,115 +17,184 @@ __device__ __forceinline__ uint32_t score_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with six DPP adds: Hillis-Steele
+// inside each 16-lane row (row_shr 1, 2, 4, 8), then lane 15 of rows 0 / 2 into rows 1 / 3
+// (row_bcast:15) and lane 31 into rows 2-3 (row_bcast:31).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);
+  return x;
+}
+
+// Exclusive prefix, over (segment, wave) pairs in segment-major order, of NSEG*WAVES <= 64 words
+// written by the waves of the workgroup to `words[seg * WAVES + wave]`: every wave loads them
+// one per lane, scans with DPP and picks its own NSEG offsets with v_readlane.  Returns the
+// grand total.  Call after a barrier that follows the writes.
+template <int WAVES, int NSEG>
+__device__ __forceinline__ uint32_t seg_wave_offsets(const uint32_t* words, int wave, uint32_t (&off)[NSEG]) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t w = (lane < NSEG * WAVES) ? words[lane] : 0u;
+  const uint32_t inc = wave_incl_scan(w);
+  const uint32_t exc = inc - w;
+  const int uw = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+  for (int sgm = 0; sgm < NSEG; ++sgm) off[sgm] = (uint32_t)__builtin_amdgcn_readlane((int)exc, sgm * WAVES + uw);
+  return (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+}
+
 // Finds the bin d (scanning from the highest bin down) with
 //   sum_{d' > d} hist[d'] < remaining <= sum_{d' >= d} hist[d'];
-// writes d and the count above it to sh_out[0..1].  nb <= 4 * TK_THREADS bins.
+// writes d and the count above it to found[0..1].  nb <= 4 * THREADS bins.
+// wave_tot: 16 words of LDS.
+template <int THREADS>
 __device__ __forceinline__ void find_bin(const uint32_t* hist, int nb, uint32_t remaining, uint32_t* wave_tot,
-                                         uint32_t* sh_out) {
+                                         uint32_t* found) {
+  constexpr int WAVES = THREADS / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int per = (nb + TK_THREADS - 1) / TK_THREADS;  // bins per thread, descending order
-  uint32_t loc[4];
+  const int per = (nb + THREADS - 1) / THREADS;  // bins per thread, descending order
+  uint32_t loc[4] = {0u, 0u, 0u, 0u};
   uint32_t mine = 0;
-  for (int i = 0; i < per; ++i) {
-    int rb = tid * per + i;  // reversed bin index
-    loc[i] = (rb < nb) ? hist[nb - 1 - rb] : 0u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rb = tid * per + i;  // reversed bin index
+    if (i < per && rb < nb) loc[i] = hist[nb - 1 - rb];
     mine += loc[i];
   }
-  // inclusive scan across the block
-  uint32_t inc = mine;
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t v = __shfl_up(inc, o);
-    if (lane >= o) inc += v;
-  }
+  const uint32_t inc = wave_incl_scan(mine);
   if (lane == 63) wave_tot[wave] = inc;
   __syncthreads();
-  uint32_t off = 0;
-  for (int w = 0; w < wave; ++w) off += wave_tot[w];
-  uint32_t excl = off + inc - mine;
-  for (int i = 0; i < per; ++i) {
-    if (excl < remaining && remaining <= excl + loc[i]) {
-      sh_out[0] = (uint32_t)(nb - 1 - (tid * per + i));
-      sh_out[1] = excl;
+  uint32_t off[1];
+  seg_wave_offsets<WAVES, 1>(wave_tot, wave, off);
+  uint32_t excl = off[0] + inc - mine;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < per && excl < remaining && remaining <= excl + loc[i]) {
+      found[0] = (uint32_t)(nb - 1 - (tid * per + i));
+      found[1] = excl;
     }
     excl += loc[i];
   }
   __syncthreads();
 }
 
-
 // Exact selection of the `keep` largest of the valid keys at virtual positions 0..n-1, emitted
 // in ascending position order; equal keys resolve to the lowest position.  Run by a whole
-// 1024-thread workgroup.
-//   key_of(i, valid) -> key of position i (valid = false marks a hole that is never selected)
-//   emit(pos, i, key)   called once per selected position, pos = its rank in ascending order
+// workgroup of THREADS (512 or 1024) threads.
+//   key4_of(i4, k, valid)  loads the keys of positions i4..i4+3 (i4 a multiple of 4; positions
+//                          >= n must come back invalid); valid = false marks a hole
+//   emit(pos, i, key)      called once per selected position, pos = its rank in ascending order
 //   total = number of valid positions (>= keep); keep >= total selects everything.
-//   hist0_ready: hist[] already holds the histogram of the top 12 key bits of all valid keys.
-// Radix select: three histogram passes (12 + 12 + 8 bits, most significant first) find the key T
-// of the keep-th largest and r, how many keys equal to T are still to be taken; the output
-// slot of a selected position is (#greater before it) + min(#equal before it, r).
-template <class KeyFn, class EmitFn>
-__device__ __forceinline__ void block_select(int n, int total, int keep, bool hist0_ready, KeyFn key_of, EmitFn emit,
-                                             uint32_t* hist, uint32_t* wave_tot, uint32_t* wave_eq,
-                                             uint32_t* wave_gt, uint32_t* found) {
+//   hist0_ready: hist[] already holds the histogram of the top B0 key bits of all valid keys.
+//   hist: 2^B0 words of LDS (B0 = 11 or 12);  xch: TK_XCH words of LDS.
+// Radix select: three histogram passes (B0 bits, then the rest in two halves, most significant
+// first) find the key T of the keep-th largest and r, how many keys equal to T are still to be
+// taken.  Emission walks 16*THREADS positions per round as four segments; a thread owns four
+// consecutive positions of each segment.  The output slot of a selected position is
+// (#greater before it) + min(#equal before it, r): packed (greater | equal << 16) counts are
+// scanned with DPP inside the wave and across (segment, wave) pairs after one barrier.
+template <int THREADS, int B0, class Key4Fn, class EmitFn>
+__device__ __forceinline__ void block_select(int n, int total, int keep, bool hist0_ready, Key4Fn key4_of,
+                                             EmitFn emit, uint32_t* hist, uint32_t* xch) {
+  constexpr int WAVES = THREADS / 64;
+  constexpr int B1 = (32 - B0 + 1) / 2, B2 = 32 - B0 - B1;
+  constexpr int SEG = 4 * THREADS;  // positions per segment
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t* wave_tot = xch;   // [16]
+  uint32_t* segw = xch + 16;  // [2][4 * WAVES <= 64] packed counts, double-buffered across rounds
+  uint32_t* found = xch + 16 + 128;
   const bool all = keep >= total;
   uint32_t T = 0, r = 0;
   if (!all) {
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)keep;
 #pragma unroll 1
     for (int pass = 0; pass < 3; ++pass) {
-      const int width = pass == 2 ? 8 : 12;
-      const int sh = pass == 0 ? 20 : pass == 1 ? 8 : 0;
+      const int width = pass == 0 ? B0 : pass == 1 ? B1 : B2;
+      const int sh = pass == 0 ? 32 - B0 : pass == 1 ? B2 : 0;
       const int nb = 1 << width;
       if (!(pass == 0 && hist0_ready)) {
-        for (int i = tid; i < nb; i += TK_THREADS) hist[i] = 0;
+        for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += TK_THREADS) {
-          bool valid;
-          const uint32_t k = key_of(i, valid);
-          if (valid && (k & mask) == prefix) atomicAdd(&hist[(k >> sh) & (nb - 1)], 1u);
+#pragma unroll 1
+        for (int base = 0; base < n; base += 4 * SEG) {
+          uint32_t k[4][4];
+          bool v[4][4];
+#pragma unroll
+          for (int sgm = 0; sgm < 4; ++sgm) key4_of(base + sgm * SEG + 4 * tid, k[sgm], v[sgm]);
+#pragma unroll
+          for (int sgm = 0; sgm < 4; ++sgm)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v[sgm][e] && (k[sgm][e] & mask) == prefix) atomicAdd(&hist[(k[sgm][e] >> sh) & (nb - 1)], 1u);
         }
         __syncthreads();
       }
-      find_bin(hist, nb, remaining, wave_tot, found);
+      find_bin<THREADS>(hist, nb, remaining, wave_tot, found);
       prefix |= found[0] << sh;
       mask |= (uint32_t)(nb - 1) << sh;
       remaining -= found[1];
-      __syncthreads();
     }
     T = prefix;
     r = remaining;
   }
   uint32_t gt_run = 0, eq_run = 0;
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int round = 0;
 #pragma unroll 1
-  for (int base = 0; base < n; base += TK_THREADS) {
-    const int i = base + tid;
-    bool valid = false;
-    uint32_t k = 0;
-    if (i < n) k = key_of(i, valid);
-    const bool gt = valid && (all || k > T);
-    const bool eq = valid && !all && k == T;
-    const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
-    if (lane == 0) {
-      wave_gt[wave] = __popcll(bgt);
-      wave_eq[wave] = __popcll(beq);
-    }
-    __syncthreads();
-    uint32_t gt_before = gt_run + __popcll(bgt & lt_mask), eq_before = eq_run + __popcll(beq & lt_mask);
-    uint32_t gt_tot = 0, eq_tot = 0;
+  for (int base = 0; base < n; base += 4 * SEG, ++round) {
+    uint32_t k[4][4];
+    bool v[4][4];
+    uint32_t p[4], inc[4];
 #pragma unroll
-    for (int w = 0; w < TK_WAVES; ++w) {
-      const uint32_t g = wave_gt[w], e = wave_eq[w];
-      if (w < wave) { gt_before += g; eq_before += e; }
-      gt_tot += g;
-      eq_tot += e;
+    for (int sgm = 0; sgm < 4; ++sgm) key4_of(base + sgm * SEG + 4 * tid, k[sgm], v[sgm]);
+    uint32_t* x = segw + (round & 1) * 64;  // double-buffered: one barrier per round
+#pragma unroll
+    for (int sgm = 0; sgm < 4; ++sgm) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool gt = v[sgm][e] && (all || k[sgm][e] > T);
+        const bool eq = v[sgm][e] && !all && k[sgm][e] == T;
+        c += (gt ? 1u : 0u) + (eq ? 0x10000u : 0u);
+      }
+      p[sgm] = c;
+      inc[sgm] = wave_incl_scan(c);
+      if (lane == 63) x[sgm * WAVES + wave] = inc[sgm];
     }
-    if (gt || (eq && eq_before < r)) emit(gt_before + (eq_before < r ? eq_before : r), i, k);
-    gt_run += gt_tot;
-    eq_run += eq_tot;
     __syncthreads();
+    uint32_t off[4];
+    const uint32_t tot = seg_wave_offsets<WAVES, 4>(x, wave, off);  // fields stay below 2^15: no carry
+#pragma unroll
+    for (int sgm = 0; sgm < 4; ++sgm) {
+      const uint32_t before = off[sgm] + inc[sgm] - p[sgm];
+      uint32_t g = gt_run + (before & 0xffffu), q = eq_run + (before >> 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool gt = v[sgm][e] && (all || k[sgm][e] > T);
+        const bool eq = v[sgm][e] && !all && k[sgm][e] == T;
+        if (gt || (eq && q < r)) emit(g + (q < r ? q : r), base + sgm * SEG + 4 * tid + e, k[sgm][e]);
+        g += gt ? 1u : 0u;
+        q += eq ? 1u : 0u;
+      }
+    }
+    gt_run += tot & 0xffffu;
+    eq_run += tot >> 16;
   }
+}
+
+// adapts a per-position key function to the four-at-a-time interface
+template <class KeyFn>
+__device__ __forceinline__ auto key4_from_scalar(int n, KeyFn key_of) {
+  return [=](int i4, uint32_t (&k)[4], bool (&v)[4]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = false;
+      k[e] = 0;
+      if (i4 + e < n) k[e] = key_of(i4 + e, v[e]);
+    }
+  };
 }
 
 }  // namespace asx
