@@ -73,9 +73,11 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->ws_bytes = workspace_bytes;
   c->score_variant = 12;
   c->select_mode = 0;
-  if (workspace_bytes > 0 && hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
-    delete c;
-    return AS_ERR_HIP;
+  if (workspace_bytes > 0) {
+    if (hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
+      delete c;
+      return AS_ERR_HIP;
+    }
   }
   *out = c;
   return AS_OK;

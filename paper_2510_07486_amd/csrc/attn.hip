@@ -3,33 +3,44 @@
 // selection was made.
 //
 // HBM-bound on the index-gathered K and V rows (2 x 256 B per selected token and KV head).
-// Split-C: a 256-thread workgroup owns one 128-token chunk of the logical token list of one
+// Split-C: a 256-thread workgroup owns 128-token chunks of the logical token list of one
 // (sequence, KV head) and up to 8 of the group's query heads, so every gathered row is read
-// once for the whole group.  A 16-lane segment reads one 256-byte row with 128-bit loads
-// (4 rows per wavefront load).  Per chunk: logits -> LDS, chunk max, p = exp(l - m), then
-// P*V with no rescaling inside the chunk.  Partials (m, l, o) go to the workspace and a
-// small second kernel merges them and writes bf16.
+// once for the whole group.  The dependent chain index -> page id -> row address is walked
+// once per chunk with one lane per token (three memory round trips in all); then a 16-lane
+// row of the wavefront reads one 256-byte K / V row with non-temporal 128-bit loads, 16 loads
+// in flight per lane.  Q.K uses v_dot2c_f32_bf16 and a DPP rotate all-reduce inside the row;
+// logits go to LDS, the chunk max and p = exp(l - m) follow, then P.V with no rescaling inside
+// the chunk.  Each workgroup writes its partial (m, l, o); a small second kernel merges them
+// and writes bf16.
 #include "common.hpp"
 
 namespace asx {
 
 static constexpr int AT_CHUNK = AS_ATTN_CHUNK;  // 128 tokens: 4 waves x 8 loads x 4 rows
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
 __host__ __device__ inline int attn_nsplit(int C) { return (C + AT_CHUNK - 1) / AT_CHUNK + 1; }
 static inline int attn_gh(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 
+// partial outputs and partial (m, l) pairs
 size_t attn_workspace_bytes(const as_params* p) {
   size_t heads = (size_t)p->batch * p->n_q_heads;
   size_t ns = (size_t)attn_nsplit(p->budget);
   return heads * ns * (AS_HEAD_DIM + 2) * sizeof(float);
 }
 
-__device__ __forceinline__ float seg16_sum(float v) {
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
-  return v;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+// sum over the 16 lanes of a DPP row, result in every lane (rotations by 8, 4, 2, 1)
+__device__ __forceinline__ float row16_allsum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x124, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x122, 0xf, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x121, 0xf, 0xf, false));
+  return x;
 }
 __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -39,6 +50,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
   return v;
 }
+__device__ __forceinline__ uint4 ld16_nt(const void* p) {
+  const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
 
 template <int GH>
 __global__ __launch_bounds__(256) void attn_split_kernel(
@@ -46,9 +61,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
     float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit) {
-  __shared__ float lg[GH][AT_CHUNK];        // logits, then probabilities
-  __shared__ float sc_sh[GH];               // rescale factor of the running accumulator
-  __shared__ float red[4][GH][AS_HEAD_DIM]; // per-wave partial outputs
+  __shared__ float lg[GH][AT_CHUNK];         // logits, then probabilities
+  __shared__ float sc_sh[GH];                // rescale factor of the running accumulator
+  __shared__ float red[4][GH][AS_HEAD_DIM];  // per-wave partial outputs
 
   const int b = blockIdx.z;
   const int hblocks = G / GH;
@@ -74,128 +89,137 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 0] = -INFINITY;
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 1] = 0.f;
     }
-    return;
-  }
-
-  // the block's query heads, dims 8c..8c+7, as fp32
-  float qf[GH][8];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    const uint4 u = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + h0 + g) * AS_HEAD_DIM + c * 8);
-    qf[g][0] = bf16lo(u.x); qf[g][1] = bf16hi(u.x); qf[g][2] = bf16lo(u.y); qf[g][3] = bf16hi(u.y);
-    qf[g][4] = bf16lo(u.z); qf[g][5] = bf16hi(u.z); qf[g][6] = bf16lo(u.w); qf[g][7] = bf16hi(u.w);
-  }
-  float acc[GH][8];
-#pragma unroll
-  for (int g = 0; g < GH; ++g)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  // running softmax stats of head g live in wave (g & 3), slot g >> 2 (all lanes alike)
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-
-  const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
-  const int32_t* bt_row = block_table + (int64_t)b * max_pages;
-
-#pragma unroll 1
-  for (int ck = ck_begin; ck < ck_end; ++ck) {
-    const int ti0 = ck * AT_CHUNK + w * 32 + slot;
-    uint4 vreg[8];
-    // ---- phase 1: logits of this wave's 32 tokens (8 loads x 4 rows) ----
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int ti = ti0 + it * 4;
-      const bool valid = ti < L;
-      int n = 0;
-      if (valid) n = (ti < cnt) ? idx_row[ti] : tail0 + (ti - cnt);
-      n = n < 0 ? 0 : (n >= N ? N - 1 : n);  // keeps a bad index inside the sequence's pages
-      const int32_t page = bt_row[n >> 4];
-      const int64_t off = chunk_offset(page, Hkv, j) + (int64_t)(n & 15) * AS_HEAD_DIM + c * 8;
-      const uint4 ku = *reinterpret_cast<const uint4*>(k_pool + off);
-      vreg[it] = *reinterpret_cast<const uint4*>(v_pool + off);
-      float kf[8] = {bf16lo(ku.x), bf16hi(ku.x), bf16lo(ku.y), bf16hi(ku.y),
-                     bf16lo(ku.z), bf16hi(ku.z), bf16lo(ku.w), bf16hi(ku.w)};
-      float mine = 0.f;
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s = fmaf(qf[g][e], kf[e], s);
-        s = seg16_sum(s);
-        if (c == g) mine = s;
-      }
-      if (c < GH) lg[c][w * 32 + it * 4 + slot] = valid ? mine * sm_scale : -INFINITY;
-    }
-    __syncthreads();
-    // ---- phase 1b: chunk max, probabilities, running stats (wave w owns heads w, w+4) ----
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int g = w + 4 * k;
-      if (g < GH) {
-        const float x0 = lg[g][lane], x1 = lg[g][lane + 64];
-        const float mx = wave_max(fmaxf(x0, x1));
-        const float m_new = fmaxf(m_run[k], mx);      // finite: the chunk holds >= 1 valid token
-        const float scl = (m_run[k] == -INFINITY) ? 0.f : expf(m_run[k] - m_new);
-        const float p0 = expf(x0 - m_new), p1 = expf(x1 - m_new);
-        lg[g][lane] = p0;
-        lg[g][lane + 64] = p1;
-        const float ps = wave_sum(p0 + p1);
-        l_run[k] = l_run[k] * scl + ps;
-        m_run[k] = m_new;
-        if (lane == 0) sc_sh[g] = scl;
-      }
-    }
-    __syncthreads();
-    // ---- phase 2: acc = acc * scale + sum_t p_t V_t ----
+  } else {
+    // the block's query heads, dims 8c..8c+7, as packed bf16 pairs
+    uint32_t qp[GH][4];
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
-      const float scl = sc_sh[g];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] *= scl;
+      const uint4 u = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + h0 + g) * AS_HEAD_DIM + c * 8);
+      qp[g][0] = u.x; qp[g][1] = u.y; qp[g][2] = u.z; qp[g][3] = u.w;
     }
+    float acc[GH][8];
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const uint4 vu = vreg[it];
-      float vf[8] = {bf16lo(vu.x), bf16hi(vu.x), bf16lo(vu.y), bf16hi(vu.y),
-                     bf16lo(vu.z), bf16hi(vu.z), bf16lo(vu.w), bf16hi(vu.w)};
+    for (int g = 0; g < GH; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    // running softmax stats of head g live in wave (g & 3), slot g >> 2 (all lanes alike)
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+    const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
+    const int32_t* bt_row = block_table + (int64_t)b * max_pages;
+
+#pragma unroll 1
+    for (int ck = ck_begin; ck < ck_end; ++ck) {
+      // ---- addresses: lane l (< 32) resolves token l of this wave's 32 ----
+      const int tw0 = ck * AT_CHUNK + w * 32;
+      uint32_t my_pk = 0;  // page id << 4 | slot in page
+      {
+        const int ti = tw0 + (lane & 31);
+        int n = 0;
+        if (ti < L) n = (ti < cnt) ? idx_row[ti] : tail0 + (ti - cnt);
+        n = n < 0 ? 0 : (n >= N ? N - 1 : n);  // keeps a bad index inside the sequence's pages
+        my_pk = ((uint32_t)bt_row[n >> 4] << 4) | (uint32_t)(n & 15);
+      }
+      // ---- all 16 row loads of this lane (8 K, 8 V) ----
+      uint4 kreg[8], vreg[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const uint32_t pk = __shfl(my_pk, it * 4 + slot);
+        const int64_t off = chunk_offset((int32_t)(pk >> 4), Hkv, j) + (int64_t)(pk & 15) * AS_HEAD_DIM + c * 8;
+        kreg[it] = ld16_nt(k_pool + off);
+        vreg[it] = ld16_nt(v_pool + off);
+      }
+      // ---- phase 1: logits ----
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const bool valid = tw0 + it * 4 + slot < L;
+        float mine = 0.f;
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          float s = dot2_bf16(qp[g][0], kreg[it].x, 0.f);
+          s = dot2_bf16(qp[g][1], kreg[it].y, s);
+          s = dot2_bf16(qp[g][2], kreg[it].z, s);
+          s = dot2_bf16(qp[g][3], kreg[it].w, s);
+          s = row16_allsum(s);
+          if (c == g) mine = s;
+        }
+        if (c < GH) lg[c][w * 32 + it * 4 + slot] = valid ? mine * sm_scale : -INFINITY;
+      }
+      __syncthreads();
+      // ---- phase 1b: chunk max, probabilities, running stats (wave w owns heads w, w+4) ----
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int g = w + 4 * k;
+        if (g < GH) {
+          const float x0 = lg[g][lane], x1 = lg[g][lane + 64];
+          const float mx = wave_max(fmaxf(x0, x1));
+          const float m_new = fmaxf(m_run[k], mx);  // finite: the chunk holds >= 1 valid token
+          const float scl = (m_run[k] == -INFINITY) ? 0.f : expf(m_run[k] - m_new);
+          const float p0 = expf(x0 - m_new), p1 = expf(x1 - m_new);
+          lg[g][lane] = p0;
+          lg[g][lane + 64] = p1;
+          const float ps = wave_sum(p0 + p1);
+          l_run[k] = l_run[k] * scl + ps;
+          m_run[k] = m_new;
+          if (lane == 0) sc_sh[g] = scl;
+        }
+      }
+      __syncthreads();
+      // ---- phase 2: acc = acc * scale + sum_t p_t V_t ----
 #pragma unroll
       for (int g = 0; g < GH; ++g) {
-        const float pr = lg[g][w * 32 + it * 4 + slot];
+        const float scl = sc_sh[g];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pr, vf[e], acc[g][e]);
+        for (int e = 0; e < 8; ++e) acc[g][e] *= scl;
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const uint4 vu = vreg[it];
+        float vf[8] = {bf16lo(vu.x), bf16hi(vu.x), bf16lo(vu.y), bf16hi(vu.y),
+                       bf16lo(vu.z), bf16hi(vu.z), bf16lo(vu.w), bf16hi(vu.w)};
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          const float pr = lg[g][w * 32 + it * 4 + slot];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pr, vf[e], acc[g][e]);
+        }
+      }
+      __syncthreads();
+    }
+
+    // ---- reduce the 4 slots of a wave, then the 4 waves ----
+#pragma unroll
+    for (int g = 0; g < GH; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = acc[g][e];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (slot == 0) red[w][g][c * 8 + e] = v;
+      }
+    __syncthreads();
+    for (int i = tid; i < GH * AS_HEAD_DIM; i += 256) {
+      const int g = i / AS_HEAD_DIM, d = i % AS_HEAD_DIM;
+      const float v = red[0][g][d] + red[1][g][d] + red[2][g][d] + red[3][g][d];
+      part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int g = w + 4 * k;
+        if (g < GH) {
+          part_ml[(pbase + (int64_t)g * nsplit) * 2 + 0] = m_run[k];
+          part_ml[(pbase + (int64_t)g * nsplit) * 2 + 1] = l_run[k];
+        }
       }
     }
-    __syncthreads();
   }
 
-  // ---- reduce the 4 slots of a wave, then the 4 waves ----
-#pragma unroll
-  for (int g = 0; g < GH; ++g)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float v = acc[g][e];
-      v += __shfl_xor(v, 16);
-      v += __shfl_xor(v, 32);
-      if (slot == 0) red[w][g][c * 8 + e] = v;
-    }
-  __syncthreads();
-  for (int i = tid; i < GH * AS_HEAD_DIM; i += 256) {
-    const int g = i / AS_HEAD_DIM, d = i % AS_HEAD_DIM;
-    const float v = red[0][g][d] + red[1][g][d] + red[2][g][d] + red[3][g][d];
-    part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int g = w + 4 * k;
-      if (g < GH) {
-        part_ml[(pbase + (int64_t)g * nsplit) * 2 + 0] = m_run[k];
-        part_ml[(pbase + (int64_t)g * nsplit) * 2 + 1] = l_run[k];
-      }
-    }
-  }
 }
 
-// merges the split partials of one (sequence, query head)
+// merges the split partials of one (sequence, query head).  A separate launch on purpose: a
+// "last workgroup merges" scheme needs device-scope fences, which write back and invalidate
+// the whole per-XCD L2 on this chip and cost several times the kernel itself.
 __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* __restrict__ part_o,
                                                                    const float* __restrict__ part_ml,
                                                                    uint16_t* __restrict__ out,
