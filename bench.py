@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=4)
     ap.add_argument("--serial-only", action="store_true")
+    ap.add_argument("--sel-streams", type=int, default=2, help="selection streams (layers round-robin over them)")
     ap.add_argument("--unfused", action="store_true", help="score and top-k as separate kernels through HBM scores")
     return ap.parse_args()
 
@@ -85,25 +86,29 @@ def main():
     eps = float(np.float32(1e-2))
     p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1], ridge_eps=eps,
                         sm_scale=float(np.float32(1 / math.sqrt(128))))
-    ctx_sel, ctx_att = api.Context(p), api.Context(p)
+    n_sel = max(1, a.sel_streams)
+    ctx_sels = [api.Context(p) for _ in range(n_sel)]
+    ctx_att = api.Context(p)
     if a.score_variant >= 0:
-        ctx_sel.set_score_variant(a.score_variant)
+        for c in ctx_sels:
+            c.set_score_variant(a.score_variant)
     kvs = [api.kv_view(L["k"], L["v"], bt, ctx_lens) for L in layers]
     B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
     stride = bt.shape[1] * wl.PAGE
-    q_hat = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
-    scores = torch.empty((B, Hkv, stride), dtype=torch.float32, device=dev)
+    q_hats = [torch.empty((B, Hq, 128), dtype=torch.float32, device=dev) for _ in range(n_sel)]
+    scores = torch.empty((B, Hkv, stride), dtype=torch.float32, device=dev) if a.unfused else None
     # double-buffered selections: step t attends over sel[t % 2], selection writes sel[(t+1) % 2]
     sel = [[(torch.empty((B, Hkv, C), dtype=torch.int32, device=dev),
              torch.empty((B, Hkv), dtype=torch.int32, device=dev)) for _ in range(n_layers)] for _ in range(2)]
     out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
-    s_sel, s_att = torch.cuda.Stream(), torch.cuda.Stream()
+    s_sels, s_att = [torch.cuda.Stream() for _ in range(n_sel)], torch.cuda.Stream()
 
-    def select(l, dst, stream, ev_pair=None):
+    def select(l, dst, stream, ev_pair=None, lane=0):
         """The two calls as_select_step makes (as_predict_query, as_score_topk), issued separately so that the
         K-streaming part can be bracketed by events on its own stream."""
         L = layers[l % resident]
         kv = kvs[l % resident]
+        ctx_sel, q_hat = ctx_sels[lane], q_hats[lane]
         api.as_predict_query(ctx_sel, p, L["qw"], L["qc"], q_hat, stream=stream)
         if ev_pair is not None:
             ev_pair[0].record(stream)
@@ -125,24 +130,26 @@ def main():
     # prime both selection buffers
     for t in range(2):
         for l in range(n_layers):
-            select(l, sel[t][l], s_sel)
+            select(l, sel[t][l], s_sels[0])
     torch.cuda.synchronize()
 
     def step_overlapped(t, score_events=None):
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
         for l in range(n_layers):
+            lane = l % n_sel
             ev = torch.cuda.Event()
             ev.record(s_att)                       # layer l's step-t query/key/value exist from here on
-            s_sel.wait_event(ev)
+            s_sels[lane].wait_event(ev)
             pair = None
             if score_events is not None:
                 pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                 score_events.append(pair)
-            select(l, nxt[l], s_sel, pair)
+            select(l, nxt[l], s_sels[lane], pair, lane)
             attend(l, cur[l], s_att)
-        done = torch.cuda.Event()
-        done.record(s_sel)
-        s_att.wait_event(done)                     # the next step's attention needs every new selection
+        for s_sel in s_sels:                       # the next step's attention needs every new selection
+            done = torch.cuda.Event()
+            done.record(s_sel)
+            s_att.wait_event(done)
 
     def step_serial(t, score_events=None):
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
@@ -179,8 +186,11 @@ def main():
     tokens = int(ctx_lens_cpu.sum())
     k_bytes = tokens * Hkv * 256                                   # algorithmic bytes of one scoring launch
     kv_gather = int(torch.clamp(ctx_lens_cpu, max=C).sum()) * Hkv * 512
-    score_ms = float(np.mean(score_ms_ovl))
-    score_ms_alone = float(np.mean(score_ms_serial))
+    # dominant kernel: the K-streaming part of the selection.  Its roofline uses the launches of the
+    # single-stream timed pass (the kernel alone on the GPU); the rate it keeps while sharing HBM with
+    # the attention stream is reported next to it.
+    score_ms = float(np.mean(score_ms_serial))
+    score_ms_shared = float(np.mean(score_ms_ovl))
     achieved = k_bytes / (score_ms * 1e-3) / 1e9
     step_roofline_us = (k_bytes + kv_gather) / (HBM_PEAK_GBS * 1e9) * 1e6
 
@@ -201,16 +211,17 @@ def main():
         "config": {"workload": f"{a.workload}: Qwen3-8B attention shape" if a.workload in ("c2", "c3", "c5") else a.workload,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128, "context": w.ctx,
                    "window": w.window, "budget": C, "page_size": 16, "layers_per_step": n_layers,
-                   "layers_resident": resident, "streams": 1 if a.serial_only else 2},
+                   "layers_resident": resident, "streams": 1 if a.serial_only else 1 + n_sel},
         "serial_us_per_layer_step": round(us_layer_serial, 2),
         "step_roofline_us": round(step_roofline_us, 2),
         "step_roofline_frac": round(step_roofline_us / us_layer, 4),
         "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
         "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
-        "score_keys_gbs_serial": round(k_bytes / (score_ms_alone * 1e-3) / 1e9, 1),
+        "score_keys_gbs_while_overlapped": round(k_bytes / (score_ms_shared * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "kernel": "score_keys" if a.unfused else "score_topk (slice + merge kernels)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4)},
+                     "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4),
+                     "measured_in": "single-stream timed pass (events on the launch stream)"},
         "input_gen_s": round(gen_s, 1),
     }
 

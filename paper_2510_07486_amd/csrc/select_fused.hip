@@ -9,10 +9,10 @@
 // and emits them in ascending token order: straight into sel_idx when the row has a single
 // slice, otherwise as (key, index) candidates that a small merge kernel reduces to the row's
 // top-C.  72 KB of LDS per workgroup lets two share a compute unit, so one workgroup's
-// latency-bound phases (table and query fetch, radix select) hide behind the other's streaming.  The global top-C is contained in the union of the per-slice top-C, and both levels
+// latency-bound phases (table and query fetch, radix select) hide behind the other's streaming.
+// The global top-C is contained in the union of the per-slice top-C, and both levels
 // resolve equal keys to the lowest index, so the result equals a full sort of the row.
 // HBM traffic: one read of K, 8 B per candidate instead of 4 B per token.
-#include <cstdlib>
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
     int max_pages, int slice_len, int nslices, int C, int ccap, uint32_t* __restrict__ cand_key,
     int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt, int32_t* __restrict__ sel_idx,
-    int32_t* __restrict__ sel_cnt, int dbg) {
+    int32_t* __restrict__ sel_cnt) {
   constexpr int FS_WAVES = fs_shape<FS_THREADS>::WAVES, FS_SMAX = fs_shape<FS_THREADS>::SMAX;
   constexpr int FS_B0 = fs_shape<FS_THREADS>::B0, FS_BINS = fs_shape<FS_THREADS>::BINS;
   __shared__ __attribute__((aligned(16))) uint32_t keys[FS_SMAX];
@@ -148,7 +148,6 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   }
   __syncthreads();
 
-  if (dbg == 1) return;
   // ---- local top-min(C, n_loc), ascending token order; results are staged in LDS (the page
   //      images are dead by now) and written out with coalesced stores ----
   const int keep = n_loc < C ? n_loc : C;
@@ -180,7 +179,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? src[i] : -1;
     if (tid == 0) sel_cnt[row] = keep;
   } else {
-    if (staged && dbg != 3)
+    if (staged)
       for (int i = tid; i < keep; i += FS_THREADS) {
         cand_key[cbase + i] = o_key[i];
         cand_idx[cbase + i] = o_idx[i];
@@ -243,13 +242,12 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
     cand_cnt = cand_idx + n;
   }
   dim3 grid(pl.nslices, p->n_kv_heads, p->batch);
-  static const int dbg = getenv("AS_DBG") ? atoi(getenv("AS_DBG")) : 0;
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
 #define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
   hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
                      q_hat, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, \
-                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt, dbg)
+                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt)
   if (g_fs_threads == 1024) {
     if (two) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
   } else {
