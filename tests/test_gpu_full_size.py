@@ -1,0 +1,61 @@
+"""Parity at BASELINE's full sizes, in the launch configuration bench.py times: one layer of c3 / c4 / c5 is
+generated on the device, the HIP path runs on the whole batch, and sampled sequences are copied to the host and
+checked against the oracle one by one (selection sets with the tie band, q_hat and attention within 2e-2)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_07486_amd import api
+from paper_2510_07486_amd import workloads as wl
+from gpu_common import SCALE, f32
+from helpers import compare_selection
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,budget,samples", [("c3", 2048, (0, 17, 31)), ("c4", 4096, (3, 15)),
+                                                   ("c5", 1024, (0, 21, 63)), ("c5", 4096, (5, 40))])
+def test_full_size_sampled_sequences(name, budget, samples):
+    print("full-size", name, budget, samples, flush=True)
+    w = wl.scaled(wl.CONFIGS[name], budget=budget, layers=1)
+    inp = wl.make_inputs(w, "cuda")
+    eps = f32(1e-2)
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, inp.max_pages, ridge_eps=eps,
+                        sm_scale=f32(SCALE))
+    ctx = api.Context(p)
+    kv = api.kv_view(inp.k_pool, inp.v_pool, inp.block_table, inp.ctx_lens)
+    s_sel, s_att = torch.cuda.Stream(), torch.cuda.Stream()
+    sel_idx = torch.empty((w.batch, w.n_kv_heads, w.budget), dtype=torch.int32, device="cuda")
+    sel_cnt = torch.empty((w.batch, w.n_kv_heads), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    api.as_select_step(ctx, p, kv, inp.q_win, inp.q_cur, sel_idx, sel_cnt, stream=s_sel)     # selection stream
+    ev = torch.cuda.Event(); ev.record(s_sel)
+    s_att.wait_event(ev)
+    out, lse = api.as_sparse_decode_attn(ctx, p, kv, inp.q_real, sel_idx, sel_cnt, stream=s_att)
+    q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur, stream=s_att)
+    torch.cuda.synchronize()
+    # properties that hold for every row at any size
+    lens = inp.ctx_lens.cpu()
+    cnt = sel_cnt.cpu()
+    assert torch.equal(cnt, torch.clamp(lens, max=w.budget)[:, None].expand(-1, w.n_kv_heads).to(torch.int32))
+    idx = sel_idx.cpu()
+    for b in range(w.batch):
+        c = int(cnt[b, 0])
+        r = idx[b, :, :c]
+        assert (r >= 0).all() and (r < int(lens[b])).all() and (r[:, 1:] > r[:, :-1]).all()
+        assert (idx[b, :, c:] == -1).all()
+    assert torch.isfinite(out.float()).all()
+    swaps_total = 0
+    for b in samples:
+        one = wl.extract_sequence(inp, b)
+        rq, rs, ridx, rcnt = oracle.select_step(one.k_pool, one.block_table, one.ctx_lens, one.q_win, one.q_cur,
+                                                w.budget, eps)
+        assert (q_hat[b].cpu() - rq[0]).abs().max().item() <= 2e-2
+        swaps_total += compare_selection(sel_idx[b:b + 1], sel_cnt[b:b + 1], ridx, rcnt, rs, one.ctx_lens, w.budget)
+        ref, ref_lse = oracle.sparse_decode_attn(one.k_pool, one.v_pool, one.block_table, one.ctx_lens, one.q_real,
+                                                 sel_idx[b:b + 1].cpu(), sel_cnt[b:b + 1].cpu(), f32(SCALE))
+        err = (out[b].cpu().float() - ref[0].float()).abs().max().item()
+        assert err <= 2e-2, (b, err)
+        assert (lse[b].cpu() - ref_lse[0]).abs().max().item() <= 1e-3
+    print(f"  {name}: tie swaps {swaps_total} over {len(samples)} sampled sequences", flush=True)
