@@ -38,7 +38,7 @@ as_status check_params(const as_params* p) {
   if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
   if (p->n_q_heads / p->n_kv_heads > AS_MAX_GROUP) return AS_ERR_UNSUPPORTED;
   if (p->batch > 65535 || p->n_kv_heads > 65535) return AS_ERR_UNSUPPORTED;
-  if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 26) return AS_ERR_UNSUPPORTED;
+  if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 25) return AS_ERR_UNSUPPORTED;
   return AS_OK;
 }
 

@@ -1,48 +1,54 @@
 // Fused key scoring + top-k for one layer-step (Alg. 1 step 7 followed by the cache rank's
-// top-k, Sec. 4.3 items (1)-(2)), without ever writing the per-token scores to HBM.
+// top-k, Sec. 4.3 items (1)-(2)), without ever writing the per-token scores to HBM
+// (interleaving 4 B/token of score writes with the K stream costs about 15 % of the read rate).
 //
-// Each (sequence, KV head) row is cut into slices of at most 8192 tokens.  One 512-thread
-// workgroup streams the slice's K pages (coalesced non-temporal 128-bit loads, transposed
-// through a per-wave 4 KB LDS image into the MFMA operand layout, see score_common.hpp),
-// keeps the 32-bit order-preserving keys of its scores in LDS (32 KB) and accumulates the first
-// radix histogram while it streams.  It then radix-selects its local top-min(C, slice) in LDS
-// and emits them in ascending token order: straight into sel_idx when the row has a single
-// slice, otherwise as (key, index) candidates that a small merge kernel reduces to the row's
-// top-C.  72 KB of LDS per workgroup lets two share a compute unit, so one workgroup's
-// latency-bound phases (table and query fetch, radix select) hide behind the other's streaming.
-// The global top-C is contained in the union of the per-slice top-C, and both levels
-// resolve equal keys to the lowest index, so the result equals a full sort of the row.
-// HBM traffic: one read of K, 8 B per candidate instead of 4 B per token.
+// Each (sequence, KV head) row is cut into shares; one workgroup owns a share and walks it in
+// sub-slices of 4096 (512 threads) or 8192 (1024 threads) tokens.  Per sub-slice it streams
+// the K pages (coalesced non-temporal 128-bit loads, transposed through a per-wave 4 KB LDS
+// image into the MFMA operand layout, see score_common.hpp), keeps the 32-bit order-preserving
+// keys of the scores in LDS and accumulates the first radix histogram while it streams.  Then an
+// exact radix select in LDS over (running set R of the best <= C so far) + (new keys) yields the
+// new R, ascending by token.  After the last sub-slice R goes out: straight into sel_idx when
+// the row has a single share, otherwise as (key, index) candidates that a small merge kernel
+// reduces to the row's top-C.  The top-C of a row is contained in the union of the top-C of its
+// parts and every level resolves equal keys to the lowest index, so the result equals a full
+// sort of the row.  HBM traffic: one read of K plus 8 B per candidate of a multi-share row.
+//
+// Budgets above the running-set capacity (2048 / 4096) use shares of one sub-slice, whose local
+// top-min(C, sub-slice) needs no running set.  The first sub-slice of a long share has a
+// pseudo-random shorter length so that the select phases of the workgroups sharing a compute
+// unit do not coincide and hide behind each other's streaming.
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
 
 namespace asx {
 
-// Two shapes of the slice workgroup: 512 threads / 8192 tokens / 72 KB LDS (two per compute
-// unit) and 1024 threads / 16384 tokens / 144 KB (one per compute unit, half the candidates).
 template <int THREADS> struct fs_shape {
   static constexpr int WAVES = THREADS / 64;
-  static constexpr int SMAX = THREADS * 16;               // tokens per slice (keys: 4 B each)
-  static constexpr int B0 = THREADS == 1024 ? 12 : 11;    // bits of the histogram built while streaming
+  static constexpr int SSUB = THREADS * 8;                // tokens per sub-slice (keys: 4 B each)
+  static constexpr int RCAP = THREADS * 4;                // running-set capacity (key + index)
+  static constexpr int B0 = 11;                           // bits of the histogram built while streaming
   static constexpr int BINS = 1 << B0;
+  static constexpr int SHARE_CAP = THREADS * 32;          // tokens per share (balance of ragged batches)
 };
-static constexpr int FS_MAX_SLICES = 8192;
-static int g_fs_threads = 512;   // development knob
-extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 1024) ? 1024 : 512; }
+static constexpr int FS_MAX_SLICES = 4096;  // shares per row the merge kernel can index (4 per thread)
+static int g_fs_threads = 1024;             // development knob: workgroup shape of the slice kernel
+extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 512) ? 512 : 1024; }
 
-select_plan plan_select(const as_params* p) {
+static select_plan plan_for(const as_params* p, int thr) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  const int smax = g_fs_threads * 16;
-  const int target_wgs = g_fs_threads == 1024 ? 512 : 1024;   // two rounds per compute unit
+  const int ssub = thr * 8, rcap = thr * 4, share_cap = thr * 32;
+  const int target_wgs = thr == 1024 ? 256 : 512;   // one resident set of workgroups
   int64_t st = rows > 0 ? (target_wgs + rows - 1) / rows : 1;
   if (st < 1) st = 1;
   int64_t sl = (max_ctx + st - 1) / st;
   sl = (sl + 63) / 64 * 64;
   if (sl < 256) sl = 256;
-  if (sl > smax) sl = smax;
+  if (sl > share_cap) sl = share_cap;
+  if (p->budget > rcap && sl > ssub) sl = ssub;     // no running set: one sub-slice per share
   pl.slice_len = (int)sl;
   pl.nslices = (int)((max_ctx + sl - 1) / sl);
   if (pl.nslices < 1) pl.nslices = 1;
@@ -50,179 +56,261 @@ select_plan plan_select(const as_params* p) {
   return pl;
 }
 
+select_plan plan_select(const as_params* p) { return plan_for(p, g_fs_threads); }
+
 size_t select_workspace_bytes(const as_params* p) {
-  const select_plan pl = plan_select(p);
-  if (pl.nslices == 1) return 0;
-  const size_t rows = (size_t)p->batch * p->n_kv_heads;
-  return rows * pl.nslices * ((size_t)pl.ccap * 8 + 4);
+  size_t best = 0;  // sized for either workgroup shape
+  for (int thr : {512, 1024}) {
+    const select_plan pl = plan_for(p, thr);
+    if (pl.nslices > 1) {
+      const size_t rows = (size_t)p->batch * p->n_kv_heads;
+      const size_t b = rows * pl.nslices * ((size_t)pl.ccap * 8 + 4);
+      if (b > best) best = b;
+    }
+  }
+  return best;
 }
 
 template <int NSET, int FS_THREADS>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const uint16_t* __restrict__ k_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
-    int max_pages, int slice_len, int nslices, int C, int ccap, uint32_t* __restrict__ cand_key,
+    int max_pages, int share_len, int nshares, int C, int ccap, uint32_t* __restrict__ cand_key,
     int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt, int32_t* __restrict__ sel_idx,
     int32_t* __restrict__ sel_cnt) {
-  constexpr int FS_WAVES = fs_shape<FS_THREADS>::WAVES, FS_SMAX = fs_shape<FS_THREADS>::SMAX;
-  constexpr int FS_B0 = fs_shape<FS_THREADS>::B0, FS_BINS = fs_shape<FS_THREADS>::BINS;
-  __shared__ __attribute__((aligned(16))) uint32_t keys[FS_SMAX];
-  __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images; output staging after streaming
+  using shape = fs_shape<FS_THREADS>;
+  constexpr int FS_WAVES = shape::WAVES, SSUB = shape::SSUB, RCAP = shape::RCAP;
+  constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS;
+  __shared__ __attribute__((aligned(16))) uint32_t keys[SSUB];
+  __shared__ __attribute__((aligned(16))) uint32_t r_key[RCAP];
+  __shared__ int32_t r_idx[RCAP];
+  __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images; selection output between sub-slices
   __shared__ uint32_t hist[FS_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
-  const int b = blockIdx.z, j = blockIdx.y, sl = blockIdx.x;
+  const int b = blockIdx.z, j = blockIdx.y, sh = blockIdx.x;
   const int64_t row = (int64_t)b * Hkv + j;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t = lane & 15, grp = lane >> 4;
   const int N = ctx_lens[b];
-  const int tok0 = sl * slice_len;
-  int n_loc = N - tok0;
-  n_loc = n_loc < 0 ? 0 : (n_loc > slice_len ? slice_len : n_loc);
-  const bool final_out = (nslices == 1);
-  if (n_loc == 0) {
+  const int tok0 = sh * share_len;
+  int n_share = N - tok0;
+  n_share = n_share < 0 ? 0 : (n_share > share_len ? share_len : n_share);
+  const bool final_out = (nshares == 1);
+  if (n_share == 0) {
     if (final_out) {
       for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = -1;
       if (tid == 0) sel_cnt[row] = 0;
     } else if (tid == 0) {
-      cand_cnt[row * nslices + sl] = 0;
+      cand_cnt[row * nshares + sh] = 0;
     }
     return;
   }
-  for (int i = tid; i < FS_BINS; i += FS_THREADS) hist[i] = 0;
 
-  // ---- stream the slice: wave w owns page quads w, w+8, ...; lane l keeps the page id of
-  //      (iteration l>>2, page l&3), one table load per wave for the whole slice ----
-  const int npages_loc = (n_loc + AS_PAGE - 1) / AS_PAGE;
-  const int page0 = tok0 / AS_PAGE;
-  int32_t my_page = 0;
-  {
-    const int lp = ((lane >> 2) * FS_WAVES + wave) * 4 + (lane & 3);
-    if (lp < npages_loc) my_page = block_table[(int64_t)b * max_pages + page0 + lp];
+  // sub-slice schedule: full sub-slices, except a shorter pseudo-random first one in long shares
+  int cur_len = SSUB;
+  if (n_share > SSUB) {
+    const uint32_t wg = (uint32_t)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
+    cur_len = SSUB / 2 + 64 * (int)((wg * 2654435761u >> 16) % (SSUB / 128));
   }
+  const int32_t* bt_row = block_table + (int64_t)b * max_pages + tok0 / AS_PAGE;
+  // lane l keeps the page id of (iteration l>>2, page l&3) of the current sub-slice
+  auto load_pages = [&](int pos, int len) -> int32_t {
+    const int lp = ((lane >> 2) * FS_WAVES + wave) * 4 + (lane & 3);
+    const int npg = (len + AS_PAGE - 1) / AS_PAGE;
+    return lp < npg ? bt_row[pos / AS_PAGE + lp] : 0;
+  };
+  int pos = 0;
+  int n_sub = n_share < cur_len ? n_share : cur_len;
+  int32_t my_page = load_pages(0, n_sub);
+
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
-  __syncthreads();
 
   uint4* st = stage[wave];
-  const int nquads = (npages_loc + 3) / 4;
+  uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);        // [SSUB] pairs fit: SSUB*8 B = stage
+  int32_t* o_idx = reinterpret_cast<int32_t*>(o_key + SSUB);
+  int rn = 0;       // entries of the running set
+  int keep = 0;
 #pragma unroll 1
-  for (int it = 0; wave + FS_WAVES * it < nquads; ++it) {
-    const int q = wave + FS_WAVES * it;
-    uint4 kb[4][4];
+  while (true) {
+    // ---- histogram of the running set, then stream the sub-slice ----
+    for (int i = tid; i < FS_BINS; i += FS_THREADS) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < rn; i += FS_THREADS) atomicAdd(&hist[r_key[i] >> (32 - FS_B0)], 1u);
+    const int npages_sub = (n_sub + AS_PAGE - 1) / AS_PAGE;
+    const int nquads = (npages_sub + 3) / 4;
+#pragma unroll 1
+    for (int it = 0; wave + FS_WAVES * it < nquads; ++it) {
+      const int q = wave + FS_WAVES * it;
+      uint4 kb[4][4];
 #pragma unroll
-    for (int pg = 0; pg < 4; ++pg) {
-      const int32_t page = __shfl(my_page, it * 4 + pg);
-      const uint4* base = reinterpret_cast<const uint4*>(k_pool + chunk_offset(page, Hkv, j));
+      for (int pg = 0; pg < 4; ++pg) {
+        const int32_t page = __shfl(my_page, it * 4 + pg);
+        const uint4* base = reinterpret_cast<const uint4*>(k_pool + chunk_offset(page, Hkv, j));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) kb[pg][i] = ld16<true>(base + i * 64 + lane);
-    }
-    float res[4];
-#pragma unroll
-    for (int pg = 0; pg < 4; ++pg) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st[lds_slot(4 * i + grp, t)] = kb[pg][i];
-      __builtin_amdgcn_wave_barrier();
-      uint4 kk[4];
-#pragma unroll
-      for (int m = 0; m < 4; ++m) kk[m] = st[lds_slot(t, cmap(grp, m))];
-      __builtin_amdgcn_wave_barrier();
-      float v = -INFINITY;
-#pragma unroll
-      for (int s = 0; s < NSET; ++s) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[s][m], __builtin_bit_cast(bf16x8, kk[m]), acc, 0, 0, 0);
-        v = fmaxf(v, fold_rows(acc));
+        for (int i = 0; i < 4; ++i) kb[pg][i] = ld16<true>(base + i * 64 + lane);
       }
-      res[pg] = group_max(v);
-    }
-    const float outv = grp == 0 ? res[0] : grp == 1 ? res[1] : grp == 2 ? res[2] : res[3];
-    const int tl = (q * 4 + grp) * AS_PAGE + t;  // token within the slice
-    if (tl < n_loc) {
-      const uint32_t key = score_key(outv + 0.0f);
-      keys[tl] = key;
-      atomicAdd(&hist[key >> (32 - FS_B0)], 1u);
-    }
-  }
-  __syncthreads();
-
-  // ---- local top-min(C, n_loc), ascending token order; results are staged in LDS (the page
-  //      images are dead by now) and written out with coalesced stores ----
-  const int keep = n_loc < C ? n_loc : C;
-  const int64_t cbase = (row * nslices + sl) * (int64_t)ccap;
-  uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);          // [FS_SMAX / 2]
-  int32_t* o_idx = reinterpret_cast<int32_t*>(o_key + FS_SMAX / 2);      // [FS_SMAX / 2]
-  const bool staged = final_out || keep <= FS_SMAX / 2;
-  auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
-    const uint4 u = (i4 < n_loc) ? *reinterpret_cast<const uint4*>(&keys[i4]) : make_uint4(0, 0, 0, 0);
-    k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
+      float res[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = i4 + e < n_loc;
-  };
-  auto emit = [&](uint32_t pos, int i, uint32_t key) {
-    if (final_out) {
-      reinterpret_cast<int32_t*>(o_key)[pos] = tok0 + i;           // up to FS_SMAX indices
-    } else if (staged) {
-      o_key[pos] = key;
-      o_idx[pos] = tok0 + i;
-    } else {
-      cand_key[cbase + pos] = key;
-      cand_idx[cbase + pos] = tok0 + i;
+      for (int pg = 0; pg < 4; ++pg) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st[lds_slot(4 * i + grp, t)] = kb[pg][i];
+        __builtin_amdgcn_wave_barrier();
+        uint4 kk[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) kk[m] = st[lds_slot(t, cmap(grp, m))];
+        __builtin_amdgcn_wave_barrier();
+        float v = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < NSET; ++s) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int m = 0; m < 4; ++m)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[s][m], __builtin_bit_cast(bf16x8, kk[m]), acc, 0, 0, 0);
+          v = fmaxf(v, fold_rows(acc));
+        }
+        res[pg] = group_max(v);
+      }
+      const float outv = grp == 0 ? res[0] : grp == 1 ? res[1] : grp == 2 ? res[2] : res[3];
+      const int tl = (q * 4 + grp) * AS_PAGE + t;  // token within the sub-slice
+      if (tl < n_sub) {
+        const uint32_t key = score_key(outv + 0.0f);
+        keys[tl] = key;
+        atomicAdd(&hist[key >> (32 - FS_B0)], 1u);
+      }
     }
-  };
-  block_select<FS_THREADS, FS_B0>(n_loc, n_loc, keep, true, key4_of, emit, hist, xch);
-  __syncthreads();
+    // page ids of the next sub-slice travel while this one is selected
+    const int next_pos = pos + n_sub;
+    const int next_len = (n_share - next_pos) < SSUB ? (n_share - next_pos) : SSUB;
+    const bool last = next_pos >= n_share;
+    if (!last) my_page = load_pages(next_pos, next_len);
+    __syncthreads();
+
+    // ---- select the best min(C, rn + n_sub) of (running set, new keys), ascending by token;
+    //      the page images are dead, so the result is staged there ----
+    const int rn4 = (rn + 3) & ~3;
+    const int total = rn + n_sub;
+    keep = total < C ? total : C;
+    auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
+      uint4 u = make_uint4(0, 0, 0, 0);
+      if (i4 < rn4) {
+        u = *reinterpret_cast<const uint4*>(&r_key[i4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = i4 + e < rn;
+      } else {
+        const int jj = i4 - rn4;
+        if (jj < n_sub) u = *reinterpret_cast<const uint4*>(&keys[jj]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = jj + e < n_sub;
+      }
+      k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
+    };
+    auto emit = [&](uint32_t at, int i, uint32_t key) {
+      o_key[at] = key;
+      o_idx[at] = (i < rn4) ? r_idx[i] : tok0 + pos + (i - rn4);
+    };
+    block_select<FS_THREADS, FS_B0>(rn4 + n_sub, total, keep, true, key4_of, emit, hist, xch);
+    __syncthreads();
+    if (last) break;
+    for (int i = tid; i < keep; i += FS_THREADS) {   // keep <= C <= RCAP whenever a share has several sub-slices
+      r_key[i] = o_key[i];
+      r_idx[i] = o_idx[i];
+    }
+    rn = keep;
+    pos = next_pos;
+    n_sub = next_len;
+    __syncthreads();
+  }
+
+  // ---- write out, coalesced ----
   if (final_out) {
-    const int32_t* src = reinterpret_cast<const int32_t*>(o_key);
-    for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? src[i] : -1;
+    for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? o_idx[i] : -1;
     if (tid == 0) sel_cnt[row] = keep;
   } else {
-    if (staged)
-      for (int i = tid; i < keep; i += FS_THREADS) {
-        cand_key[cbase + i] = o_key[i];
-        cand_idx[cbase + i] = o_idx[i];
-      }
-    if (tid == 0) cand_cnt[row * nslices + sl] = keep;
+    const int64_t cbase = (row * nshares + sh) * (int64_t)ccap;
+    for (int i = tid; i < keep; i += FS_THREADS) {
+      cand_key[cbase + i] = o_key[i];
+      cand_idx[cbase + i] = o_idx[i];
+    }
+    if (tid == 0) cand_cnt[row * nshares + sh] = keep;
   }
 }
 
 // Reduces a row's per-slice candidates (ascending token order within and across slices) to
-// its top-C, again ascending and with ties to the lowest index.
+// its top-C, again ascending and with ties to the lowest index.  Rows with at most
+// MG_LDS candidates are first compacted into LDS (one read of the candidates); larger rows
+// run the same selection over the global arrays.
+static constexpr int MG_LDS = 12288;  // (key, index) pairs: 96 KB
+
 __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t* __restrict__ cand_key,
                                                                   const int32_t* __restrict__ cand_idx,
                                                                   const int32_t* __restrict__ cand_cnt, int nslices,
                                                                   int ccap, int C, int32_t* __restrict__ sel_idx,
                                                                   int32_t* __restrict__ sel_cnt) {
   __shared__ int32_t cnt_sh[FS_MAX_SLICES];
+  __shared__ int32_t pre_sh[FS_MAX_SLICES];
+  __shared__ __attribute__((aligned(16))) uint32_t lkey[MG_LDS];
+  __shared__ int32_t lidx[MG_LDS];
   __shared__ uint32_t hist[TK_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
-  __shared__ int total_sh;
   const int64_t row = blockIdx.x;
-  const int tid = threadIdx.x;
-  if (tid == 0) total_sh = 0;
-  __syncthreads();
-  int mine = 0;
-  for (int s = tid; s < nslices; s += TK_THREADS) {
-    const int c = cand_cnt[row * nslices + s];
-    cnt_sh[s] = c;
-    mine += c;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // counts and their exclusive prefix over slices: a thread owns 4 consecutive slices
+  uint32_t c4[4], mine = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int sl = 4 * tid + e;
+    c4[e] = sl < nslices ? (uint32_t)cand_cnt[row * nslices + sl] : 0u;
+    mine += c4[e];
   }
-  for (int o = 32; o >= 1; o >>= 1) mine += __shfl_xor(mine, o);
-  if ((tid & 63) == 0 && mine) atomicAdd(&total_sh, mine);
+  const uint32_t inc = wave_incl_scan(mine);
+  if (lane == 63) xch[wave] = inc;
   __syncthreads();
-  const int total = total_sh;
+  uint32_t woff[1];
+  const int total = (int)seg_wave_offsets<TK_THREADS / 64, 1>(xch, wave, woff);
+  uint32_t run = woff[0] + inc - mine;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int sl = 4 * tid + e;
+    if (sl < nslices) {
+      cnt_sh[sl] = (int32_t)c4[e];
+      pre_sh[sl] = (int32_t)run;
+    }
+    run += c4[e];
+  }
+  __syncthreads();
   const int keep = total < C ? total : C;
   const int64_t cbase = row * nslices * (int64_t)ccap;
-  auto key_of = [&](int v, bool& valid) -> uint32_t {
-    valid = (v % ccap) < cnt_sh[v / ccap];
-    return valid ? cand_key[cbase + v] : 0u;
-  };
-  auto emit = [&](uint32_t pos, int v, uint32_t) { sel_idx[row * C + pos] = cand_idx[cbase + v]; };
-  if (keep > 0)
-    block_select<TK_THREADS, 12>(nslices * ccap, total, keep, false, key4_from_scalar(nslices * ccap, key_of), emit, hist,
-                                 xch);
+  const int nvirt = nslices * ccap;
+  if (keep > 0) {
+    if (total <= MG_LDS) {
+      for (int v = tid; v < nvirt; v += TK_THREADS) {
+        const int sl = v / ccap, i = v - sl * ccap;
+        if (i < cnt_sh[sl]) {
+          const int pos = pre_sh[sl] + i;
+          lkey[pos] = cand_key[cbase + v];
+          lidx[pos] = cand_idx[cbase + v];
+        }
+      }
+      __syncthreads();
+      auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
+        const uint4 u = (i4 < total) ? *reinterpret_cast<const uint4*>(&lkey[i4]) : make_uint4(0, 0, 0, 0);
+        k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = i4 + e < total;
+      };
+      auto emit = [&](uint32_t pos, int i, uint32_t) { sel_idx[row * C + pos] = lidx[i]; };
+      block_select<TK_THREADS, 12>(total, total, keep, false, key4_of, emit, hist, xch);
+    } else {
+      auto key_of = [&](int v, bool& valid) -> uint32_t {
+        valid = (v % ccap) < cnt_sh[v / ccap];
+        return valid ? cand_key[cbase + v] : 0u;
+      };
+      auto emit = [&](uint32_t pos, int v, uint32_t) { sel_idx[row * C + pos] = cand_idx[cbase + v]; };
+      block_select<TK_THREADS, 12>(nvirt, total, keep, false, key4_from_scalar(nvirt, key_of), emit, hist, xch);
+    }
+  }
   for (int i = keep + tid; i < C; i += TK_THREADS) sel_idx[row * C + i] = -1;
   if (tid == 0) sel_cnt[row] = keep;
 }
