@@ -18,6 +18,7 @@
 // top-min(C, sub-slice) needs no running set.  The first sub-slice of a long share has a
 // pseudo-random shorter length so that the select phases of the workgroups sharing a compute
 // unit do not coincide and hide behind each other's streaming.
+#include <cstdlib>
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
@@ -40,8 +41,9 @@ static select_plan plan_for(const as_params* p, int thr) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  const int ssub = thr * 8, rcap = thr * 4, share_cap = thr * 32;
-  const int target_wgs = thr == 1024 ? 256 : 512;   // one resident set of workgroups
+  const int ssub = thr * 8, rcap = thr * 4;
+  const int share_cap = getenv("AS_SHARE_CAP") ? atoi(getenv("AS_SHARE_CAP")) : thr * 32;
+  const int target_wgs = getenv("AS_TARGET_WGS") ? atoi(getenv("AS_TARGET_WGS")) : (thr == 1024 ? 256 : 512);
   int64_t st = rows > 0 ? (target_wgs + rows - 1) / rows : 1;
   if (st < 1) st = 1;
   int64_t sl = (max_ctx + st - 1) / st;
@@ -88,10 +90,32 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   __shared__ uint32_t hist[FS_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
-  const int b = blockIdx.z, j = blockIdx.y, sh = blockIdx.x;
-  const int64_t row = (int64_t)b * Hkv + j;
+  // Grid = (KV head, batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
+  // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
+  // sequences (the share) must vary slowest, or the workgroups that do have work pile up on half
+  // of the compute units.
+  const int j = blockIdx.x, sh = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t = lane & 15, grp = lane >> 4;
+  // Longest sequences first: workgroups are dispatched in blockIdx order, so the y-th dispatched
+  // batch slot takes the sequence of length rank y (ties by index) and the short ones fill the tail.
+  int b = blockIdx.y;
+  const int B = gridDim.y;
+  if (B > 1 && B <= SSUB) {
+    int32_t* lens = reinterpret_cast<int32_t*>(keys);
+    for (int i = tid; i < B; i += FS_THREADS) lens[i] = ctx_lens[i];
+    __syncthreads();
+    for (int u = tid; u < B; u += FS_THREADS) {
+      const int lu = lens[u];
+      int rank = 0;
+      for (int v = 0; v < B; ++v) rank += (lens[v] > lu) || (lens[v] == lu && v < u);
+      if (rank == (int)blockIdx.y) xch[0] = (uint32_t)u;
+    }
+    __syncthreads();
+    b = (int)xch[0];
+    __syncthreads();
+  }
+  const int64_t row = (int64_t)b * Hkv + j;
   const int N = ctx_lens[b];
   const int tok0 = sh * share_len;
   int n_share = N - tok0;
@@ -329,7 +353,7 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
     cand_idx = reinterpret_cast<int32_t*>(cand_key + n);
     cand_cnt = cand_idx + n;
   }
-  dim3 grid(pl.nslices, p->n_kv_heads, p->batch);
+  dim3 grid(p->n_kv_heads, p->batch, pl.nslices);
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
 #define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
