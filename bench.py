@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--cpu-sample-seqs", type=int, default=4)
     ap.add_argument("--serial-only", action="store_true")
     ap.add_argument("--sel-streams", type=int, default=2, help="selection streams (layers round-robin over them)")
+    ap.add_argument("--slice-threads", type=int, default=0, help="development: 512 or 1024-thread selection workgroups")
     ap.add_argument("--unfused", action="store_true", help="score and top-k as separate kernels through HBM scores")
     return ap.parse_args()
 
@@ -57,6 +58,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     api.lib()                                       # fails loudly if the HIP library is not built
+    if a.slice_threads:
+        api.lib().as_debug_set_slice_threads(a.slice_threads)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
 

@@ -33,6 +33,7 @@ template <int THREADS> struct fs_shape {
   static constexpr int BINS = 1 << B0;
   static constexpr int SHARE_CAP = THREADS * 32;          // tokens per share (balance of ragged batches)
 };
+static constexpr int FS_PG = 2;             // pages a wave loads per iteration (8 KB in flight per wave)
 static constexpr int FS_MAX_SLICES = 4096;  // shares per row the merge kernel can index (4 per thread)
 static int g_fs_threads = 1024;             // development knob: workgroup shape of the slice kernel
 extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 512) ? 512 : 1024; }
@@ -73,7 +74,7 @@ size_t select_workspace_bytes(const as_params* p) {
   return best;
 }
 
-template <int NSET, int FS_THREADS>
+template <int NSET, int FS_THREADS, int PG>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const uint16_t* __restrict__ k_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
@@ -138,9 +139,9 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     cur_len = SSUB / 2 + 64 * (int)((wg * 2654435761u >> 16) % (SSUB / 128));
   }
   const int32_t* bt_row = block_table + (int64_t)b * max_pages + tok0 / AS_PAGE;
-  // lane l keeps the page id of (iteration l>>2, page l&3) of the current sub-slice
+  // lane l keeps the page id of (iteration l / PG, page l % PG) of the current sub-slice
   auto load_pages = [&](int pos, int len) -> int32_t {
-    const int lp = ((lane >> 2) * FS_WAVES + wave) * 4 + (lane & 3);
+    const int lp = ((lane / PG) * FS_WAVES + wave) * PG + (lane % PG);
     const int npg = (len + AS_PAGE - 1) / AS_PAGE;
     return lp < npg ? bt_row[pos / AS_PAGE + lp] : 0;
   };
@@ -163,21 +164,21 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     __syncthreads();
     for (int i = tid; i < rn; i += FS_THREADS) atomicAdd(&hist[r_key[i] >> (32 - FS_B0)], 1u);
     const int npages_sub = (n_sub + AS_PAGE - 1) / AS_PAGE;
-    const int nquads = (npages_sub + 3) / 4;
+    const int ngroups = (npages_sub + PG - 1) / PG;   // a wave takes PG pages per iteration
 #pragma unroll 1
-    for (int it = 0; wave + FS_WAVES * it < nquads; ++it) {
+    for (int it = 0; wave + FS_WAVES * it < ngroups; ++it) {
       const int q = wave + FS_WAVES * it;
-      uint4 kb[4][4];
+      uint4 kb[PG][4];
 #pragma unroll
-      for (int pg = 0; pg < 4; ++pg) {
-        const int32_t page = __shfl(my_page, it * 4 + pg);
+      for (int pg = 0; pg < PG; ++pg) {
+        const int32_t page = __shfl(my_page, it * PG + pg);
         const uint4* base = reinterpret_cast<const uint4*>(k_pool + chunk_offset(page, Hkv, j));
 #pragma unroll
         for (int i = 0; i < 4; ++i) kb[pg][i] = ld16<true>(base + i * 64 + lane);
       }
-      float res[4];
+      float res[PG];
 #pragma unroll
-      for (int pg = 0; pg < 4; ++pg) {
+      for (int pg = 0; pg < PG; ++pg) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) st[lds_slot(4 * i + grp, t)] = kb[pg][i];
         __builtin_amdgcn_wave_barrier();
@@ -196,9 +197,11 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
         }
         res[pg] = group_max(v);
       }
-      const float outv = grp == 0 ? res[0] : grp == 1 ? res[1] : grp == 2 ? res[2] : res[3];
-      const int tl = (q * 4 + grp) * AS_PAGE + t;  // token within the sub-slice
-      if (tl < n_sub) {
+      float outv = res[0];
+#pragma unroll
+      for (int pg = 1; pg < PG; ++pg) outv = grp == pg ? res[pg] : outv;
+      const int tl = (q * PG + grp) * AS_PAGE + t;  // token within the sub-slice
+      if (grp < PG && tl < n_sub) {
         const uint32_t key = score_key(outv + 0.0f);
         keys[tl] = key;
         atomicAdd(&hist[key >> (32 - FS_B0)], 1u);
@@ -357,7 +360,7 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
 #define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
                      q_hat, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, \
                      p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt)
   if (g_fs_threads == 1024) {
