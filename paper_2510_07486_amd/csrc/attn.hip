@@ -3,25 +3,30 @@
 // selection was made.
 //
 // HBM-bound on the index-gathered K and V rows (2 x 256 B per selected token and KV head).
-// Split-C: a 256-thread workgroup owns 128-token chunks of the logical token list of one
-// (sequence, KV head) and up to 8 of the group's query heads, so every gathered row is read
-// once for the whole group.  The dependent chain index -> page id -> row address is walked
-// once per chunk with one lane per token (three memory round trips in all); then a 16-lane
-// row of the wavefront reads one 256-byte K / V row with non-temporal 128-bit loads, 16 loads
-// in flight per lane.  Q.K uses v_dot2c_f32_bf16 and a DPP rotate all-reduce inside the row;
-// logits go to LDS, the chunk max and p = exp(l - m) follow, then P.V with no rescaling inside
-// the chunk.  Each workgroup writes its partial (m, l, o); a small second kernel merges them
-// and writes bf16.
+// Split-C: a 256-thread workgroup owns a split (a few hundred tokens, chosen so that about six
+// workgroups per compute unit exist) of the logical token list of one (sequence, KV head) and up
+// to 8 of the group's query heads, so every gathered row is read once for the whole group; it
+// walks the split in 64-token inner chunks with an online softmax across chunks.  The dependent
+// chain index -> page id -> row address is resolved for four chunks at a time with one lane per
+// token, speculatively and one step ahead, so it is off the critical path; a 16-lane row of the
+// wavefront reads one 256-byte K / V row with non-temporal 128-bit loads.  Q.K uses
+// v_dot2c_f32_bf16 and a DPP rotate all-reduce inside the row; logits go to LDS, the chunk max and
+// p = exp(l - m) follow, then P.V with no rescaling inside the chunk.  Each workgroup writes its
+// partial (m, l, o); a small second kernel merges them and writes bf16.  (Measured and rejected: a
+// barrier-free variant with one online softmax per 16-lane row, 40 % slower from register
+// pressure; a "last workgroup merges" variant, 8x slower from device-scope fences.)
 #include "common.hpp"
 
 namespace asx {
 
-static constexpr int AT_CHUNK = AS_ATTN_CHUNK;  // 128 tokens: 4 waves x 8 loads x 4 rows
+static constexpr int AT_SPLIT = AS_ATTN_CHUNK;  // smallest workgroup split, tokens (sizes the workspace)
+static constexpr int AT_IT = 4;                 // row loads per lane and inner chunk (K and V each)
+static constexpr int AT_CHUNK = 4 * AT_IT * 4;  // inner chunk: 4 waves x AT_IT loads x 4 rows = 64 tokens
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-__host__ __device__ inline int attn_nsplit(int C) { return (C + AT_CHUNK - 1) / AT_CHUNK + 1; }
+__host__ __device__ inline int attn_nsplit(int C) { return (C + AT_SPLIT - 1) / AT_SPLIT + 1; }
 static inline int attn_gh(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 
 // partial outputs and partial (m, l) pairs
@@ -60,7 +65,8 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
     const uint16_t* __restrict__ k_pool, const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
-    float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit) {
+    float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit,
+    int cps /* inner chunks per split */) {
   __shared__ float lg[GH][AT_CHUNK];         // logits, then probabilities
   __shared__ float sc_sh[GH];                // rescale factor of the running accumulator
   __shared__ float red[4][GH][AS_HEAD_DIM];  // per-wave partial outputs
@@ -73,6 +79,14 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int slot = lane >> 4, c = lane & 15;
 
+  const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
+  // lane l resolves token (l & 15) of this wave's share of inner chunk (first + (l >> 4)): four chunks at once
+  auto fetch_index = [&](int ck_first) -> int {
+    const int ti = (ck_first + (lane >> 4)) * AT_CHUNK + w * (AT_IT * 4) + (lane & 15);
+    return (ti < C) ? idx_row[ti] : 0;
+  };
+  const int raw_first = fetch_index(split * cps);  // speculative: validated once the lengths are known
+
   const int N = ctx_lens[b];
   int cnt = sel_cnt[b * Hkv + j];
   cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
@@ -80,8 +94,8 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);
   const int nchunks = (L + AT_CHUNK - 1) / AT_CHUNK;
-  const int ck_begin = split;
-  const int ck_end = (split == nsplit - 1) ? nchunks : (split + 1 < nchunks ? split + 1 : nchunks);
+  const int ck_begin = split * cps;
+  const int ck_end = (split == nsplit - 1) ? nchunks : ((split + 1) * cps < nchunks ? (split + 1) * cps : nchunks);
 
   const int64_t pbase = ((int64_t)b * Hq + h0) * nsplit + split;  // + g * nsplit per head
   if (ck_begin >= ck_end) {                                       // nothing here: mark empty
@@ -105,33 +119,44 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
     // running softmax stats of head g live in wave (g & 3), slot g >> 2 (all lanes alike)
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 
-    const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
     const int32_t* bt_row = block_table + (int64_t)b * max_pages;
 
+    // Addresses of four inner chunks are resolved together, one lane per token.  The index load does
+    // not wait for the lengths (any slot below C is readable; it is validated afterwards) and the
+    // next four chunks are resolved while the current ones are processed, so after the first chunk
+    // the chain index -> page id -> row address is off the critical path.
+    auto page_of = [&](int ck_first, int raw) -> uint32_t {
+      const int ti = (ck_first + (lane >> 4)) * AT_CHUNK + w * (AT_IT * 4) + (lane & 15);
+      int n = 0;
+      if (ti < L) n = (ti < cnt) ? raw : tail0 + (ti - cnt);
+      n = n < 0 ? 0 : (n >= N ? N - 1 : n);  // keeps a bad index inside the sequence's pages
+      return ((uint32_t)bt_row[n >> 4] << 4) | (uint32_t)(n & 15);  // page id << 4 | slot in page
+    };
+    uint32_t my_pk = page_of(ck_begin, raw_first);
 #pragma unroll 1
-    for (int ck = ck_begin; ck < ck_end; ++ck) {
-      // ---- addresses: lane l (< 32) resolves token l of this wave's 32 ----
-      const int tw0 = ck * AT_CHUNK + w * 32;
-      uint32_t my_pk = 0;  // page id << 4 | slot in page
-      {
-        const int ti = tw0 + (lane & 31);
-        int n = 0;
-        if (ti < L) n = (ti < cnt) ? idx_row[ti] : tail0 + (ti - cnt);
-        n = n < 0 ? 0 : (n >= N ? N - 1 : n);  // keeps a bad index inside the sequence's pages
-        my_pk = ((uint32_t)bt_row[n >> 4] << 4) | (uint32_t)(n & 15);
-      }
-      // ---- all 16 row loads of this lane (8 K, 8 V) ----
-      uint4 kreg[8], vreg[8];
+    for (int ck0 = ck_begin; ck0 < ck_end; ck0 += 4) {
+      const bool more = ck0 + 4 < ck_end;
+      int raw_next = 0;
+      if (more) raw_next = fetch_index(ck0 + 4);
+      uint32_t pk_next = 0;
+#pragma unroll 1
+      for (int cc = 0; cc < 4; ++cc) {
+      const int ck = ck0 + cc;
+      if (ck >= ck_end) break;
+      if (cc == 1 && more) pk_next = page_of(ck0 + 4, raw_next);
+      const int tw0 = ck * AT_CHUNK + w * (AT_IT * 4);
+      // ---- all row loads of this lane (AT_IT K, AT_IT V) ----
+      uint4 kreg[AT_IT], vreg[AT_IT];
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const uint32_t pk = __shfl(my_pk, it * 4 + slot);
+      for (int it = 0; it < AT_IT; ++it) {
+        const uint32_t pk = __shfl(my_pk, cc * 16 + it * 4 + slot);
         const int64_t off = chunk_offset((int32_t)(pk >> 4), Hkv, j) + (int64_t)(pk & 15) * AS_HEAD_DIM + c * 8;
         kreg[it] = ld16_nt(k_pool + off);
         vreg[it] = ld16_nt(v_pool + off);
       }
       // ---- phase 1: logits ----
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
+      for (int it = 0; it < AT_IT; ++it) {
         const bool valid = tw0 + it * 4 + slot < L;
         float mine = 0.f;
 #pragma unroll
@@ -143,7 +168,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
           s = row16_allsum(s);
           if (c == g) mine = s;
         }
-        if (c < GH) lg[c][w * 32 + it * 4 + slot] = valid ? mine * sm_scale : -INFINITY;
+        if (c < GH) lg[c][w * (AT_IT * 4) + it * 4 + slot] = valid ? mine * sm_scale : -INFINITY;
       }
       __syncthreads();
       // ---- phase 1b: chunk max, probabilities, running stats (wave w owns heads w, w+4) ----
@@ -151,14 +176,13 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
       for (int k = 0; k < 2; ++k) {
         const int g = w + 4 * k;
         if (g < GH) {
-          const float x0 = lg[g][lane], x1 = lg[g][lane + 64];
-          const float mx = wave_max(fmaxf(x0, x1));
+          const float x0 = lg[g][lane];
+          const float mx = wave_max(x0);
           const float m_new = fmaxf(m_run[k], mx);  // finite: the chunk holds >= 1 valid token
           const float scl = (m_run[k] == -INFINITY) ? 0.f : expf(m_run[k] - m_new);
-          const float p0 = expf(x0 - m_new), p1 = expf(x1 - m_new);
+          const float p0 = expf(x0 - m_new);
           lg[g][lane] = p0;
-          lg[g][lane + 64] = p1;
-          const float ps = wave_sum(p0 + p1);
+          const float ps = wave_sum(p0);
           l_run[k] = l_run[k] * scl + ps;
           m_run[k] = m_new;
           if (lane == 0) sc_sh[g] = scl;
@@ -173,18 +197,20 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
         for (int e = 0; e < 8; ++e) acc[g][e] *= scl;
       }
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
+      for (int it = 0; it < AT_IT; ++it) {
         const uint4 vu = vreg[it];
         float vf[8] = {bf16lo(vu.x), bf16hi(vu.x), bf16lo(vu.y), bf16hi(vu.y),
                        bf16lo(vu.z), bf16hi(vu.z), bf16lo(vu.w), bf16hi(vu.w)};
 #pragma unroll
         for (int g = 0; g < GH; ++g) {
-          const float pr = lg[g][w * 32 + it * 4 + slot];
+          const float pr = lg[g][w * (AT_IT * 4) + it * 4 + slot];
 #pragma unroll
           for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pr, vf[e], acc[g][e]);
         }
       }
       __syncthreads();
+      }
+      my_pk = pk_next;
     }
 
     // ---- reduce the 4 slots of a wave, then the 4 waves ----
@@ -247,13 +273,13 @@ __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* 
 template <int GH>
 static hipError_t launch_attn_gh(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                                  const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                                 int nsplit, hipStream_t s) {
+                                 int nsplit, int cps, hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
   dim3 grid(nsplit, p->n_kv_heads * (G / GH), p->batch);
   hipLaunchKernelGGL(attn_split_kernel<GH>, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
                      sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, p->budget, p->max_pages_per_seq,
-                     p->sm_scale, nsplit);
+                     p->sm_scale, nsplit, cps);
   return hipGetLastError();
 }
 
@@ -262,16 +288,27 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
                        hipStream_t s) {
   const int64_t heads = (int64_t)p->batch * p->n_q_heads;
   if (heads == 0) return hipSuccess;
-  const int nsplit = attn_nsplit(p->budget);
+  const int G = p->n_q_heads / p->n_kv_heads;
+  // split size: about six workgroups per compute unit, so that per-split costs (partials through HBM,
+  // query fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens
+  const int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (G / attn_gh(G));
+  int64_t nsel = (1536 + pairs - 1) / pairs;
+  const int64_t max_sel = (p->budget + AT_SPLIT - 1) / AT_SPLIT;
+  if (nsel > max_sel) nsel = max_sel;
+  if (nsel < 1) nsel = 1;
+  int split_tokens = (int)((p->budget + nsel - 1) / nsel);
+  split_tokens = (split_tokens + AT_CHUNK - 1) / AT_CHUNK * AT_CHUNK;
+  if (split_tokens < AT_SPLIT) split_tokens = AT_SPLIT;
+  const int cps = split_tokens / AT_CHUNK;
+  const int nsplit = (p->budget + split_tokens - 1) / split_tokens + 1;   // <= attn_nsplit(budget)
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
-  const int G = p->n_q_heads / p->n_kv_heads;
   hipError_t e;
   switch (attn_gh(G)) {
-    case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, s); break;
-    case 4: e = launch_attn_gh<4>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, s); break;
-    case 2: e = launch_attn_gh<2>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, s); break;
-    default: e = launch_attn_gh<1>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, s); break;
+    case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+    case 4: e = launch_attn_gh<4>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+    case 2: e = launch_attn_gh<2>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+    default: e = launch_attn_gh<1>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
   }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)heads), dim3(AS_HEAD_DIM), 0, s, part_o, part_ml, out, lse,
