@@ -131,10 +131,175 @@ __global__ __launch_bounds__(64) void predict_kernel(const uint16_t* __restrict_
   }
 }
 
+// Window sizes known at compile time (the paper profiles W = 16): the same algorithm with the
+// Cholesky row, the forward-solve residual and the back-substituted weights of a lane held in
+// registers, all LDS operands at static addresses (broadcast reads the compiler can pipeline),
+// divisions replaced by one reciprocal per diagonal element, and the W(W+1)/2 softmax
+// exponentials spread over the 64 lanes instead of W sequential ones per lane.
+template <int W>
+__global__ __launch_bounds__(64) void predict_kernel_w(const uint16_t* __restrict__ q_win,
+                                                       const uint16_t* __restrict__ q_cur,
+                                                       float* __restrict__ q_hat, double eps, double beta) {
+  __shared__ float Rf[(W + 1) * RS];   // row i < W = Q_{t-1-i}, row W = Q_t
+  __shared__ double A[W][W + 1];       // Gram, then the Cholesky factor L
+  __shared__ double Om[W][W + 1];      // row k-1: beta*omega^{(k)} - max, then exp of it
+  __shared__ double colb[W], diag[W];  // broadcast of the current Cholesky column and pivot
+  __shared__ double bv[W], yv[W], invd[W], zinv[W], av[W];
+
+  const int lane = threadIdx.x;
+  const int r = lane;
+  const int64_t bh = blockIdx.x;
+  const uint32_t* win = reinterpret_cast<const uint32_t*>(q_win + bh * (int64_t)W * AS_HEAD_DIM);
+  const uint32_t* cur = reinterpret_cast<const uint32_t*>(q_cur + bh * (int64_t)AS_HEAD_DIM);
+#pragma unroll
+  for (int i = 0; i < W; ++i) {
+    const uint32_t w2 = win[(int64_t)(W - 1 - i) * (AS_HEAD_DIM / 2) + lane];
+    Rf[i * RS + 2 * lane] = bf16lo(w2);
+    Rf[i * RS + 2 * lane + 1] = bf16hi(w2);
+  }
+  {
+    const uint32_t w2 = cur[lane];
+    Rf[W * RS + 2 * lane] = bf16lo(w2);
+    Rf[W * RS + 2 * lane + 1] = bf16hi(w2);
+  }
+  __syncthreads();
+
+  // Gram matrix (+ eps on the diagonal) and rhs, one (i, j) pair per lane and round
+  constexpr int NPAIRS = (W + 1) * (W + 2) / 2;
+  for (int p = lane; p < NPAIRS; p += 64) {
+    int i = (int)((sqrtf(8.0f * (float)p + 1.0f) - 1.0f) * 0.5f);
+    while (i * (i + 1) / 2 > p) --i;
+    while ((i + 1) * (i + 2) / 2 <= p) ++i;
+    const int j = p - i * (i + 1) / 2;
+    const float* ri = Rf + i * RS;
+    const float* rj = Rf + j * RS;
+    double s0 = 0.0, s1 = 0.0;
+#pragma unroll 8
+    for (int d = 0; d < AS_HEAD_DIM; d += 2) {
+      s0 += (double)ri[d] * (double)rj[d];
+      s1 += (double)ri[d + 1] * (double)rj[d + 1];
+    }
+    const double s = s0 + s1;
+    if (i < W) A[i][j] = s + (i == j ? eps : 0.0);
+    else if (j < W) bv[j] = s;
+  }
+  __syncthreads();
+
+  // Cholesky with row r in registers; column j is broadcast through LDS
+  double a[W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) a[k] = (r < W && k <= r) ? A[r][k] : 0.0;
+#pragma unroll
+  for (int j = 0; j < W; ++j) {
+    if (r == j) diag[j] = a[j];                 // final by now: all earlier columns are folded in
+    __syncthreads();
+    const double djj = sqrt(diag[j]);
+    const double lij = a[j] / djj;              // meaningful for r > j
+    if (r == j) a[j] = djj;
+    if (r > j && r < W) {
+      a[j] = lij;
+      colb[r] = lij;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = j + 1; k < W; ++k)
+      if (k <= r && r < W) a[k] -= lij * colb[k];
+    // colb is next written after the first barrier of step j+1, which every lane passes only
+    // after these reads
+  }
+  __syncthreads();
+  if (r < W) {
+#pragma unroll
+    for (int k = 0; k < W; ++k)
+      if (k <= r) A[r][k] = a[k];
+    double dd = 1.0;
+#pragma unroll
+    for (int k = 0; k < W; ++k)
+      if (k == r) dd = a[k];
+    invd[r] = 1.0 / dd;
+  }
+  __syncthreads();
+
+  // forward solve y = L^-1 b
+  {
+    double rr = (r < W) ? bv[r] : 0.0;
+    double y = 0.0;
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+      const double yj = __shfl(rr, j) * invd[j];
+      if (r == j) y = yj;
+      if (r > j) rr -= a[j] * yj;
+    }
+    if (r < W) yv[r] = y;
+  }
+  __syncthreads();
+
+  // lane kk: L_k^T omega = y_{1:k} for k = kk+1, weights stay zero above kk
+  double om[W];
+#pragma unroll
+  for (int i = 0; i < W; ++i) om[i] = 0.0;
+#pragma unroll
+  for (int i = W - 1; i >= 0; --i) {
+    double s = yv[i];
+#pragma unroll
+    for (int m = i + 1; m < W; ++m) s -= A[m][i] * om[m];
+    om[i] = (i <= r) ? s * invd[i] : 0.0;
+  }
+  if (r < W) {
+    double mx = beta * om[0];
+#pragma unroll
+    for (int i = 1; i < W; ++i)
+      if (i <= r) mx = fmax(mx, beta * om[i]);
+#pragma unroll
+    for (int i = 0; i < W; ++i) Om[r][i] = beta * om[i] - mx;
+  }
+  __syncthreads();
+  // exponentials of the W(W+1)/2 (k, i) pairs, spread over the lanes
+  for (int p = lane; p < W * (W + 1) / 2; p += 64) {
+    int k = (int)((sqrtf(8.0f * (float)p + 1.0f) - 1.0f) * 0.5f);
+    while (k * (k + 1) / 2 > p) --k;
+    while ((k + 1) * (k + 2) / 2 <= p) ++k;
+    const int i = p - k * (k + 1) / 2;
+    Om[k][i] = exp(Om[k][i]);
+  }
+  __syncthreads();
+  if (r < W) {
+    double z = 0.0;
+#pragma unroll
+    for (int i = 0; i < W; ++i)
+      if (i <= r) z += Om[r][i];
+    zinv[r] = 1.0 / z;
+  }
+  __syncthreads();
+  if (r < W) {
+    double acc = 0.0;
+#pragma unroll
+    for (int kk = 0; kk < W; ++kk)
+      if (kk >= r) acc += Om[kk][r] * zinv[kk];
+    av[r] = acc / (double)W;
+  }
+  __syncthreads();
+  for (int d = lane; d < AS_HEAD_DIM; d += 64) {
+    double acc = av[0] * (double)Rf[W * RS + d];
+#pragma unroll
+    for (int i = 1; i < W; ++i) acc += av[i] * (double)Rf[(i - 1) * RS + d];
+    q_hat[bh * AS_HEAD_DIM + d] = (float)acc;
+  }
+}
+
 hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
                           hipStream_t s) {
   const int64_t heads = (int64_t)p->batch * p->n_q_heads;
   if (heads == 0) return hipSuccess;
+  if (p->window == 16 || p->window == 8) {
+    if (p->window == 16)
+      hipLaunchKernelGGL(predict_kernel_w<16>, dim3((unsigned)heads), dim3(64), 0, s, q_win, q_cur, q_hat,
+                         (double)p->ridge_eps, (double)p->softmax_beta);
+    else
+      hipLaunchKernelGGL(predict_kernel_w<8>, dim3((unsigned)heads), dim3(64), 0, s, q_win, q_cur, q_hat,
+                         (double)p->ridge_eps, (double)p->softmax_beta);
+    return hipGetLastError();
+  }
   size_t lds = predict_lds_bytes(p->window);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(predict_kernel),
