@@ -18,7 +18,6 @@
 // top-min(C, sub-slice) needs no running set.  The first sub-slice of a long share has a
 // pseudo-random shorter length so that the select phases of the workgroups sharing a compute
 // unit do not coincide and hide behind each other's streaming.
-#include <cstdlib>
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
@@ -38,22 +37,64 @@ static constexpr int FS_MAX_SLICES = 4096;  // shares per row the merge kernel c
 static int g_fs_threads = 1024;             // development knob: workgroup shape of the slice kernel
 extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 512) ? 512 : 1024; }
 
+static int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+// Picks how many shares a row is cut into with a small cost model (microseconds), evaluated for
+// the longest context the block table allows.  Workgroups run in rounds of one resident set;
+// a full round streams at the chip's rate (HBM-bound, T_SHARED per token and workgroup), a
+// partly filled last round at the rate one compute unit can pull alone (T_ALONE).  Every share
+// pays a fixed start-up, one LDS select per sub-slice and, when a row has several shares, its
+// candidates through HBM plus the merge kernel.  Constants are measured on MI355X.
 static select_plan plan_for(const as_params* p, int thr) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  const int ssub = thr * 8, rcap = thr * 4;
-  const int share_cap = getenv("AS_SHARE_CAP") ? atoi(getenv("AS_SHARE_CAP")) : thr * 32;
-  const int target_wgs = getenv("AS_TARGET_WGS") ? atoi(getenv("AS_TARGET_WGS")) : (thr == 1024 ? 256 : 512);
-  int64_t st = rows > 0 ? (target_wgs + rows - 1) / rows : 1;
-  if (st < 1) st = 1;
-  int64_t sl = (max_ctx + st - 1) / st;
-  sl = (sl + 63) / 64 * 64;
-  if (sl < 256) sl = 256;
-  if (sl > share_cap) sl = share_cap;
-  if (p->budget > rcap && sl > ssub) sl = ssub;     // no running set: one sub-slice per share
-  pl.slice_len = (int)sl;
-  pl.nslices = (int)((max_ctx + sl - 1) / sl);
+  const int ssub = thr * 8, rcap = thr * 4, share_cap = thr * 32;
+  const int64_t slots = (int64_t)device_cus() * (thr == 1024 ? 1 : 2);
+  const double T_SHARED = 9.5e-3 * 256.0 / (double)device_cus() * (thr == 1024 ? 1.0 : 2.0);
+  const double T_ALONE = 7.2e-3 * (thr == 1024 ? 1.0 : 2.0);
+  const double T_FIX = 7.0, T_SELECT = 5.0, T_MERGE = 12.0, T_CAND_PER_MIB = 2.1;
+  double best = 1e30;
+  int64_t best_sl = 256;
+  for (int64_t st = 1; st <= 4096; st = st < 8 ? st + 1 : st + st / 4) {
+    int64_t sl = (max_ctx + st - 1) / st;
+    sl = (sl + 63) / 64 * 64;
+    if (sl < 256) sl = 256;
+    if (sl > share_cap) sl = share_cap;
+    if (p->budget > rcap && sl > ssub) sl = ssub;   // no running set: one sub-slice per share
+    const int64_t nsh = (max_ctx + sl - 1) / sl > 0 ? (max_ctx + sl - 1) / sl : 1;
+    if (nsh > FS_MAX_SLICES) continue;
+    const int64_t nsub = (sl + ssub - 1) / ssub;
+    double t = 0.0;
+    for (int64_t left = rows * nsh; left > 0; left -= slots) {
+      const double fill = (double)(left < slots ? left : slots) / (double)slots;
+      const double per_tok = T_SHARED * fill > T_ALONE ? T_SHARED * fill : T_ALONE;
+      t += (double)sl * per_tok + T_FIX + (double)nsub * T_SELECT;
+    }
+    if (nsh > 1) {
+      const double ccap = (double)(p->budget < sl ? p->budget : sl);
+      t += (double)rows * (double)nsh * ccap * 8.0 / 1048576.0 * T_CAND_PER_MIB;
+      t += T_MERGE * (double)((rows + device_cus() - 1) / device_cus()) * (1.0 + (double)nsh * ccap / 16384.0);
+    }
+    if (t < best) {
+      best = t;
+      best_sl = sl;
+    }
+    if (sl == 256) break;
+  }
+  pl.slice_len = (int)best_sl;
+  pl.nslices = (int)((max_ctx + best_sl - 1) / best_sl);
   if (pl.nslices < 1) pl.nslices = 1;
   pl.ccap = p->budget < pl.slice_len ? p->budget : pl.slice_len;
   return pl;
