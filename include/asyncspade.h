@@ -28,7 +28,10 @@
  *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 16,
  *     budget > 65536; AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
  *     Contents of device arrays (page ids in range, indices unique and in range) are
- *     the caller's contract.
+ *     the caller's contract; as a guard against faults, page ids are clamped into
+ *     [0, num_pages) and token indices into [0, ctx_lens[b]) before they are used, so a
+ *     corrupt table gives unspecified results for its rows but no out-of-pool access.
+ *     num_pages must be >= 1.
  */
 #ifndef ASYNCSPADE_H
 #define ASYNCSPADE_H

@@ -101,7 +101,10 @@ def _stream(stream) -> C.c_void_p:
 
 def kv_view(k_pool, v_pool, block_table, ctx_lens) -> AsKvView:
     assert k_pool.dtype == torch.bfloat16 and block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
-    return AsKvView(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(ctx_lens), k_pool.shape[0])
+    kv = AsKvView(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(ctx_lens), k_pool.shape[0])
+    # the view holds raw device pointers: keep the tensors alive as long as the view is
+    kv._keep_alive = (k_pool, v_pool, block_table, ctx_lens)
+    return kv
 
 
 def _check(code: int, where: str):

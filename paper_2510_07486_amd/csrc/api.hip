@@ -45,7 +45,7 @@ as_status check_params(const as_params* p) {
 as_status check_kv(const as_kv_view* kv, bool need_v) {
   if (!kv || !kv->k_pool || !kv->block_table || !kv->ctx_lens) return AS_ERR_INVALID_ARG;
   if (need_v && !kv->v_pool) return AS_ERR_INVALID_ARG;
-  if (kv->num_pages < 0) return AS_ERR_INVALID_ARG;
+  if (kv->num_pages < 1) return AS_ERR_INVALID_ARG;
   return AS_OK;
 }
 

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
     float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit,
-    int cps /* inner chunks per split */) {
+    int cps /* inner chunks per split */, int32_t last_page) {
   __shared__ float lg[GH][AT_CHUNK];         // logits, then probabilities
   __shared__ float sc_sh[GH];                // rescale factor of the running accumulator
   __shared__ float red[4][GH][AS_HEAD_DIM];  // per-wave partial outputs
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
   };
   const int raw_first = fetch_index(split * cps);  // speculative: validated once the lengths are known
 
-  const int N = ctx_lens[b];
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt[b * Hkv + j];
   cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
   int tail0 = sel_ctx_lens ? sel_ctx_lens[b] : N;
@@ -130,7 +130,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
       int n = 0;
       if (ti < L) n = (ti < cnt) ? raw : tail0 + (ti - cnt);
       n = n < 0 ? 0 : (n >= N ? N - 1 : n);  // keeps a bad index inside the sequence's pages
-      return ((uint32_t)bt_row[n >> 4] << 4) | (uint32_t)(n & 15);  // page id << 4 | slot in page
+      int32_t pg = bt_row[n >> 4];
+      pg = pg < 0 ? 0 : (pg > last_page ? last_page : pg);           // a corrupt table must not leave the pool
+      return ((uint32_t)pg << 4) | (uint32_t)(n & 15);              // page id << 4 | slot in page
     };
     uint32_t my_pk = page_of(ck_begin, raw_first);
 #pragma unroll 1
@@ -279,7 +281,7 @@ static hipError_t launch_attn_gh(const as_params* p, const as_kv_view* kv, const
   hipLaunchKernelGGL(attn_split_kernel<GH>, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
                      sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, p->budget, p->max_pages_per_seq,
-                     p->sm_scale, nsplit, cps);
+                     p->sm_scale, nsplit, cps, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
   return hipGetLastError();
 }
 

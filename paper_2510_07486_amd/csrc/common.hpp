@@ -34,6 +34,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   return u >> 16;
 }
 
+// context length as the kernels use it: a corrupt entry must not index past the block table
+__device__ __forceinline__ int clamp_ctx(int n, int max_pages) {
+  const int cap = max_pages * AS_PAGE;
+  return n < 0 ? 0 : (n > cap ? cap : n);
+}
+
 // element offset of token `slot` of (page, kv head j) in a [pages][Hkv][16][128] pool
 __device__ __forceinline__ int64_t chunk_offset(int32_t page, int Hkv, int j) {
   return ((int64_t)page * Hkv + j) * (int64_t)(AS_PAGE * AS_HEAD_DIM);

@@ -22,9 +22,9 @@ __global__ __launch_bounds__(256) void score_mfma_direct(const uint16_t* __restr
                                                          const int32_t* __restrict__ ctx_lens,
                                                          const float* __restrict__ q_hat, float* __restrict__ scores,
                                                          int64_t stride, int Hq, int Hkv, int G, int agg,
-                                                         int max_pages) {
+                                                         int max_pages, int32_t last_page) {
   const int b = blockIdx.z, j = blockIdx.y;
-  const int N = ctx_lens[b];
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
   const int p0 = blockIdx.x * SC_TP;
   if (p0 >= npages) return;
@@ -35,6 +35,7 @@ __global__ __launch_bounds__(256) void score_mfma_direct(const uint16_t* __restr
 
   int32_t my_page = 0;
   if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
 
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
@@ -84,10 +85,10 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
                                                       const int32_t* __restrict__ ctx_lens,
                                                       const float* __restrict__ q_hat, float* __restrict__ scores,
                                                       int64_t stride, int Hq, int Hkv, int G, int agg,
-                                                      int max_pages) {
+                                                      int max_pages, int32_t last_page) {
   __shared__ uint4 stage[4][4 * 256];  // per wave: 4 page images of 4 KB
   const int b = blockIdx.z, j = blockIdx.y;
-  const int N = ctx_lens[b];
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
   const int p0 = blockIdx.x * SC_TP;
   if (p0 >= npages) return;
@@ -98,6 +99,7 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
 
   int32_t my_page = 0;
   if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
 
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
@@ -171,9 +173,9 @@ __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restr
                                                          const int32_t* __restrict__ block_table,
                                                          const int32_t* __restrict__ ctx_lens,
                                                          float* __restrict__ scores, int64_t stride, int Hkv,
-                                                         int max_pages) {
+                                                         int max_pages, int32_t last_page) {
   const int b = blockIdx.z, j = blockIdx.y;
-  const int N = ctx_lens[b];
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
   const int p0 = blockIdx.x * SC_TP;
   if (p0 >= npages) return;
@@ -182,6 +184,7 @@ __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restr
   if (pw >= npages) return;
   int32_t my_page = 0;
   if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
   float* srow = scores + ((int64_t)b * Hkv + j) * stride;
 #pragma unroll 1
   for (int qd = 0; qd < SC_PPW / 4; ++qd) {
@@ -211,18 +214,19 @@ hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, c
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
   dim3 grid((p->max_pages_per_seq + SC_TP - 1) / SC_TP, p->n_kv_heads, p->batch);
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
+  const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
 #define AS_SCORE_LAUNCH(KERNEL)                                                                              \
   hipLaunchKernelGGL(KERNEL, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat, scores, stride, \
-                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq)
+                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, last_page)
   const bool nt = variant >= 10;
   switch (variant % 10) {
     case 9:
       if (nt)
         hipLaunchKernelGGL(stream_read_paged<true>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                           stride, p->n_kv_heads, p->max_pages_per_seq);
+                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page);
       else
         hipLaunchKernelGGL(stream_read_paged<false>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                           stride, p->n_kv_heads, p->max_pages_per_seq);
+                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page);
       break;
     case 1:
       if (two) { if (nt) AS_SCORE_LAUNCH((score_mfma_lds<2, false, true>)); else AS_SCORE_LAUNCH((score_mfma_lds<2, false, false>)); }

@@ -121,7 +121,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
     int max_pages, int share_len, int nshares, int C, int ccap, uint32_t* __restrict__ cand_key,
     int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt, int32_t* __restrict__ sel_idx,
-    int32_t* __restrict__ sel_cnt) {
+    int32_t* __restrict__ sel_cnt, int32_t last_page) {
   using shape = fs_shape<FS_THREADS>;
   constexpr int FS_WAVES = shape::WAVES, SSUB = shape::SSUB, RCAP = shape::RCAP;
   constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     __syncthreads();
   }
   const int64_t row = (int64_t)b * Hkv + j;
-  const int N = ctx_lens[b];
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int tok0 = sh * share_len;
   int n_share = N - tok0;
   n_share = n_share < 0 ? 0 : (n_share > share_len ? share_len : n_share);
@@ -184,7 +184,8 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   auto load_pages = [&](int pos, int len) -> int32_t {
     const int lp = ((lane / PG) * FS_WAVES + wave) * PG + (lane % PG);
     const int npg = (len + AS_PAGE - 1) / AS_PAGE;
-    return lp < npg ? bt_row[pos / AS_PAGE + lp] : 0;
+    const int32_t pg = lp < npg ? bt_row[pos / AS_PAGE + lp] : 0;
+    return pg < 0 ? 0 : (pg > last_page ? last_page : pg);   // a corrupt table must not leave the pool
   };
   int pos = 0;
   int n_sub = n_share < cur_len ? n_share : cur_len;
@@ -398,12 +399,13 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
     cand_cnt = cand_idx + n;
   }
   dim3 grid(p->n_kv_heads, p->batch, pl.nslices);
+  const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
 #define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
   hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
                      q_hat, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, \
-                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt)
+                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt, last_page)
   if (g_fs_threads == 1024) {
     if (two) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
   } else {

@@ -23,7 +23,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float* __restric
   const int row = blockIdx.x;
   const int b = row / Hkv;
   const int tid = threadIdx.x;
-  const int N = ctx_lens[b];
+  int N = ctx_lens[b];
+  N = N < 0 ? 0 : ((int64_t)N > stride ? (int)stride : N);   // never past the score row
   const float* s = scores + (int64_t)row * stride;
   int32_t* out = sel_idx + (int64_t)row * C;
   const int keep = N < C ? N : C;

@@ -1,0 +1,70 @@
+"""Fused scoring + top-k on crafted keys whose scores are exact in fp32 and fp64 alike (q_hat = e_0, K[n][0] a small
+integer), so the selection must equal the oracle's bit for bit: massive ties, monotone rows that replace the running
+set at every sub-slice, rows spanning several shares and several sub-slices."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_07486_amd import api
+from paper_2510_07486_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def build(B, Hkv, G, ctx_lens, pattern, seed=0):
+    max_ctx = max(ctx_lens)
+    max_pages = (max_ctx + 15) // 16
+    num_pages = B * max_pages
+    g = torch.Generator().manual_seed(seed)
+    k = torch.zeros((num_pages, Hkv, 16, 128), dtype=torch.bfloat16)
+    bt = torch.zeros((B, max_pages), dtype=torch.int32)
+    for b in range(B):
+        perm = torch.randperm(max_pages, generator=g) + b * max_pages
+        bt[b] = perm.to(torch.int32)
+        n = torch.arange(max_pages * 16)
+        for j in range(Hkv):
+            if pattern == "zero":
+                v = torch.zeros_like(n)
+            elif pattern == "ascending":
+                v = n // 7 - 3000                      # runs of 7 equal scores, increasing
+            elif pattern == "descending":
+                v = 3000 - n // 5
+            elif pattern == "sawtooth":
+                v = (n * (j + 3)) % 97 - 48
+            else:                                        # random small integers: heavy ties
+                v = torch.randint(-100, 101, n.shape, generator=g)
+            vals = v.to(torch.float32).to(torch.bfloat16)     # |v| <= 6000 < 2^8 * 2^... exact? keep |v| small enough
+            k[perm, j, :, 0] = vals.view(max_pages, 16)
+    q_hat = torch.zeros((B, Hkv * G, 128), dtype=torch.float32)
+    q_hat[:, :, 0] = 1.0
+    return k, bt, torch.tensor(ctx_lens, dtype=torch.int32), q_hat
+
+
+@pytest.mark.parametrize("pattern", ["zero", "ascending", "descending", "sawtooth", "random"])
+@pytest.mark.parametrize("shape", [
+    dict(B=2, Hkv=2, G=4, ctx=[40000, 23457], C=2048),      # few rows: many shares per row
+    dict(B=40, Hkv=8, G=4, ctx=None, C=1024),                # many rows: one share, several sub-slices
+    dict(B=3, Hkv=2, G=8, ctx=[9000, 100, 33000], C=5000),  # budget above the running-set capacity
+])
+def test_exact_scores_match_oracle_bit_for_bit(pattern, shape):
+    print("exact", pattern, {k: (v if k != "ctx" else "...") for k, v in shape.items()}, flush=True)
+    B, Hkv, G, C = shape["B"], shape["Hkv"], shape["G"], shape["C"]
+    ctx = shape["ctx"] or [int(x) for x in torch.randint(3000, 20001, (B,), generator=torch.Generator().manual_seed(3))]
+    k, bt, lens, q_hat = build(B, Hkv, G, ctx, pattern)
+    # bf16 holds integers exactly only up to 256: fold the patterns into that range
+    k = (k.float() % 251 - 125).to(torch.bfloat16) if pattern in ("ascending", "descending") else k
+    ref_s = oracle.score_keys(k, bt, lens, q_hat, Hkv)
+    ridx, rcnt = oracle.topk_select(ref_s, lens, C)
+    p = api.make_params(B, Hkv * G, Hkv, 4, C, bt.shape[1])
+    c = api.Context(p)
+    kd = k.cuda()
+    idx, cnt = api.as_score_topk(c, p, api.kv_view(kd, None, bt.cuda(), lens.cuda()), q_hat.cuda())
+    assert torch.equal(cnt.cpu(), rcnt)
+    assert torch.equal(idx.cpu(), ridx)
+    # and through the stand-alone stages
+    sc = api.as_score_keys(c, p, api.kv_view(kd, None, bt.cuda(), lens.cuda()), q_hat.cuda(), fill=0.0)
+    for b in range(B):
+        assert torch.equal(sc[b, :, : ctx[b]].cpu(), ref_s[b, :, : ctx[b]])
+    idx2, cnt2 = api.as_topk_select(c, p, sc, lens.cuda())
+    assert torch.equal(idx2.cpu(), ridx) and torch.equal(cnt2.cpu(), rcnt)
