@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasyncspade.so")
-SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip"]
+SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip"]
 
 
 def build(verbose: bool = True) -> str:

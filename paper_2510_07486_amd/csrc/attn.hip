@@ -285,6 +285,13 @@ static hipError_t launch_attn_gh(const as_params* p, const as_kv_view* kv, const
   return hipGetLastError();
 }
 
+hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
+                            const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
+                            int nsplit, int split_tokens, hipStream_t s);
+
+static int g_attn_impl = 0;  // development knob: 0 = matrix-core kernel (attn_mfma.hip), 1 = vector-ALU kernel
+extern "C" void as_debug_set_attn_impl(int v) { g_attn_impl = v; }
+
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
                        hipStream_t s) {
@@ -293,7 +300,7 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   const int G = p->n_q_heads / p->n_kv_heads;
   // split size: about six workgroups per compute unit, so that per-split costs (partials through HBM,
   // query fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens
-  const int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (G / attn_gh(G));
+  const int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? 1 : G / attn_gh(G));
   int64_t nsel = (1536 + pairs - 1) / pairs;
   const int64_t max_sel = (p->budget + AT_SPLIT - 1) / AT_SPLIT;
   if (nsel > max_sel) nsel = max_sel;
@@ -306,6 +313,9 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
   hipError_t e;
+  if (g_attn_impl == 0)
+    e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, split_tokens, s);
+  else
   switch (attn_gh(G)) {
     case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
     case 4: e = launch_attn_gh<4>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;

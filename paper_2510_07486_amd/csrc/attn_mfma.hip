@@ -1,0 +1,251 @@
+// Sparse decode attention on the matrix cores (Sec. 4.1; the 4*q*h*C term of Appendix B).
+//
+// The vector-ALU formulation (attn.hip) is issue-bound: about 75 instructions per gathered row
+// and head group of 4, twice that at group size 8, which caps it near 4 TB/s and 2.4 TB/s.
+// Here both contractions of a 32-token step run as v_mfma_f32_16x16x32_bf16 and the whole GQA
+// group (up to 16 heads) shares every gathered row at no extra cost:
+//   S^T[token][head] = K_tile[16 x 128] * Q^T[128 x 16]     (two 16-token tiles, 4 MFMAs each)
+//   O[head][dim]    += P[16 x 32] * V[32 x 128]             (8 dim tiles, P split hi + lo)
+// K and V rows arrive with the same coalesced 256-byte row gathers (16 lanes per row,
+// non-temporal), are staged in per-wave LDS images and read back in operand layout: K with
+// the XOR-swizzled 128-bit reads of the scoring kernel, V with ds_read_b64_tr_b16, the
+// transposing LDS read that hands a lane four tokens of one dim.  The S^T accumulator layout
+// (lane = head, 4 tokens per tile and lane group) IS the A-operand layout of P for the PV
+// product, so probabilities go from registers straight back into the matrix core.  Each
+// wavefront keeps its own online-softmax state (no barrier in the loop); the four waves of a
+// workgroup merge once at the end and write one partial (m, l, o) per head and split, which
+// attn_combine_kernel (attn.hip) reduces.
+#include "common.hpp"
+#include "score_common.hpp"
+
+namespace asx {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_m __attribute__((ext_vector_type(4)));
+
+static constexpr int AM_STEP = 32;          // tokens per wave step
+static constexpr int AM_VROW = 288;         // bytes per V row in LDS (256 + 32: spreads the tr reads over banks)
+static constexpr int AM_KIMG = 256;         // uint4 per 16-token K image
+static constexpr int AM_WAVE_LDS = AM_KIMG * 16 * 2 + AM_STEP * AM_VROW;  // 8 KB K + 9 KB V per wave
+
+__device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
+  const u32x4_m r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_m*>(p));
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+__global__ __launch_bounds__(256) void attn_mfma_kernel(
+    const uint16_t* __restrict__ k_pool, const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
+    const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit,
+    int split_tokens, int32_t last_page) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * AM_WAVE_LDS];
+  __shared__ float m_sh[4][16], l_sh[4][16];
+
+  const int b = blockIdx.z, j = blockIdx.y, split = blockIdx.x;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int t = lane & 15, grp = lane >> 4;   // operand coordinates: row / column index, k group
+  const int slot = grp, c = t;                // gather coordinates: row within a 4-row load, 16-byte chunk
+
+  const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
+  // lane l (< 32, upper half mirrors) resolves token l of a 32-token step of this wave
+  auto step_token = [&](int step) -> int { return split * split_tokens + step * AM_STEP + (lane & 31); };
+  auto fetch_index = [&](int step) -> int {
+    const int ti = step_token(step);
+    return (ti < C) ? idx_row[ti] : 0;
+  };
+  const int raw_first = fetch_index(w);       // speculative: validated once the lengths are known
+
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
+  int cnt = sel_cnt[b * Hkv + j];
+  cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
+  int tail0 = sel_ctx_lens ? sel_ctx_lens[b] : N;
+  tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
+  const int L = cnt + (N - tail0);
+  const int t_begin = split * split_tokens;
+  const int t_end = (split == nsplit - 1) ? L : (t_begin + split_tokens < L ? t_begin + split_tokens : L);
+  const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G) * nsplit + split;  // + g * nsplit per head
+  if (t_begin >= t_end) {                                                     // nothing here: mark empty
+    if (tid < G) {
+      part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 0] = -INFINITY;
+      part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 1] = 0.f;
+    }
+    return;
+  }
+  const int nsteps = (t_end - t_begin + AM_STEP - 1) / AM_STEP;
+
+  // Q^T as the B operand of S^T = K Q^T: lane (head t, k group grp), step m holds the 8 dims of
+  // chunk cmap(grp, m) of head t (zero for t >= G)
+  bf16x8 qb[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    uint4 u = make_uint4(0, 0, 0, 0);
+    if (t < G) u = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + (int64_t)j * G + t) * AS_HEAD_DIM + cmap(grp, m) * 8);
+    qb[m] = __builtin_bit_cast(bf16x8, u);
+  }
+
+  unsigned char* my_lds = lds_raw + w * AM_WAVE_LDS;
+  uint4* kimg = reinterpret_cast<uint4*>(my_lds);                       // [2][256] swizzled 16-byte slots
+  unsigned char* vimg = my_lds + AM_KIMG * 16 * 2;                      // [32][AM_VROW]
+  const int32_t* bt_row = block_table + (int64_t)b * max_pages;
+
+  auto page_of = [&](int step, int raw) -> uint32_t {
+    const int ti = step_token(step);
+    int n = 0;
+    if (ti < t_end) n = (ti < cnt) ? raw : tail0 + (ti - cnt);
+    n = n < 0 ? 0 : (n >= N ? N - 1 : n);                               // keeps a bad index inside the sequence
+    int32_t pg = bt_row[n >> 4];
+    pg = pg < 0 ? 0 : (pg > last_page ? last_page : pg);                // a corrupt table must not leave the pool
+    return ((uint32_t)pg << 4) | (uint32_t)(n & 15);
+  };
+
+  f32x4 o_acc[8];                       // O[head 4*grp+i][dim 16*nt + t]
+#pragma unroll
+  for (int nt = 0; nt < 8; ++nt) o_acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f; // softmax state of head t (replicated in the 4 lane groups)
+
+  uint32_t my_pk = (w < nsteps) ? page_of(w, raw_first) : 0u;
+#pragma unroll 1
+  for (int step = w; step < nsteps; step += 4) {
+    // next step's index is requested now, its page id after this step's rows are on their way
+    const bool more = step + 4 < nsteps;
+    int raw_next = 0;
+    if (more) raw_next = fetch_index(step + 4);
+    // ---- gather the 32 K and V rows of the step (8 loads of 4 rows each) ----
+    uint4 kr[8], vr[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const uint32_t pk = __shfl(my_pk, it * 4 + slot);
+      const int64_t off = chunk_offset((int32_t)(pk >> 4), Hkv, j) + (int64_t)(pk & 15) * AS_HEAD_DIM + c * 8;
+      kr[it] = am_ld16_nt(k_pool + off);
+      vr[it] = am_ld16_nt(v_pool + off);
+    }
+    uint32_t pk_next = 0;
+    if (more) pk_next = page_of(step + 4, raw_next);
+    // ---- stage them: K rows swizzled per 16-token tile, V rows padded ----
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = it * 4 + slot;                                    // token of the step
+      kimg[(row >> 4) * AM_KIMG + lds_slot(row & 15, c)] = kr[it];
+      *reinterpret_cast<uint4*>(vimg + row * AM_VROW + c * 16) = vr[it];
+    }
+    __builtin_amdgcn_wave_barrier();
+    // ---- S^T = K Q^T for the two tiles: lane (head t, grp) gets tokens tile*16 + 4*grp + i ----
+    float s[8];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const uint4 kk = kimg[tile * AM_KIMG + lds_slot(t, cmap(grp, m))];
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kk), qb[m], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = t_begin + step * AM_STEP + tile * 16 + 4 * grp + i;
+        s[tile * 4 + i] = (tok < t_end) ? acc[i] * sm_scale : -INFINITY;
+      }
+    }
+    // ---- online softmax of head t over the step's 32 tokens ----
+    float mx = s[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);                               // finite: the step holds a valid token
+    const float scl = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+    float p[8], ps = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = __expf(s[e] - m_new);                                      // exp(-inf) = 0 for masked tokens
+      ps += p[e];
+    }
+    ps += __shfl_xor(ps, 16);
+    ps += __shfl_xor(ps, 32);
+    l_run = l_run * scl + ps;
+    m_run = m_new;
+    // P as A operand (row = head t, k slots e = tokens tile (e>>2), 4*grp + (e&3)), split hi + lo
+    uint32_t ph[4], pl[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const uint32_t h0 = f32_to_bf16_rne(p[e]), h1 = f32_to_bf16_rne(p[e + 1]);
+      const uint32_t l0 = f32_to_bf16_rne(p[e] - __uint_as_float(h0 << 16));
+      const uint32_t l1 = f32_to_bf16_rne(p[e + 1] - __uint_as_float(h1 << 16));
+      ph[e >> 1] = h0 | (h1 << 16);
+      pl[e >> 1] = l0 | (l1 << 16);
+    }
+    const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
+    const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
+    // rescale O: this lane holds heads 4*grp + i, whose factors live in lanes (t = head)
+    float rs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rs[i] = __shfl(scl, 4 * grp + i);
+    // ---- O += P V: V^T fragments through the transposing LDS read ----
+    // lane rho = t of a 16-lane block points at token (tile*16 + 4*grp + (rho>>2)), dims 16*nt + 4*(rho&3);
+    // it receives dims 16*nt + t of tokens tile*16 + 4*grp + 0..3
+    const unsigned char* vbase = vimg + (4 * grp + (t >> 2)) * AM_VROW + (t & 3) * 8;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+      const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(vbase + nt * 32));
+      const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(vbase + 16 * AM_VROW + nt * 32));
+      struct { s16x4 a, b; } pr = {v0, v1};
+      const bf16x8 vb = __builtin_bit_cast(bf16x8, pr);
+      f32x4 acc = o_acc[nt];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] *= rs[i];
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, acc, 0, 0, 0);
+      o_acc[nt] = acc;
+    }
+    __builtin_amdgcn_wave_barrier();
+    my_pk = pk_next;
+  }
+
+  // ---- merge the four waves: common max per head, rescale, sum ----
+  if (grp == 0) {
+    m_sh[w][t] = m_run;
+    l_sh[w][t] = l_run;
+  }
+  __syncthreads();                      // also: every wave is done with its LDS images
+  float M = -INFINITY, Ls = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, m_sh[ww][t]);
+#pragma unroll
+  for (int ww = 0; ww < 4; ++ww) Ls += (m_sh[ww][t] == -INFINITY) ? 0.f : l_sh[ww][t] * __expf(m_sh[ww][t] - M);
+  const float wgt = (m_run == -INFINITY) ? 0.f : __expf(m_run - M);   // this wave's factor for head t
+  float* red = reinterpret_cast<float*>(lds_raw);                      // [4 waves][16 heads][128] fp32 = 32 KB
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float f = __shfl(wgt, 4 * grp + i);
+    const int head = 4 * grp + i;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) red[(w * 16 + head) * AS_HEAD_DIM + nt * 16 + t] = o_acc[nt][i] * f;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * AS_HEAD_DIM; i += 256) {
+    const int g = i / AS_HEAD_DIM, d = i % AS_HEAD_DIM;
+    const float v = red[(0 * 16 + g) * AS_HEAD_DIM + d] + red[(1 * 16 + g) * AS_HEAD_DIM + d] +
+                    red[(2 * 16 + g) * AS_HEAD_DIM + d] + red[(3 * 16 + g) * AS_HEAD_DIM + d];
+    part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
+  }
+  if (w == 0 && grp == 0 && t < G) {
+    part_ml[(pbase + (int64_t)t * nsplit) * 2 + 0] = M;
+    part_ml[(pbase + (int64_t)t * nsplit) * 2 + 1] = Ls;
+  }
+}
+
+hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
+                            const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
+                            int nsplit, int split_tokens, hipStream_t s) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  dim3 grid(nsplit, p->n_kv_heads, p->batch);
+  hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
+                     reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
+                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, p->budget, p->max_pages_per_seq,
+                     p->sm_scale, nsplit, split_tokens, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
+  return hipGetLastError();
+}
+
+}  // namespace asx
