@@ -26,7 +26,7 @@ typedef uint32_t u32x4_m __attribute__((ext_vector_type(4)));
 static constexpr int AM_STEP = 32;          // tokens per wave step
 static constexpr int AM_VROW = 288;         // bytes per V row in LDS (256 + 32: spreads the tr reads over banks)
 static constexpr int AM_KIMG = 256;         // uint4 per 16-token K image
-static constexpr int AM_WAVE_LDS = AM_KIMG * 16 * 2 + AM_STEP * AM_VROW;  // 8 KB K + 9 KB V per wave
+static constexpr int AM_WAVE_LDS = AM_KIMG * 16 + AM_STEP * AM_VROW;      // 4 KB K tile + 9 KB V per wave
 
 __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
   const u32x4_m r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_m*>(p));
@@ -85,8 +85,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   }
 
   unsigned char* my_lds = lds_raw + w * AM_WAVE_LDS;
-  uint4* kimg = reinterpret_cast<uint4*>(my_lds);                       // [2][256] swizzled 16-byte slots
-  unsigned char* vimg = my_lds + AM_KIMG * 16 * 2;                      // [32][AM_VROW]
+  uint4* kimg = reinterpret_cast<uint4*>(my_lds);                       // [256] swizzled 16-byte slots, one 16-token tile
+  unsigned char* vimg = my_lds + AM_KIMG * 16;                          // [32][AM_VROW]
   const int32_t* bt_row = block_table + (int64_t)b * max_pages;
 
   auto page_of = [&](int step, int raw) -> uint32_t {
@@ -122,24 +122,23 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     }
     uint32_t pk_next = 0;
     if (more) pk_next = page_of(step + 4, raw_next);
-    // ---- stage them: K rows swizzled per 16-token tile, V rows padded ----
+    // ---- stage V (padded rows); K goes through one 16-token image, tile after tile ----
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = it * 4 + slot;                                    // token of the step
-      kimg[(row >> 4) * AM_KIMG + lds_slot(row & 15, c)] = kr[it];
-      *reinterpret_cast<uint4*>(vimg + row * AM_VROW + c * 16) = vr[it];
-    }
-    __builtin_amdgcn_wave_barrier();
+    for (int it = 0; it < 8; ++it) *reinterpret_cast<uint4*>(vimg + (it * 4 + slot) * AM_VROW + c * 16) = vr[it];
     // ---- S^T = K Q^T for the two tiles: lane (head t, grp) gets tokens tile*16 + 4*grp + i ----
     float s[8];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) kimg[lds_slot(it * 4 + slot, c)] = kr[tile * 4 + it];
+      __builtin_amdgcn_wave_barrier();
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        const uint4 kk = kimg[tile * AM_KIMG + lds_slot(t, cmap(grp, m))];
+        const uint4 kk = kimg[lds_slot(t, cmap(grp, m))];
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kk), qb[m], acc, 0, 0, 0);
       }
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int tok = t_begin + step * AM_STEP + tile * 16 + 4 * grp + i;
