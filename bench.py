@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--sel-streams", type=int, default=2, help="selection streams (layers round-robin over them)")
     ap.add_argument("--slice-threads", type=int, default=0, help="development: 512 or 1024-thread selection workgroups")
     ap.add_argument("--unfused", action="store_true", help="score and top-k as separate kernels through HBM scores")
+    ap.add_argument("--pack", type=int, default=1, help="layers per packed selection launch (as_select_step_pack)")
     return ap.parse_args()
 
 
@@ -90,7 +91,8 @@ def main():
     p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1], ridge_eps=eps,
                         sm_scale=float(np.float32(1 / math.sqrt(128))))
     n_sel = max(1, a.sel_streams)
-    ctx_sels = [api.Context(p) for _ in range(n_sel)]
+    pack = max(1, min(a.pack, api.AS_MAX_PACK, n_layers))
+    ctx_sels = [api.Context(p, pack=pack) for _ in range(n_sel)]
     ctx_att = api.Context(p)
     if a.score_variant >= 0:
         for c in ctx_sels:
@@ -125,6 +127,22 @@ def main():
             if ev_pair is not None:
                 ev_pair[1].record(stream)
 
+    # packed selection: layers [g*pack, (g+1)*pack) in one as_select_step_pack call
+    n_packs = (n_layers + pack - 1) // pack
+    pack_ios = None
+    if pack > 1:
+        pack_ios = [[(api.AsLayerIo * len(range(g * pack, min(n_layers, (g + 1) * pack))))(
+            *[api.layer_io(kvs[l % resident], layers[l % resident]["qw"], layers[l % resident]["qc"],
+                           sel[t][l][0], sel[t][l][1]) for l in range(g * pack, min(n_layers, (g + 1) * pack))])
+            for g in range(n_packs)] for t in range(2)]
+
+    def select_pack(g, t_dst, stream, ev_pair=None, lane=0):
+        if ev_pair is not None:
+            ev_pair[0].record(stream)
+        api.as_select_step_pack(ctx_sels[lane], p, pack_ios[t_dst][g], stream=stream)
+        if ev_pair is not None:
+            ev_pair[1].record(stream)
+
     def attend(l, src, stream):
         L = layers[l % resident]
         api.as_sparse_decode_attn(ctx_att, p, kvs[l % resident], L["qr"], src[0], src[1], out=out, stream=stream,
@@ -139,15 +157,21 @@ def main():
     def step_overlapped(t, score_events=None):
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
         for l in range(n_layers):
-            lane = l % n_sel
-            ev = torch.cuda.Event()
-            ev.record(s_att)                       # layer l's step-t query/key/value exist from here on
-            s_sels[lane].wait_event(ev)
-            pair = None
-            if score_events is not None:
-                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                score_events.append(pair)
-            select(l, nxt[l], s_sels[lane], pair, lane)
+            last_of_pack = (l % pack == pack - 1) or l == n_layers - 1
+            if last_of_pack:                       # a pack is selected once its last layer's q/k/v exist
+                g = l // pack
+                lane = g % n_sel
+                ev = torch.cuda.Event()
+                ev.record(s_att)                   # layer l's step-t query/key/value exist from here on
+                s_sels[lane].wait_event(ev)
+                pair = None
+                if score_events is not None:
+                    pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                    score_events.append(pair)
+                if pack > 1:
+                    select_pack(g, (t + 1) % 2, s_sels[lane], pair, lane)
+                else:
+                    select(l, nxt[l], s_sels[lane], pair, lane)
             attend(l, cur[l], s_att)
         for s_sel in s_sels:                       # the next step's attention needs every new selection
             done = torch.cuda.Event()
@@ -157,11 +181,15 @@ def main():
     def step_serial(t, score_events=None):
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
         for l in range(n_layers):
-            pair = None
-            if score_events is not None:
-                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                score_events.append(pair)
-            select(l, nxt[l], s_att, pair)
+            if pack == 1 or l % pack == pack - 1 or l == n_layers - 1:
+                pair = None
+                if score_events is not None:
+                    pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                    score_events.append(pair)
+                if pack > 1:
+                    select_pack(l // pack, (t + 1) % 2, s_att, pair)
+                else:
+                    select(l, nxt[l], s_att, pair)
             attend(l, cur[l], s_att)
 
     def timed(step_fn):
@@ -192,8 +220,9 @@ def main():
     # dominant kernel: the K-streaming part of the selection.  Its roofline uses the launches of the
     # single-stream timed pass (the kernel alone on the GPU); the rate it keeps while sharing HBM with
     # the attention stream is reported next to it.
-    score_ms = float(np.mean(score_ms_serial))
-    score_ms_shared = float(np.mean(score_ms_ovl))
+    # with packs, an event pair brackets one as_select_step_pack call (predictor included): per-layer average
+    score_ms = float(np.sum(score_ms_serial)) / (a.steps * n_layers)
+    score_ms_shared = float(np.sum(score_ms_ovl)) / (a.steps * n_layers)
     achieved = k_bytes / (score_ms * 1e-3) / 1e9
     step_roofline_us = (k_bytes + kv_gather) / (HBM_PEAK_GBS * 1e9) * 1e6
 
@@ -214,14 +243,16 @@ def main():
         "config": {"workload": f"{a.workload}: Qwen3-8B attention shape" if a.workload in ("c2", "c3", "c5") else a.workload,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128, "context": w.ctx,
                    "window": w.window, "budget": C, "page_size": 16, "layers_per_step": n_layers,
-                   "layers_resident": resident, "streams": 1 if a.serial_only else 1 + n_sel},
+                   "layers_resident": resident, "streams": 1 if a.serial_only else 1 + n_sel,
+                   "layers_per_select_launch": pack},
         "serial_us_per_layer_step": round(us_layer_serial, 2),
         "step_roofline_us": round(step_roofline_us, 2),
         "step_roofline_frac": round(step_roofline_us / us_layer, 4),
         "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
         "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "score_keys_gbs_while_overlapped": round(k_bytes / (score_ms_shared * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "score_keys" if a.unfused else "score_topk (slice + merge kernels)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "score_keys" if a.unfused else ("score_topk (slice + merge kernels)" if pack == 1 else
+                                                              "select_step_pack (predict + slice + merge kernels)"), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4),
                      "measured_in": "single-stream timed pass (events on the launch stream)"},

@@ -147,6 +147,30 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win,
                          const void* q_cur, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
+/*
+ * Depth-wise packed selection (Sec. 4.3, "Depth-wise Parallelism on Cache Rank": several
+ * consecutive decoder blocks are bundled into one unit and filtered with parallelism along
+ * the depth dimension).  One call = as_select_step for n_layers layers, run as ONE predictor
+ * launch and ONE scoring/top-k launch (plus one merge launch when rows are cut into shares)
+ * whose grids cover every layer of the pack.  Each layer brings its own cache view, query
+ * window and output arrays; all layers share the shapes in `p`.  Results are identical, bit
+ * for bit, to n_layers separate as_select_step calls.
+ *   layers    HOST array of n_layers entries (read during the call, not kept);
+ *             1 <= n_layers <= AS_MAX_PACK, else AS_ERR_UNSUPPORTED
+ *   the ctx workspace must hold as_workspace_bytes_pack(p, n_layers), else AS_ERR_WORKSPACE
+ */
+#define AS_MAX_PACK 16
+typedef struct {
+  as_kv_view kv;       /* this layer's cache; block_table / ctx_lens may be shared by the layers */
+  const void* q_win;   /* bf16 [B][Hq][W][128] oldest first */
+  const void* q_cur;   /* bf16 [B][Hq][128]                 */
+  int32_t* sel_idx;    /* int32 [B][Hkv][C] out             */
+  int32_t* sel_cnt;    /* int32 [B][Hkv]    out             */
+} as_layer_io;
+size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers);
+as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io* layers, int32_t n_layers,
+                              void* stream);
+
 #ifdef __cplusplus
 }
 #endif

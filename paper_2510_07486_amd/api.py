@@ -19,7 +19,9 @@ _lib = None
 
 AS_AGG_MAX, AS_AGG_SUM = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
-           "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step"]
+           "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",
+           "as_select_step_pack"]
+AS_MAX_PACK = 16
 
 
 class AsParams(C.Structure):
@@ -32,6 +34,11 @@ class AsParams(C.Structure):
 class AsKvView(C.Structure):
     _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_table", C.c_void_p),
                 ("ctx_lens", C.c_void_p), ("num_pages", C.c_int64)]
+
+
+class AsLayerIo(C.Structure):
+    _fields_ = [("kv", AsKvView), ("q_win", C.c_void_p), ("q_cur", C.c_void_p), ("sel_idx", C.c_void_p),
+                ("sel_cnt", C.c_void_p)]
 
 
 class AsError(RuntimeError):
@@ -70,6 +77,12 @@ def lib():
         L.as_score_topk.argtypes = [vp, PP, KP, vp, vp, vp, vp]
         L.as_select_step.restype = C.c_int
         L.as_select_step.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp]
+        L.as_workspace_bytes_pack.restype = C.c_size_t
+        L.as_workspace_bytes_pack.argtypes = [PP, C.c_int32]
+        L.as_select_step_pack.restype = C.c_int
+        L.as_select_step_pack.argtypes = [vp, PP, C.POINTER(AsLayerIo), C.c_int32, vp]
+        L.as_debug_select_plan.restype = C.c_int
+        L.as_debug_select_plan.argtypes = [PP, C.c_int, C.POINTER(C.c_int32)]
         L.as_debug_set_score_variant.restype = C.c_int
         L.as_debug_set_score_variant.argtypes = [vp, C.c_int]
         L.as_debug_set_select_mode.restype = C.c_int
@@ -116,12 +129,25 @@ def as_workspace_bytes(p: AsParams) -> int:
     return int(lib().as_workspace_bytes(C.byref(p)))
 
 
+def select_plan(p: AsParams, n_layers: int = 1):
+    """(share length, shares per row, candidates per share) the fused selection would use."""
+    out = (C.c_int32 * 3)()
+    _check(lib().as_debug_select_plan(C.byref(p), n_layers, out), "as_debug_select_plan")
+    return tuple(out)
+
+
+def as_workspace_bytes_pack(p: AsParams, n_layers: int) -> int:
+    return int(lib().as_workspace_bytes_pack(C.byref(p), n_layers))
+
+
 class Context:
     """Owns one as_ctx (device workspace).  One per concurrently used stream."""
 
-    def __init__(self, p: AsParams, device: int = 0, workspace_bytes: Optional[int] = None):
+    def __init__(self, p: AsParams, device: int = 0, workspace_bytes: Optional[int] = None, pack: int = 1):
         self.handle = C.c_void_p()
-        nbytes = as_workspace_bytes(p) if workspace_bytes is None else workspace_bytes
+        nbytes = workspace_bytes
+        if nbytes is None:      # large enough for the single-layer calls and for packs of `pack` layers
+            nbytes = max(as_workspace_bytes(p), as_workspace_bytes_pack(p, pack) if pack > 1 else 0)
         _check(lib().as_create(C.byref(self.handle), device, nbytes), "as_create")
         self.workspace_bytes = nbytes
 
@@ -203,3 +229,17 @@ def as_select_step(ctx: Context, p: AsParams, kv: AsKvView, q_win, q_cur, sel_id
     _check(lib().as_select_step(ctx.handle, C.byref(p), C.byref(kv), _ptr(q_win), _ptr(q_cur), _ptr(sel_idx),
                                 _ptr(sel_cnt), _stream(stream)), "as_select_step")
     return sel_idx, sel_cnt
+
+
+def layer_io(kv: AsKvView, q_win, q_cur, sel_idx, sel_cnt) -> AsLayerIo:
+    io = AsLayerIo(kv, _ptr(q_win), _ptr(q_cur), _ptr(sel_idx), _ptr(sel_cnt))
+    io._keep_alive = (kv, q_win, q_cur, sel_idx, sel_cnt)
+    return io
+
+
+def as_select_step_pack(ctx: Context, p: AsParams, layers, stream=None):
+    """layers: sequence of AsLayerIo (see layer_io) or a prepared ctypes array of them."""
+    if not isinstance(layers, C.Array):
+        layers = (AsLayerIo * len(layers))(*layers)
+    _check(lib().as_select_step_pack(ctx.handle, C.byref(p), layers, len(layers), _stream(stream)),
+           "as_select_step_pack")

@@ -9,19 +9,21 @@ namespace {
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct ws_layout {
-  size_t q_hat, scores, cand, attn, total;
+  size_t q_hat, q_hat_layer, scores, cand, attn, total;
   int64_t score_stride;
 };
 
-ws_layout layout_of(const as_params* p) {
+// n_layers > 1: the layout of a packed selection (one q_hat block per layer, candidates of the
+// whole pack); the single-layer layout also holds the score rows of the unfused path.
+ws_layout layout_of(const as_params* p, int n_layers = 1) {
   ws_layout l;
   l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
   l.q_hat = 0;
-  size_t qh = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
-  l.scores = l.q_hat + qh;
-  size_t sc = align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
+  l.q_hat_layer = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
+  l.scores = l.q_hat + l.q_hat_layer * n_layers;
+  size_t sc = n_layers > 1 ? 0 : align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
   l.cand = l.scores + sc;
-  l.attn = l.cand + align_up(asx::select_workspace_bytes(p));
+  l.attn = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
   l.total = l.attn + align_up(asx::attn_workspace_bytes(p));
   return l;
 }
@@ -181,11 +183,59 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   return hip_status(e);
 }
 
+size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers) {
+  if (check_params(p) != AS_OK || n_layers < 1 || n_layers > AS_MAX_PACK) return 0;
+  return layout_of(p, n_layers).total;
+}
+
+as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io* layers, int32_t n_layers,
+                              void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !layers || n_layers < 1) return AS_ERR_INVALID_ARG;
+  if (n_layers > AS_MAX_PACK || (int64_t)p->batch * n_layers > 65535) return AS_ERR_UNSUPPORTED;
+  for (int l = 0; l < n_layers; ++l) {
+    if ((st = check_kv(&layers[l].kv, false)) != AS_OK) return st;
+    if (!layers[l].q_win || !layers[l].q_cur || !layers[l].sel_idx || !layers[l].sel_cnt) return AS_ERR_INVALID_ARG;
+  }
+  const ws_layout lay = layout_of(p, n_layers);
+  if (!ctx->ws || ctx->ws_bytes < lay.total) return AS_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(ctx->ws);
+  asx::pred_tab pt = {};
+  asx::sel_tab stab = {};
+  for (int l = 0; l < n_layers; ++l) {
+    float* q_hat = reinterpret_cast<float*>(ws + lay.q_hat + lay.q_hat_layer * l);
+    pt.q_win[l] = static_cast<const uint16_t*>(layers[l].q_win);
+    pt.q_cur[l] = static_cast<const uint16_t*>(layers[l].q_cur);
+    pt.q_hat[l] = q_hat;
+    stab.k_pool[l] = static_cast<const uint16_t*>(layers[l].kv.k_pool);
+    stab.block_table[l] = layers[l].kv.block_table;
+    stab.ctx_lens[l] = layers[l].kv.ctx_lens;
+    stab.q_hat[l] = q_hat;
+    stab.sel_idx[l] = layers[l].sel_idx;
+    stab.sel_cnt[l] = layers[l].sel_cnt;
+    stab.last_page[l] = (int32_t)(layers[l].kv.num_pages - 1);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
+  if (e != hipSuccess) return AS_ERR_HIP;
+  return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand, s));
+}
+
 // Development knobs (not part of the documented ABI): pick the key-scoring kernel variant of
 // as_score_keys, and whether as_select_step fuses scoring with top-k (0) or not (1).
 as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
   if (!ctx) return AS_ERR_INVALID_ARG;
   ctx->score_variant = variant;
+  return AS_OK;
+}
+// share plan of the fused selection for a pack of n_layers layers: out = {share length, shares per row, candidates per share}
+as_status as_debug_select_plan(const as_params* p, int n_layers, int32_t* out) {
+  if (check_params(p) != AS_OK || !out || n_layers < 1) return AS_ERR_INVALID_ARG;
+  const asx::select_plan pl = asx::plan_select(p, n_layers);
+  out[0] = pl.slice_len;
+  out[1] = pl.nslices;
+  out[2] = pl.ccap;
   return AS_OK;
 }
 as_status as_debug_set_select_mode(as_ctx* ctx, int mode) {

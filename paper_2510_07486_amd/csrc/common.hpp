@@ -11,6 +11,7 @@
 #define AS_MAX_GROUP 16
 #define AS_MAX_BUDGET 65536
 #define AS_ATTN_CHUNK 128 /* tokens per attention split */
+#define AS_PACK_MAX AS_MAX_PACK /* layers one packed selection launch can cover */
 
 struct as_ctx {
   int device;
@@ -45,7 +46,27 @@ __device__ __forceinline__ int64_t chunk_offset(int32_t page, int Hkv, int j) {
   return ((int64_t)page * Hkv + j) * (int64_t)(AS_PAGE * AS_HEAD_DIM);
 }
 
+// Per-layer pointers of a packed launch (several decoder layers in one grid).  Passed to the
+// kernels by value: the layer index is uniform per workgroup, so a kernel reads its entry with
+// scalar loads from the kernel-argument segment and no pointer table has to be staged in HBM.
+struct pred_tab {
+  const uint16_t* q_win[AS_PACK_MAX];
+  const uint16_t* q_cur[AS_PACK_MAX];
+  float* q_hat[AS_PACK_MAX];
+};
+struct sel_tab {
+  const uint16_t* k_pool[AS_PACK_MAX];
+  const int32_t* block_table[AS_PACK_MAX];
+  const int32_t* ctx_lens[AS_PACK_MAX];
+  const float* q_hat[AS_PACK_MAX];
+  int32_t* sel_idx[AS_PACK_MAX];
+  int32_t* sel_cnt[AS_PACK_MAX];
+  int32_t last_page[AS_PACK_MAX];   // num_pages - 1 of the layer's pool (page ids are clamped to it)
+};
+
 // ---- launchers (host) -------------------------------------------------------------
+// predictor over n_layers * batch * n_q_heads heads; single-layer form below
+hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab& tab, hipStream_t s);
 hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
                           hipStream_t s);
 hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
@@ -54,8 +75,9 @@ hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, 
                        int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // fused scoring + top-k (select_fused.hip): rows are cut into slices of `slice_len` tokens
 struct select_plan { int slice_len, nslices, ccap; };
-select_plan plan_select(const as_params* p);
-size_t select_workspace_bytes(const as_params* p);
+select_plan plan_select(const as_params* p, int n_layers);
+size_t select_workspace_bytes(const as_params* p, int n_layers);
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s);
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
                                int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // partial buffers live in the ctx workspace

@@ -20,9 +20,8 @@ __host__ __device__ inline size_t predict_lds_bytes(int W) {
   return dbl * sizeof(double) + (size_t)(W + 1) * RS * sizeof(float);
 }
 
-__global__ __launch_bounds__(64) void predict_kernel(const uint16_t* __restrict__ q_win,
-                                                     const uint16_t* __restrict__ q_cur,
-                                                     float* __restrict__ q_hat, int W, double eps, double beta) {
+__global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int heads_per_layer, int W, double eps,
+                                                     double beta) {
   extern __shared__ double smem_d[];
   double* A = smem_d;                    // [W][W+1] lower Cholesky factor in place
   double* Om = A + (size_t)W * (W + 1);  // [W][W+1] row k-1: omega^{(k)} then w^{(k)}
@@ -32,9 +31,11 @@ __global__ __launch_bounds__(64) void predict_kernel(const uint16_t* __restrict_
   float* Rf = reinterpret_cast<float*>(av + W);  // [W+1][RS]; row i<W = Q_{t-1-i}, row W = Q_t
 
   const int lane = threadIdx.x;
-  const int64_t bh = blockIdx.x;
-  const uint32_t* win = reinterpret_cast<const uint32_t*>(q_win + bh * (int64_t)W * AS_HEAD_DIM);
-  const uint32_t* cur = reinterpret_cast<const uint32_t*>(q_cur + bh * (int64_t)AS_HEAD_DIM);
+  const int layer = blockIdx.x / heads_per_layer;          // uniform: the table entry is read with scalar loads
+  const int64_t bh = blockIdx.x - layer * heads_per_layer;
+  float* __restrict__ q_hat = tab.q_hat[layer];
+  const uint32_t* win = reinterpret_cast<const uint32_t*>(tab.q_win[layer] + bh * (int64_t)W * AS_HEAD_DIM);
+  const uint32_t* cur = reinterpret_cast<const uint32_t*>(tab.q_cur[layer] + bh * (int64_t)AS_HEAD_DIM);
 
   // 1. stage the window newest-first (lane holds dims 2*lane, 2*lane+1)
   for (int i = 0; i < W; ++i) {
@@ -137,9 +138,8 @@ __global__ __launch_bounds__(64) void predict_kernel(const uint16_t* __restrict_
 // divisions replaced by one reciprocal per diagonal element, and the W(W+1)/2 softmax
 // exponentials spread over the 64 lanes instead of W sequential ones per lane.
 template <int W>
-__global__ __launch_bounds__(64) void predict_kernel_w(const uint16_t* __restrict__ q_win,
-                                                       const uint16_t* __restrict__ q_cur,
-                                                       float* __restrict__ q_hat, double eps, double beta) {
+__global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int heads_per_layer, double eps,
+                                                       double beta) {
   __shared__ float Rf[(W + 1) * RS];   // row i < W = Q_{t-1-i}, row W = Q_t
   __shared__ double A[W][W + 1];       // Gram, then the Cholesky factor L
   __shared__ double Om[W][W + 1];      // row k-1: beta*omega^{(k)} - max, then exp of it
@@ -148,9 +148,11 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const uint16_t* __restric
 
   const int lane = threadIdx.x;
   const int r = lane;
-  const int64_t bh = blockIdx.x;
-  const uint32_t* win = reinterpret_cast<const uint32_t*>(q_win + bh * (int64_t)W * AS_HEAD_DIM);
-  const uint32_t* cur = reinterpret_cast<const uint32_t*>(q_cur + bh * (int64_t)AS_HEAD_DIM);
+  const int layer = blockIdx.x / heads_per_layer;
+  const int64_t bh = blockIdx.x - layer * heads_per_layer;
+  float* __restrict__ q_hat = tab.q_hat[layer];
+  const uint32_t* win = reinterpret_cast<const uint32_t*>(tab.q_win[layer] + bh * (int64_t)W * AS_HEAD_DIM);
+  const uint32_t* cur = reinterpret_cast<const uint32_t*>(tab.q_cur[layer] + bh * (int64_t)AS_HEAD_DIM);
 #pragma unroll
   for (int i = 0; i < W; ++i) {
     const uint32_t w2 = win[(int64_t)(W - 1 - i) * (AS_HEAD_DIM / 2) + lane];
@@ -287,16 +289,18 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const uint16_t* __restric
   }
 }
 
-hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
-                          hipStream_t s) {
-  const int64_t heads = (int64_t)p->batch * p->n_q_heads;
+hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab& tab, hipStream_t s) {
+  const int64_t per_layer = (int64_t)p->batch * p->n_q_heads;
+  const int64_t heads = per_layer * n_layers;
   if (heads == 0) return hipSuccess;
+  if (heads > 0x7fffffff) return hipErrorInvalidValue;
+  const int hpl = (int)per_layer;
   if (p->window == 16 || p->window == 8) {
     if (p->window == 16)
-      hipLaunchKernelGGL(predict_kernel_w<16>, dim3((unsigned)heads), dim3(64), 0, s, q_win, q_cur, q_hat,
+      hipLaunchKernelGGL(predict_kernel_w<16>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
                          (double)p->ridge_eps, (double)p->softmax_beta);
     else
-      hipLaunchKernelGGL(predict_kernel_w<8>, dim3((unsigned)heads), dim3(64), 0, s, q_win, q_cur, q_hat,
+      hipLaunchKernelGGL(predict_kernel_w<8>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
                          (double)p->ridge_eps, (double)p->softmax_beta);
     return hipGetLastError();
   }
@@ -306,9 +310,18 @@ hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint1
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(predict_kernel, dim3((unsigned)heads), dim3(64), lds, s, q_win, q_cur, q_hat, p->window,
+  hipLaunchKernelGGL(predict_kernel, dim3((unsigned)heads), dim3(64), lds, s, tab, hpl, p->window,
                      (double)p->ridge_eps, (double)p->softmax_beta);
   return hipGetLastError();
+}
+
+hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
+                          hipStream_t s) {
+  pred_tab tab = {};
+  tab.q_win[0] = q_win;
+  tab.q_cur[0] = q_cur;
+  tab.q_hat[0] = q_hat;
+  return launch_predict_pack(p, 1, tab, s);
 }
 
 }  // namespace asx

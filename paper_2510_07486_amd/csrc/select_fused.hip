@@ -56,9 +56,9 @@ static int device_cus() {
 // partly filled last round at the rate one compute unit can pull alone (T_ALONE).  Every share
 // pays a fixed start-up, one LDS select per sub-slice and, when a row has several shares, its
 // candidates through HBM plus the merge kernel.  Constants are measured on MI355X.
-static select_plan plan_for(const as_params* p, int thr) {
+static select_plan plan_for(const as_params* p, int thr, int n_layers) {
   select_plan pl;
-  const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
+  const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
   const int ssub = thr * 8, rcap = thr * 4, share_cap = thr * 32;
   const int64_t slots = (int64_t)device_cus() * (thr == 1024 ? 1 : 2);
@@ -100,14 +100,14 @@ static select_plan plan_for(const as_params* p, int thr) {
   return pl;
 }
 
-select_plan plan_select(const as_params* p) { return plan_for(p, g_fs_threads); }
+select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, g_fs_threads, n_layers); }
 
-size_t select_workspace_bytes(const as_params* p) {
+size_t select_workspace_bytes(const as_params* p, int n_layers) {
   size_t best = 0;  // sized for either workgroup shape
   for (int thr : {512, 1024}) {
-    const select_plan pl = plan_for(p, thr);
+    const select_plan pl = plan_for(p, thr, n_layers);
     if (pl.nslices > 1) {
-      const size_t rows = (size_t)p->batch * p->n_kv_heads;
+      const size_t rows = (size_t)p->batch * p->n_kv_heads * n_layers;
       const size_t b = rows * pl.nslices * ((size_t)pl.ccap * 8 + 4);
       if (b > best) best = b;
     }
@@ -117,11 +117,8 @@ size_t select_workspace_bytes(const as_params* p) {
 
 template <int NSET, int FS_THREADS, int PG>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
-    const uint16_t* __restrict__ k_pool, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ ctx_lens, const float* __restrict__ q_hat, int Hq, int Hkv, int G, int agg,
-    int max_pages, int share_len, int nshares, int C, int ccap, uint32_t* __restrict__ cand_key,
-    int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt, int32_t* __restrict__ sel_idx,
-    int32_t* __restrict__ sel_cnt, int32_t last_page) {
+    const sel_tab tab, int B, int Hq, int Hkv, int G, int agg, int max_pages, int share_len, int nshares, int C,
+    int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt) {
   using shape = fs_shape<FS_THREADS>;
   constexpr int FS_WAVES = shape::WAVES, SSUB = shape::SSUB, RCAP = shape::RCAP;
   constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS;
@@ -132,7 +129,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   __shared__ uint32_t hist[FS_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
-  // Grid = (KV head, batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
+  // Grid = (KV head, layer * B + batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
   // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
   // sequences (the share) must vary slowest, or the workgroups that do have work pile up on half
   // of the compute units.
@@ -141,8 +138,16 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   const int t = lane & 15, grp = lane >> 4;
   // Longest sequences first: workgroups are dispatched in blockIdx order, so the y-th dispatched
   // batch slot takes the sequence of length rank y (ties by index) and the short ones fill the tail.
-  int b = blockIdx.y;
-  const int B = gridDim.y;
+  const int layer = blockIdx.y / B;   // uniform: the layer's table entry comes in through scalar loads
+  const int slot = blockIdx.y - layer * B;
+  const uint16_t* __restrict__ k_pool = tab.k_pool[layer];
+  const int32_t* __restrict__ block_table = tab.block_table[layer];
+  const int32_t* __restrict__ ctx_lens = tab.ctx_lens[layer];
+  const float* __restrict__ q_hat = tab.q_hat[layer];
+  int32_t* __restrict__ sel_idx = tab.sel_idx[layer];
+  int32_t* __restrict__ sel_cnt = tab.sel_cnt[layer];
+  const int32_t last_page = tab.last_page[layer];
+  int b = slot;
   if (B > 1 && B <= SSUB) {
     int32_t* lens = reinterpret_cast<int32_t*>(keys);
     for (int i = tid; i < B; i += FS_THREADS) lens[i] = ctx_lens[i];
@@ -151,13 +156,14 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       const int lu = lens[u];
       int rank = 0;
       for (int v = 0; v < B; ++v) rank += (lens[v] > lu) || (lens[v] == lu && v < u);
-      if (rank == (int)blockIdx.y) xch[0] = (uint32_t)u;
+      if (rank == slot) xch[0] = (uint32_t)u;
     }
     __syncthreads();
     b = (int)xch[0];
     __syncthreads();
   }
-  const int64_t row = (int64_t)b * Hkv + j;
+  const int64_t row = (int64_t)b * Hkv + j;                      // row of this layer's outputs
+  const int64_t crow = ((int64_t)layer * B + b) * Hkv + j;        // row of the pack-wide candidate arrays
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int tok0 = sh * share_len;
   int n_share = N - tok0;
@@ -168,7 +174,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = -1;
       if (tid == 0) sel_cnt[row] = 0;
     } else if (tid == 0) {
-      cand_cnt[row * nshares + sh] = 0;
+      cand_cnt[crow * nshares + sh] = 0;
     }
     return;
   }
@@ -297,12 +303,12 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? o_idx[i] : -1;
     if (tid == 0) sel_cnt[row] = keep;
   } else {
-    const int64_t cbase = (row * nshares + sh) * (int64_t)ccap;
+    const int64_t cbase = (crow * nshares + sh) * (int64_t)ccap;
     for (int i = tid; i < keep; i += FS_THREADS) {
       cand_key[cbase + i] = o_key[i];
       cand_idx[cbase + i] = o_idx[i];
     }
-    if (tid == 0) cand_cnt[row * nshares + sh] = keep;
+    if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
   }
 }
 
@@ -312,25 +318,29 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 // run the same selection over the global arrays.
 static constexpr int MG_LDS = 12288;  // (key, index) pairs: 96 KB
 
-__global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t* __restrict__ cand_key,
+__global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab tab, int rows_per_layer,
+                                                                  const uint32_t* __restrict__ cand_key,
                                                                   const int32_t* __restrict__ cand_idx,
                                                                   const int32_t* __restrict__ cand_cnt, int nslices,
-                                                                  int ccap, int C, int32_t* __restrict__ sel_idx,
-                                                                  int32_t* __restrict__ sel_cnt) {
+                                                                  int ccap, int C) {
   __shared__ int32_t cnt_sh[FS_MAX_SLICES];
   __shared__ int32_t pre_sh[FS_MAX_SLICES];
   __shared__ __attribute__((aligned(16))) uint32_t lkey[MG_LDS];
   __shared__ int32_t lidx[MG_LDS];
   __shared__ uint32_t hist[TK_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
-  const int64_t row = blockIdx.x;
+  const int64_t crow = blockIdx.x;                         // row of the pack-wide candidate arrays
+  const int layer = blockIdx.x / rows_per_layer;
+  const int64_t row = crow - (int64_t)layer * rows_per_layer;  // row of this layer's outputs
+  int32_t* __restrict__ sel_idx = tab.sel_idx[layer];
+  int32_t* __restrict__ sel_cnt = tab.sel_cnt[layer];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // counts and their exclusive prefix over slices: a thread owns 4 consecutive slices
   uint32_t c4[4], mine = 0;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int sl = 4 * tid + e;
-    c4[e] = sl < nslices ? (uint32_t)cand_cnt[row * nslices + sl] : 0u;
+    c4[e] = sl < nslices ? (uint32_t)cand_cnt[crow * nslices + sl] : 0u;
     mine += c4[e];
   }
   const uint32_t inc = wave_incl_scan(mine);
@@ -350,7 +360,7 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t
   }
   __syncthreads();
   const int keep = total < C ? total : C;
-  const int64_t cbase = row * nslices * (int64_t)ccap;
+  const int64_t cbase = crow * nslices * (int64_t)ccap;
   const int nvirt = nslices * ccap;
   if (keep > 0) {
     if (total <= MG_LDS) {
@@ -384,11 +394,11 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const uint32_t
   if (tid == 0) sel_cnt[row] = keep;
 }
 
-hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
-                               int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
-  const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s) {
+  const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
   if (rows == 0) return hipSuccess;
-  const select_plan pl = plan_select(p);
+  if ((int64_t)p->batch * n_layers > 65535) return hipErrorInvalidValue;   // grid.y
+  const select_plan pl = plan_select(p, n_layers);
   const int G = p->n_q_heads / p->n_kv_heads;
   uint32_t* cand_key = nullptr;
   int32_t *cand_idx = nullptr, *cand_cnt = nullptr;
@@ -398,14 +408,12 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
     cand_idx = reinterpret_cast<int32_t*>(cand_key + n);
     cand_cnt = cand_idx + n;
   }
-  dim3 grid(p->n_kv_heads, p->batch, pl.nslices);
-  const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
+  dim3 grid(p->n_kv_heads, p->batch * n_layers, pl.nslices);
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
-  const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
-#define AS_SLICE_LAUNCH(NSET_, THR_)                                                                            \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, kp, kv->block_table, kv->ctx_lens, \
-                     q_hat, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, \
-                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, sel_idx, sel_cnt, last_page)
+#define AS_SLICE_LAUNCH(NSET_, THR_)                                                                              \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, tab, p->batch, p->n_q_heads, \
+                     p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, p->budget, pl.ccap,   \
+                     cand_key, cand_idx, cand_cnt)
   if (g_fs_threads == 1024) {
     if (two) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
   } else {
@@ -414,9 +422,22 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || pl.nslices == 1) return e;
-  hipLaunchKernelGGL(select_merge_kernel, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, cand_key, cand_idx, cand_cnt,
-                     pl.nslices, pl.ccap, p->budget, sel_idx, sel_cnt);
+  hipLaunchKernelGGL(select_merge_kernel, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, tab,
+                     p->batch * p->n_kv_heads, cand_key, cand_idx, cand_cnt, pl.nslices, pl.ccap, p->budget);
   return hipGetLastError();
+}
+
+hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
+                               int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+  sel_tab tab = {};
+  tab.k_pool[0] = reinterpret_cast<const uint16_t*>(kv->k_pool);
+  tab.block_table[0] = kv->block_table;
+  tab.ctx_lens[0] = kv->ctx_lens;
+  tab.q_hat[0] = q_hat;
+  tab.sel_idx[0] = sel_idx;
+  tab.sel_cnt[0] = sel_cnt;
+  tab.last_page[0] = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
+  return launch_select_pack(p, 1, tab, ws, s);
 }
 
 }  // namespace asx

@@ -46,3 +46,27 @@ def test_workspace_bytes_and_param_validation():
     assert L.as_predict_query(None, C.byref(ok), None, None, None, None) == 1
     assert L.as_select_step(None, C.byref(ok), None, None, None, None, None, None) == 1
     assert L.as_status_str(3).decode() == "ctx workspace too small"
+
+
+def test_pack_workspace_and_share_plan():
+    """Host logic of the depth-wise packed selection: workspace sizes and the share plan."""
+    L = api.lib()
+    small = api.make_params(1, 8, 2, 8, 256, 256)          # BASELINE configs[0] shape
+    big = api.make_params(32, 32, 8, 16, 2048, 2048)       # configs[2] shape
+    assert api.as_workspace_bytes_pack(small, 1) == api.as_workspace_bytes(small)
+    assert api.as_workspace_bytes_pack(small, 0) == 0
+    assert api.as_workspace_bytes_pack(small, api.AS_MAX_PACK + 1) == 0
+    for n in range(2, api.AS_MAX_PACK + 1):                # one q_hat block per layer + the pack's candidates
+        shares, cand = api.select_plan(small, n)[1:]
+        need = n * 8 * 128 * 4 + (n * 2 * shares * (cand * 8 + 4) if shares > 1 else 0)
+        assert api.as_workspace_bytes_pack(small, n) >= need
+    # a batch that fills the chip keeps whole rows; a single short sequence is cut into shares, fewer
+    # of them when more layers share the launch
+    assert api.select_plan(big, 1)[1] == 1 and api.select_plan(big, 12)[1] == 1
+    one, twelve = api.select_plan(small, 1), api.select_plan(small, 12)
+    assert one[1] > twelve[1] >= 1
+    for n in (1, 4, 16):
+        share, shares, cand = api.select_plan(small, n)
+        assert share * shares >= 4096 and share % 64 == 0 and cand == min(256, share)
+    # null layer array / bad pack sizes are rejected before anything touches the device
+    assert L.as_select_step_pack(None, C.byref(small), None, 1, None) == 1
