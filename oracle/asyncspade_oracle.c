@@ -20,6 +20,10 @@
  *   top-k    Sec. 4.3 item (2): the C highest-scoring tokens per KV head.
  *   attend   softmax(q K_S^T * scale) V_S over the selected set S (Sec. 4.1;
  *            Appendix B counts exactly this work, 4*q*h*C flops).
+ * Around them (data movement and set arithmetic, no floating point beyond one quotient):
+ *   overlap  Sec. 3 Eq. 1, the overlap ratio of two selections;
+ *   append / push   the cache rank's per-step state update (Sec. 4.1 workflow);
+ *   gather   KV re-organisation for the filtered tokens (Sec. 4.3, cache-rank item (3)).
  *
  * Pins (tests/test_oracle_*.py): closed forms of the predictor on hand-built
  * windows, numpy.linalg.solve, brute-force argsort, numpy GEMV, dense attention
@@ -327,6 +331,106 @@ int aso_sparse_decode_attn(int B, int Hq, int Hkv, int D, int P, int C, const ui
       if (lse) lse[(size_t)b * Hq + h] = (float)(m + log(z));
       free(toks); free(logit); free(acc);
     }
+  return 0;
+}
+
+/*
+ * Overlap ratio of two selections (Sec. 3, Eq. 1): O = |S_a intersect S_b| / |S|, with |S| the
+ * common size of the two sets (the larger one if they differ; 0 / 0 is reported as 0).
+ * Plain double loop over both index lists; entries are token indices, order irrelevant.
+ *   idx_a, idx_b int32 [B][Hkv][C]; cnt_a, cnt_b int32 [B][Hkv]
+ *   inter int32 [B][Hkv] out; ratio fp32 [B][Hkv] out (the fp32 quotient of the two integers)
+ */
+int aso_overlap_ratio(int B, int Hkv, int C, const int32_t* idx_a, const int32_t* cnt_a,
+                      const int32_t* idx_b, const int32_t* cnt_b, int32_t* inter, float* ratio) {
+  for (int r = 0; r < B * Hkv; ++r) {
+    const int32_t* a = idx_a + (size_t)r * C;
+    const int32_t* b = idx_b + (size_t)r * C;
+    int na = cnt_a[r], nb = cnt_b[r], common = 0;
+    for (int i = 0; i < na; ++i) {
+      int hit = 0;
+      for (int k = 0; k < nb; ++k) if (b[k] == a[i]) hit = 1;
+      common += hit;
+    }
+    int den = na > nb ? na : nb;
+    inter[r] = common;
+    ratio[r] = den > 0 ? (float)common / (float)den : 0.0f;
+  }
+  return 0;
+}
+
+/*
+ * Cache-side state updates of one decode step (Sec. 4.1, workflow: the cache rank appends the
+ * step's key / value states to the KV cache and enqueues its query state to the sliding window).
+ *
+ * aso_kv_append: for every sequence with room (ctx_lens[b] < P * max_pages) the new token's
+ * K and V rows are stored at position n = ctx_lens[b] and ctx_lens[b] becomes n + 1; a
+ * sequence without room is left as it is.
+ *   k_new, v_new bf16 [B][Hkv][D]
+ */
+int aso_kv_append(int B, int Hkv, int D, int P, uint16_t* k_pool, uint16_t* v_pool,
+                  const int32_t* block_table, int max_pages, int32_t* ctx_lens,
+                  const uint16_t* k_new, const uint16_t* v_new) {
+  for (int b = 0; b < B; ++b) {
+    int n = ctx_lens[b];
+    if (n < 0 || n >= P * max_pages) continue;
+    int64_t page = block_table[(int64_t)b * max_pages + n / P];
+    for (int j = 0; j < Hkv; ++j) {
+      int64_t off = ((page * Hkv + j) * P + n % P) * (int64_t)D;
+      for (int d = 0; d < D; ++d) {
+        k_pool[off + d] = k_new[((size_t)b * Hkv + j) * D + d];
+        v_pool[off + d] = v_new[((size_t)b * Hkv + j) * D + d];
+      }
+    }
+    ctx_lens[b] = n + 1;
+  }
+  return 0;
+}
+
+/*
+ * aso_window_push: the window slides by one token: the oldest query leaves, the previous
+ * current query becomes the newest window entry and q_new becomes the current query.
+ *   q_win bf16 [B][Hq][W][D] oldest first (in place); q_cur bf16 [B][Hq][D] (in place);
+ *   q_new bf16 [B][Hq][D]
+ */
+int aso_window_push(int B, int Hq, int W, int D, uint16_t* q_win, uint16_t* q_cur, const uint16_t* q_new) {
+  for (int bh = 0; bh < B * Hq; ++bh) {
+    uint16_t* win = q_win + (size_t)bh * W * D;
+    uint16_t* cur = q_cur + (size_t)bh * D;
+    for (int i = 0; i + 1 < W; ++i)
+      for (int d = 0; d < D; ++d) win[(size_t)i * D + d] = win[(size_t)(i + 1) * D + d];
+    for (int d = 0; d < D; ++d) win[(size_t)(W - 1) * D + d] = cur[d];
+    for (int d = 0; d < D; ++d) cur[d] = q_new[(size_t)bh * D + d];
+  }
+  return 0;
+}
+
+/*
+ * KV re-organisation for the filtered tokens (Sec. 4.3, cache-rank item (3)): the selected
+ * rows are copied, in selection order, into a compact paged pool of Cp = ceil(C / P) pages per
+ * sequence: token i of (b, j) goes to page b * Cp + i / P, slot i % P.
+ *   k_out, v_out bf16 [B * Cp][Hkv][P][D]; slots at and beyond sel_cnt are left untouched
+ *   out_table int32 [B][Cp] = b * Cp + i;  out_lens int32 [B] = sel_cnt[b][0]
+ */
+int aso_gather_kv(int B, int Hkv, int D, int P, int C, const uint16_t* k_pool, const uint16_t* v_pool,
+                  const int32_t* block_table, int max_pages, const int32_t* sel_idx,
+                  const int32_t* sel_cnt, uint16_t* k_out, uint16_t* v_out, int32_t* out_table,
+                  int32_t* out_lens) {
+  int Cp = (C + P - 1) / P;
+  for (int b = 0; b < B; ++b) {
+    for (int i = 0; i < Cp; ++i) out_table[(size_t)b * Cp + i] = b * Cp + i;
+    out_lens[b] = sel_cnt[(size_t)b * Hkv];
+    for (int j = 0; j < Hkv; ++j) {
+      int cnt = sel_cnt[(size_t)b * Hkv + j];
+      for (int i = 0; i < cnt; ++i) {
+        int n = sel_idx[((size_t)b * Hkv + j) * C + i];
+        const uint16_t* kr = token_ptr(k_pool, block_table, max_pages, Hkv, P, D, b, j, n);
+        const uint16_t* vr = token_ptr(v_pool, block_table, max_pages, Hkv, P, D, b, j, n);
+        int64_t off = ((((int64_t)b * Cp + i / P) * Hkv + j) * P + i % P) * (int64_t)D;
+        for (int d = 0; d < D; ++d) { k_out[off + d] = kr[d]; v_out[off + d] = vr[d]; }
+      }
+    }
+  }
   return 0;
 }
 

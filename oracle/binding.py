@@ -34,6 +34,8 @@ def _load():
         _lib.aso_sparse_decode_attn.restype = C.c_int
         _lib.aso_ridge_weights.restype = C.c_int
         _lib.aso_set_threads.restype = C.c_int
+        for fn in ("aso_overlap_ratio", "aso_kv_append", "aso_window_push", "aso_gather_kv"):
+            getattr(_lib, fn).restype = C.c_int
         _lib.aso_f64_to_bf16.restype = C.c_uint16
         _lib.aso_f64_to_bf16.argtypes = [C.c_double]
     return _lib
@@ -133,3 +135,54 @@ def select_step(k_pool, block_table, ctx_lens, q_win, q_cur, budget: int, eps: f
     scores = score_keys(k_pool, block_table, ctx_lens, q_hat, k_pool.shape[1], agg)
     sel_idx, sel_cnt = topk_select(scores, ctx_lens, budget)
     return q_hat, scores, sel_idx, sel_cnt
+
+
+def overlap_ratio(idx_a, cnt_a, idx_b, cnt_b):
+    """Eq. 1 per (b, kv head): returns (|S_a & S_b| int32 [B,Hkv], ratio fp32 [B,Hkv])."""
+    B, Hkv, Cb = idx_a.shape
+    inter = torch.empty((B, Hkv), dtype=torch.int32)
+    ratio = torch.empty((B, Hkv), dtype=torch.float32)
+    rc = _load().aso_overlap_ratio(C.c_int(B), C.c_int(Hkv), C.c_int(Cb), _p(idx_a.contiguous()),
+                                   _p(cnt_a.contiguous()), _p(idx_b.contiguous()), _p(cnt_b.contiguous()),
+                                   _p(inter), _p(ratio))
+    if rc != 0:
+        raise RuntimeError(f"aso_overlap_ratio rc={rc}")
+    return inter, ratio
+
+
+def kv_append(k_pool, v_pool, block_table, ctx_lens, k_new, v_new):
+    """In place on k_pool, v_pool and ctx_lens (host tensors)."""
+    num_pages, Hkv, P, D = k_pool.shape
+    B = ctx_lens.shape[0]
+    rc = _load().aso_kv_append(C.c_int(B), C.c_int(Hkv), C.c_int(D), C.c_int(P), _p(k_pool), _p(v_pool),
+                               _p(block_table.contiguous()), C.c_int(block_table.shape[1]), _p(ctx_lens),
+                               _p(k_new.contiguous()), _p(v_new.contiguous()))
+    if rc != 0:
+        raise RuntimeError(f"aso_kv_append rc={rc}")
+
+
+def window_push(q_win, q_cur, q_new):
+    """In place on q_win and q_cur (host tensors)."""
+    B, Hq, W, D = q_win.shape
+    rc = _load().aso_window_push(C.c_int(B), C.c_int(Hq), C.c_int(W), C.c_int(D), _p(q_win), _p(q_cur),
+                                 _p(q_new.contiguous()))
+    if rc != 0:
+        raise RuntimeError(f"aso_window_push rc={rc}")
+
+
+def gather_kv(k_pool, v_pool, block_table, sel_idx, sel_cnt, fill: float = 0.0):
+    """Returns (k_out, v_out [B*Cp,Hkv,P,D] bf16 pre-filled with `fill`, out_table [B,Cp], out_lens [B])."""
+    num_pages, Hkv, P, D = k_pool.shape
+    B, _, Cb = sel_idx.shape
+    Cp = (Cb + P - 1) // P
+    k_out = torch.full((B * Cp, Hkv, P, D), fill, dtype=torch.bfloat16)
+    v_out = torch.full((B * Cp, Hkv, P, D), fill, dtype=torch.bfloat16)
+    table = torch.empty((B, Cp), dtype=torch.int32)
+    lens = torch.empty((B,), dtype=torch.int32)
+    rc = _load().aso_gather_kv(C.c_int(B), C.c_int(Hkv), C.c_int(D), C.c_int(P), C.c_int(Cb), _p(k_pool.contiguous()),
+                               _p(v_pool.contiguous()), _p(block_table.contiguous()), C.c_int(block_table.shape[1]),
+                               _p(sel_idx.contiguous()), _p(sel_cnt.contiguous()), _p(k_out), _p(v_out), _p(table),
+                               _p(lens))
+    if rc != 0:
+        raise RuntimeError(f"aso_gather_kv rc={rc}")
+    return k_out, v_out, table, lens
