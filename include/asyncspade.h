@@ -130,6 +130,16 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
                                 const int32_t* sel_ctx_lens, void* out, float* lse, void* stream);
 
 /*
+ * Dense decode attention over the whole cache, tokens [0, ctx_lens[b]): the full-attention
+ * baseline the method is measured against (Appendix B: 4*q*h*T per layer instead of 4*q*h*C),
+ * and the call that reads a compact pool written by as_gather_kv.  Same kernels, layouts and
+ * precision as as_sparse_decode_attn; the work is split over the longest context the block
+ * table allows (16 * max_pages_per_seq).
+ */
+as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
+                               float* lse, void* stream);
+
+/*
  * Scoring and top-k in one pass (Alg. 1 step 7 + Sec. 4.3 item (2)): same result as
  * as_score_keys followed by as_topk_select, but the per-token scores never leave the chip
  * (rows are scored in slices whose keys stay in LDS; only per-slice candidates, 8 B each,
@@ -170,6 +180,51 @@ typedef struct {
 size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers);
 as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io* layers, int32_t n_layers,
                               void* stream);
+
+/*
+ * Cache-side state update of one decode step (Sec. 4.1, workflow: the cache rank appends the
+ * step's key / value states to the KV cache and enqueues its query state to the sliding window).
+ *
+ * as_kv_append: for every sequence b with room (ctx_lens[b] < 16 * max_pages_per_seq) the rows
+ * k_new[b][j], v_new[b][j] are stored at token position n = ctx_lens[b] (page
+ * block_table[b][n / 16], which the caller's allocator must have mapped) and ctx_lens[b]
+ * becomes n + 1.  A sequence without room is left unchanged.  The pools and ctx_lens are
+ * written: calls that read them on other streams must be ordered after this one by the caller.
+ *   k_pool, v_pool bf16 [num_pages][Hkv][16][128] (in place); ctx_lens int32 [B] (in place)
+ *   k_new, v_new   bf16 [B][Hkv][128]
+ *
+ * as_window_push: q_win loses its oldest entry, the previous q_cur becomes its newest entry and
+ * q_new becomes q_cur (all in place; q_new may not alias q_cur).
+ */
+as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
+                       int32_t* ctx_lens, int64_t num_pages, const void* k_new, const void* v_new, void* stream);
+as_status as_window_push(as_ctx* ctx, const as_params* p, void* q_win, void* q_cur, const void* q_new,
+                         void* stream);
+
+/*
+ * KV re-organisation for the filtered tokens (Sec. 4.3, cache-rank item (3)): copies the
+ * selected K and V rows, in selection order, into a compact paged pool that any paged decode
+ * kernel can read contiguously.  With Cp = ceil(budget / 16) pages per sequence, token i of
+ * (b, j) goes to page b * Cp + i / 16, slot i % 16; slots at and beyond sel_cnt[b][j] are left
+ * untouched.  out_table / out_lens describe the compact pool as a cache view of its own
+ * (out_table[b][i] = b * Cp + i, out_lens[b] = sel_cnt[b][0]): as_dense_decode_attn over that
+ * view, with max_pages_per_seq = Cp, is attention over exactly the selected tokens.
+ *   k_out, v_out bf16 [B * Cp][Hkv][16][128];  out_table int32 [B][Cp];  out_lens int32 [B]
+ */
+as_status as_gather_kv(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const int32_t* sel_idx,
+                       const int32_t* sel_cnt, void* k_out, void* v_out, int32_t* out_table, int32_t* out_lens,
+                       void* stream);
+
+/*
+ * Overlap ratio of two selections (Sec. 3, Eq. 1): per (b, j), inter = |S_a intersect S_b| and
+ * ratio = inter / |S|, |S| being the common set size (the larger of the two counts if they
+ * differ; 0 / 0 gives 0).  Both index lists must be ascending, as the selection calls emit them.
+ *   idx_a, idx_b int32 [B][Hkv][C]; cnt_a, cnt_b int32 [B][Hkv]
+ *   inter int32 [B][Hkv] out; ratio nullable fp32 [B][Hkv] out
+ */
+as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a, const int32_t* cnt_a,
+                           const int32_t* idx_b, const int32_t* cnt_b, int32_t* inter, float* ratio,
+                           void* stream);
 
 #ifdef __cplusplus
 }

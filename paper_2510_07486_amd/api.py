@@ -20,7 +20,8 @@ _lib = None
 AS_AGG_MAX, AS_AGG_SUM = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
            "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",
-           "as_select_step_pack"]
+           "as_select_step_pack", "as_kv_append", "as_window_push", "as_gather_kv", "as_overlap_ratio",
+           "as_dense_decode_attn"]
 AS_MAX_PACK = 16
 
 
@@ -73,6 +74,8 @@ def lib():
         L.as_topk_select.argtypes = [vp, PP, vp, C.c_int64, vp, vp, vp, vp]
         L.as_sparse_decode_attn.restype = C.c_int
         L.as_sparse_decode_attn.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp, vp, vp]
+        L.as_dense_decode_attn.restype = C.c_int
+        L.as_dense_decode_attn.argtypes = [vp, PP, KP, vp, vp, vp, vp]
         L.as_score_topk.restype = C.c_int
         L.as_score_topk.argtypes = [vp, PP, KP, vp, vp, vp, vp]
         L.as_select_step.restype = C.c_int
@@ -81,6 +84,14 @@ def lib():
         L.as_workspace_bytes_pack.argtypes = [PP, C.c_int32]
         L.as_select_step_pack.restype = C.c_int
         L.as_select_step_pack.argtypes = [vp, PP, C.POINTER(AsLayerIo), C.c_int32, vp]
+        L.as_kv_append.restype = C.c_int
+        L.as_kv_append.argtypes = [vp, PP, vp, vp, vp, vp, C.c_int64, vp, vp, vp]
+        L.as_window_push.restype = C.c_int
+        L.as_window_push.argtypes = [vp, PP, vp, vp, vp, vp]
+        L.as_gather_kv.restype = C.c_int
+        L.as_gather_kv.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp, vp, vp]
+        L.as_overlap_ratio.restype = C.c_int
+        L.as_overlap_ratio.argtypes = [vp, PP, vp, vp, vp, vp, vp, vp, vp]
         L.as_debug_select_plan.restype = C.c_int
         L.as_debug_select_plan.argtypes = [PP, C.c_int, C.POINTER(C.c_int32)]
         L.as_debug_set_score_variant.restype = C.c_int
@@ -211,6 +222,16 @@ def as_sparse_decode_attn(ctx: Context, p: AsParams, kv: AsKvView, q, sel_idx, s
     return out, lse
 
 
+def as_dense_decode_attn(ctx: Context, p: AsParams, kv: AsKvView, q, out=None, lse=None, stream=None, want_lse=True):
+    if out is None:
+        out = torch.empty((p.batch, p.n_q_heads, p.head_dim), dtype=torch.bfloat16, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((p.batch, p.n_q_heads), dtype=torch.float32, device=q.device)
+    _check(lib().as_dense_decode_attn(ctx.handle, C.byref(p), C.byref(kv), _ptr(q), _ptr(out), _ptr(lse),
+                                      _stream(stream)), "as_dense_decode_attn")
+    return out, lse
+
+
 def as_score_topk(ctx: Context, p: AsParams, kv: AsKvView, q_hat, sel_idx=None, sel_cnt=None, stream=None):
     if sel_idx is None:
         sel_idx = torch.empty((p.batch, p.n_kv_heads, p.budget), dtype=torch.int32, device=q_hat.device)
@@ -243,3 +264,47 @@ def as_select_step_pack(ctx: Context, p: AsParams, layers, stream=None):
         layers = (AsLayerIo * len(layers))(*layers)
     _check(lib().as_select_step_pack(ctx.handle, C.byref(p), layers, len(layers), _stream(stream)),
            "as_select_step_pack")
+
+
+def as_kv_append(ctx: Context, p: AsParams, k_pool, v_pool, block_table, ctx_lens, k_new, v_new, stream=None):
+    """In place on k_pool, v_pool and ctx_lens."""
+    _check(lib().as_kv_append(ctx.handle, C.byref(p), _ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(ctx_lens),
+                              k_pool.shape[0], _ptr(k_new), _ptr(v_new), _stream(stream)), "as_kv_append")
+
+
+def as_window_push(ctx: Context, p: AsParams, q_win, q_cur, q_new, stream=None):
+    """In place on q_win and q_cur."""
+    _check(lib().as_window_push(ctx.handle, C.byref(p), _ptr(q_win), _ptr(q_cur), _ptr(q_new), _stream(stream)),
+           "as_window_push")
+
+
+def compact_pages(p: AsParams) -> int:
+    return (p.budget + p.page_size - 1) // p.page_size
+
+
+def as_gather_kv(ctx: Context, p: AsParams, kv: AsKvView, sel_idx, sel_cnt, k_out=None, v_out=None, out_table=None,
+                 out_lens=None, stream=None):
+    Cp = compact_pages(p)
+    dev = sel_idx.device
+    shape = (p.batch * Cp, p.n_kv_heads, p.page_size, p.head_dim)
+    if k_out is None:
+        k_out = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    if v_out is None:
+        v_out = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    if out_table is None:
+        out_table = torch.empty((p.batch, Cp), dtype=torch.int32, device=dev)
+    if out_lens is None:
+        out_lens = torch.empty((p.batch,), dtype=torch.int32, device=dev)
+    _check(lib().as_gather_kv(ctx.handle, C.byref(p), C.byref(kv), _ptr(sel_idx), _ptr(sel_cnt), _ptr(k_out),
+                              _ptr(v_out), _ptr(out_table), _ptr(out_lens), _stream(stream)), "as_gather_kv")
+    return k_out, v_out, out_table, out_lens
+
+
+def as_overlap_ratio(ctx: Context, p: AsParams, idx_a, cnt_a, idx_b, cnt_b, inter=None, ratio=None, stream=None):
+    if inter is None:
+        inter = torch.empty((p.batch, p.n_kv_heads), dtype=torch.int32, device=idx_a.device)
+    if ratio is None:
+        ratio = torch.empty((p.batch, p.n_kv_heads), dtype=torch.float32, device=idx_a.device)
+    _check(lib().as_overlap_ratio(ctx.handle, C.byref(p), _ptr(idx_a), _ptr(cnt_a), _ptr(idx_b), _ptr(cnt_b),
+                                  _ptr(inter), _ptr(ratio), _stream(stream)), "as_overlap_ratio")
+    return inter, ratio

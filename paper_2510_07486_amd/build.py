@@ -10,7 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasyncspade.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip"]
+SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip",
+           "cache_ops.hip"]
 
 
 def _run(cmd, verbose):

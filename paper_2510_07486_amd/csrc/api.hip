@@ -148,6 +148,19 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
                                      static_cast<hipStream_t>(stream)));
 }
 
+as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
+                               float* lse, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, true)) != AS_OK) return st;
+  if (!ctx || !q || !out) return AS_ERR_INVALID_ARG;
+  const ws_layout l = layout_of(p);
+  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), nullptr, nullptr, nullptr,
+                                     static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
+                                     static_cast<hipStream_t>(stream)));
+}
+
 as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat, int32_t* sel_idx,
                         int32_t* sel_cnt, void* stream) {
   as_status st = check_params(p);
@@ -220,6 +233,48 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
   hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
   if (e != hipSuccess) return AS_ERR_HIP;
   return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand, s));
+}
+
+as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
+                       int32_t* ctx_lens, int64_t num_pages, const void* k_new, const void* v_new, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !k_pool || !v_pool || !block_table || !ctx_lens || !k_new || !v_new || num_pages < 1)
+    return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_kv_append(p, static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool),
+                                          block_table, ctx_lens, num_pages, static_cast<const uint16_t*>(k_new),
+                                          static_cast<const uint16_t*>(v_new), static_cast<hipStream_t>(stream)));
+}
+
+as_status as_window_push(as_ctx* ctx, const as_params* p, void* q_win, void* q_cur, const void* q_new,
+                         void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !q_win || !q_cur || !q_new || q_new == q_cur) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_window_push(p, static_cast<uint16_t*>(q_win), static_cast<uint16_t*>(q_cur),
+                                            static_cast<const uint16_t*>(q_new), static_cast<hipStream_t>(stream)));
+}
+
+as_status as_gather_kv(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const int32_t* sel_idx,
+                       const int32_t* sel_cnt, void* k_out, void* v_out, int32_t* out_table, int32_t* out_lens,
+                       void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, true)) != AS_OK) return st;
+  if (!ctx || !sel_idx || !sel_cnt || !k_out || !v_out || !out_table || !out_lens) return AS_ERR_INVALID_ARG;
+  if (k_out == kv->k_pool || v_out == kv->v_pool) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_gather_kv(p, kv, sel_idx, sel_cnt, static_cast<uint16_t*>(k_out),
+                                          static_cast<uint16_t*>(v_out), out_table, out_lens,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a, const int32_t* cnt_a,
+                           const int32_t* idx_b, const int32_t* cnt_b, int32_t* inter, float* ratio, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if (!ctx || !idx_a || !cnt_a || !idx_b || !cnt_b || !inter) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_overlap(p, idx_a, cnt_a, idx_b, cnt_b, inter, ratio,
+                                        static_cast<hipStream_t>(stream)));
 }
 
 // Development knobs (not part of the documented ABI): pick the key-scoring kernel variant of

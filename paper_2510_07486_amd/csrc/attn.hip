@@ -29,10 +29,43 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __host__ __device__ inline int attn_nsplit(int C) { return (C + AT_SPLIT - 1) / AT_SPLIT + 1; }
 static inline int attn_gh(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 
-// partial outputs and partial (m, l) pairs
+static int g_attn_impl = 0;  // 0: matrix-core kernel (attn_mfma.hip), 1: vector-ALU kernel below
+
+// Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head):
+// about six workgroups per compute unit, so that per-split costs (partials through HBM, query
+// fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens.  One
+// extra split at the end takes whatever lies beyond list_len (the dense tail of a sparse call).
+struct attn_geom { int nsplit, split_tokens; };
+static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  if (list_len < 1) list_len = 1;
+  int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? 1 : G / attn_gh(G));
+  if (pairs < 1) pairs = 1;
+  int64_t nsel = (1536 + pairs - 1) / pairs;
+  const int64_t max_sel = (list_len + AT_SPLIT - 1) / AT_SPLIT;
+  if (nsel > max_sel) nsel = max_sel;
+  if (nsel < 1) nsel = 1;
+  int64_t split_tokens = (list_len + nsel - 1) / nsel;
+  split_tokens = (split_tokens + AT_CHUNK - 1) / AT_CHUNK * AT_CHUNK;
+  if (split_tokens < AT_SPLIT) split_tokens = AT_SPLIT;
+  attn_geom g;
+  g.split_tokens = (int)split_tokens;
+  g.nsplit = (int)((list_len + split_tokens - 1) / split_tokens) + 1;
+  return g;
+}
+
+// partial outputs and partial (m, l) pairs, for the sparse call (list = budget) and the dense one
+// (list = longest context the block table allows), under either kernel
 size_t attn_workspace_bytes(const as_params* p) {
-  size_t heads = (size_t)p->batch * p->n_q_heads;
+  const size_t heads = (size_t)p->batch * p->n_q_heads;
   size_t ns = (size_t)attn_nsplit(p->budget);
+  const int keep = g_attn_impl;
+  for (int impl = 0; impl < 2; ++impl) {
+    g_attn_impl = impl;
+    const size_t nd = (size_t)attn_geometry(p, (int64_t)p->max_pages_per_seq * AS_PAGE).nsplit;
+    if (nd > ns) ns = nd;
+  }
+  g_attn_impl = keep;
   return heads * ns * (AS_HEAD_DIM + 2) * sizeof(float);
 }
 
@@ -88,9 +121,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
   const int raw_first = fetch_index(split * cps);  // speculative: validated once the lengths are known
 
   const int N = clamp_ctx(ctx_lens[b], max_pages);
-  int cnt = sel_cnt[b * Hkv + j];
+  int cnt = sel_cnt ? sel_cnt[b * Hkv + j] : 0;   // no selection arrays: dense attention over [0, N)
   cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
-  int tail0 = sel_ctx_lens ? sel_ctx_lens[b] : N;
+  int tail0 = sel_idx ? (sel_ctx_lens ? sel_ctx_lens[b] : N) : 0;
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);
   const int nchunks = (L + AT_CHUNK - 1) / AT_CHUNK;
@@ -280,7 +313,8 @@ static hipError_t launch_attn_gh(const as_params* p, const as_kv_view* kv, const
   dim3 grid(nsplit, p->n_kv_heads * (G / GH), p->batch);
   hipLaunchKernelGGL(attn_split_kernel<GH>, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
-                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, p->budget, p->max_pages_per_seq,
+                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0,
+                     p->max_pages_per_seq,
                      p->sm_scale, nsplit, cps, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
   return hipGetLastError();
 }
@@ -289,27 +323,19 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
                             int nsplit, int split_tokens, hipStream_t s);
 
-static int g_attn_impl = 0;  // development knob: 0 = matrix-core kernel (attn_mfma.hip), 1 = vector-ALU kernel
-extern "C" void as_debug_set_attn_impl(int v) { g_attn_impl = v; }
+extern "C" void as_debug_set_attn_impl(int v) { g_attn_impl = v; }   // development knob
 
+// sel_idx == nullptr: dense attention over [0, ctx_lens[b]) (the token list is only the "tail", from 0)
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
                        hipStream_t s) {
   const int64_t heads = (int64_t)p->batch * p->n_q_heads;
   if (heads == 0) return hipSuccess;
   const int G = p->n_q_heads / p->n_kv_heads;
-  // split size: about six workgroups per compute unit, so that per-split costs (partials through HBM,
-  // query fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens
-  const int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? 1 : G / attn_gh(G));
-  int64_t nsel = (1536 + pairs - 1) / pairs;
-  const int64_t max_sel = (p->budget + AT_SPLIT - 1) / AT_SPLIT;
-  if (nsel > max_sel) nsel = max_sel;
-  if (nsel < 1) nsel = 1;
-  int split_tokens = (int)((p->budget + nsel - 1) / nsel);
-  split_tokens = (split_tokens + AT_CHUNK - 1) / AT_CHUNK * AT_CHUNK;
-  if (split_tokens < AT_SPLIT) split_tokens = AT_SPLIT;
+  const bool dense = sel_idx == nullptr;
+  const attn_geom gm = attn_geometry(p, dense ? (int64_t)p->max_pages_per_seq * AS_PAGE : (int64_t)p->budget);
+  const int nsplit = gm.nsplit, split_tokens = gm.split_tokens;
   const int cps = split_tokens / AT_CHUNK;
-  const int nsplit = (p->budget + split_tokens - 1) / split_tokens + 1;   // <= attn_nsplit(budget)
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
   hipError_t e;

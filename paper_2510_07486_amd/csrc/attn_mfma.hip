@@ -57,9 +57,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   const int raw_first = fetch_index(w);       // speculative: validated once the lengths are known
 
   const int N = clamp_ctx(ctx_lens[b], max_pages);
-  int cnt = sel_cnt[b * Hkv + j];
+  int cnt = sel_cnt ? sel_cnt[b * Hkv + j] : 0;   // no selection arrays: dense attention over [0, N)
   cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
-  int tail0 = sel_ctx_lens ? sel_ctx_lens[b] : N;
+  int tail0 = sel_idx ? (sel_ctx_lens ? sel_ctx_lens[b] : N) : 0;
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);
   const int t_begin = split * split_tokens;
@@ -242,7 +242,8 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
   dim3 grid(nsplit, p->n_kv_heads, p->batch);
   hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
-                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, p->budget, p->max_pages_per_seq,
+                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0,
+                     p->max_pages_per_seq,
                      p->sm_scale, nsplit, split_tokens, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
   return hipGetLastError();
 }

@@ -86,4 +86,15 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
                        hipStream_t s);
 
+// cache-side bookkeeping (cache_ops.hip)
+hipError_t launch_kv_append(const as_params* p, uint16_t* k_pool, uint16_t* v_pool, const int32_t* block_table,
+                            int32_t* ctx_lens, int64_t num_pages, const uint16_t* k_new, const uint16_t* v_new,
+                            hipStream_t s);
+hipError_t launch_window_push(const as_params* p, uint16_t* q_win, uint16_t* q_cur, const uint16_t* q_new,
+                              hipStream_t s);
+hipError_t launch_gather_kv(const as_params* p, const as_kv_view* kv, const int32_t* sel_idx, const int32_t* sel_cnt,
+                            uint16_t* k_out, uint16_t* v_out, int32_t* out_table, int32_t* out_lens, hipStream_t s);
+hipError_t launch_overlap(const as_params* p, const int32_t* idx_a, const int32_t* cnt_a, const int32_t* idx_b,
+                          const int32_t* cnt_b, int32_t* inter, float* ratio, hipStream_t s);
+
 }  // namespace asx
