@@ -2,22 +2,26 @@
 // top-k, Sec. 4.3 items (1)-(2)), without ever writing the per-token scores to HBM
 // (interleaving 4 B/token of score writes with the K stream costs about 15 % of the read rate).
 //
-// Each (sequence, KV head) row is cut into shares; one workgroup owns a share and walks it in
-// sub-slices of 4096 (512 threads) or 8192 (1024 threads) tokens.  Per sub-slice it streams
-// the K pages (coalesced non-temporal 128-bit loads, transposed through a per-wave 4 KB LDS
-// image into the MFMA operand layout, see score_common.hpp), keeps the 32-bit order-preserving
-// keys of the scores in LDS and accumulates the first radix histogram while it streams.  Then an
-// exact radix select in LDS over (running set R of the best <= C so far) + (new keys) yields the
-// new R, ascending by token.  After the last sub-slice R goes out: straight into sel_idx when
-// the row has a single share, otherwise as (key, index) candidates that a small merge kernel
-// reduces to the row's top-C.  The top-C of a row is contained in the union of the top-C of its
-// parts and every level resolves equal keys to the lowest index, so the result equals a full
+// Each (sequence, KV head) row is cut into shares; one workgroup owns a share.  It streams the
+// K pages (coalesced non-temporal 128-bit loads, transposed through a per-wave 4 KB LDS image into
+// the MFMA operand layout, see score_common.hpp) and appends (order-preserving 32-bit key, token)
+// pairs to an unordered candidate buffer in LDS (one LDS atomic per wavefront reserves the slots).
+// When the buffer is nearly full, a prune keeps exactly the best C pairs (radix threshold on the
+// key over register-held candidates, ties resolved by a second radix threshold on the token) and
+// its threshold tau then filters the stream: a later token can only matter if its key exceeds tau,
+// so the inflow decays like C / tokens-seen and a 32768-token share typically needs one prune and
+// the final selection, instead of one selection per 8192 tokens.  Because tokens are unique, the
+// pairs are totally ordered by (key descending, token ascending): the result does not depend on
+// the order in which wavefronts appended.  The final selection is put into ascending token order
+// through a bitmap of the share (rank of a token = set bits below it) and goes out: straight into
+// sel_idx when the row has a single share, otherwise as (key, token) candidates that a small merge
+// kernel reduces to the row's top-C.  The top-C of a row is contained in the union of the top-C of
+// its parts and every level resolves equal keys to the lowest token, so the result equals a full
 // sort of the row.  HBM traffic: one read of K plus 8 B per candidate of a multi-share row.
 //
-// Budgets above the running-set capacity (2048 / 4096) use shares of one sub-slice, whose local
-// top-min(C, sub-slice) needs no running set.  The first sub-slice of a long share has a
-// pseudo-random shorter length so that the select phases of the workgroups sharing a compute
-// unit do not coincide and hide behind each other's streaming.
+// Pruning needs C <= half the buffer (2048 / 4096 pairs for 512 / 1024 threads); larger budgets
+// use shares that fit the buffer whole.  The first sub-slice of a long share has a pseudo-random
+// shorter length so that the prune phases of different compute units do not coincide.
 #include "common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
@@ -26,9 +30,9 @@ namespace asx {
 
 template <int THREADS> struct fs_shape {
   static constexpr int WAVES = THREADS / 64;
-  static constexpr int SSUB = THREADS * 8;                // tokens per sub-slice (keys: 4 B each)
-  static constexpr int RCAP = THREADS * 4;                // running-set capacity (key + index)
-  static constexpr int B0 = 11;                           // bits of the histogram built while streaming
+  static constexpr int CAP = THREADS * 8;                 // candidate buffer, (key, token) pairs
+  static constexpr int RCAP = THREADS * 4;                // largest budget served by pruning (a prune frees >= CAP / 2)
+  static constexpr int B0 = 11;                           // bits of the first radix pass
   static constexpr int BINS = 1 << B0;
   static constexpr int SHARE_CAP = THREADS * 32;          // tokens per share (balance of ragged batches)
 };
@@ -72,10 +76,10 @@ static select_plan plan_for(const as_params* p, int thr, int n_layers) {
     sl = (sl + 63) / 64 * 64;
     if (sl < 256) sl = 256;
     if (sl > share_cap) sl = share_cap;
-    if (p->budget > rcap && sl > ssub) sl = ssub;   // no running set: one sub-slice per share
+    if (p->budget > rcap && sl > ssub) sl = ssub;   // pruning needs C <= half the buffer: else one sub-slice per share
     const int64_t nsh = (max_ctx + sl - 1) / sl > 0 ? (max_ctx + sl - 1) / sl : 1;
     if (nsh > FS_MAX_SLICES) continue;
-    const int64_t nsub = (sl + ssub - 1) / ssub;
+    const int64_t nsub = sl > ssub ? 2 : 1;         // typical selections per share: one prune + the final one
     double t = 0.0;
     for (int64_t left = rows * nsh; left > 0; left -= slots) {
       const double fill = (double)(left < slots ? left : slots) / (double)slots;
@@ -115,19 +119,85 @@ size_t select_workspace_bytes(const as_params* p, int n_layers) {
   return best;
 }
 
+// ---- exact selection over an unordered candidate buffer ----------------------------------------
+// Candidates are (key, token) pairs in arbitrary order.  Tokens are unique, so the pairs are totally
+// ordered by (key descending, token ascending) and "the best `keep`" is unique: every pair with
+// key > T, plus the r pairs with the lowest tokens among those with key == T.
+
+// Value of the want-th largest of the (up to NPT per thread) values held in registers, over the
+// whole workgroup: three histogram passes (B0 bits, then the rest in two halves).  Returns T;
+// `r` = how many values equal to T are still wanted, `ties` = how many values equal T.
+template <int THREADS, int B0, int NPT>
+__device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], const bool (&ok)[NPT], uint32_t want,
+                                                    uint32_t* hist, uint32_t* xch, uint32_t& r, uint32_t& ties) {
+  constexpr int B1 = (32 - B0 + 1) / 2, B2 = 32 - B0 - B1;
+  const int tid = threadIdx.x;
+  uint32_t* wave_tot = xch;
+  uint32_t* found = xch + 16 + 128;
+  uint32_t prefix = 0, mask = 0, remaining = want;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int width = pass == 0 ? B0 : pass == 1 ? B1 : B2;
+    const int sh = pass == 0 ? 32 - B0 : pass == 1 ? B2 : 0;
+    const int nb = 1 << width;
+    for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < NPT; ++e)
+      if (ok[e] && (val[e] & mask) == prefix) atomicAdd(&hist[(val[e] >> sh) & (nb - 1)], 1u);
+    __syncthreads();
+    find_bin<THREADS>(hist, nb, remaining, wave_tot, found);
+    prefix |= found[0] << sh;
+    mask |= (uint32_t)(nb - 1) << sh;
+    remaining -= found[1];
+    if (pass == 2) ties = hist[found[0]];
+  }
+  __syncthreads();   // hist and found may be reused by the caller
+  r = remaining;
+  return prefix;
+}
+
+// Marks, among this thread's NPT candidates, the ones that belong to the best `keep` of the `total`
+// candidates of the workgroup (keep < total).  Returns the key threshold T.
+template <int THREADS, int B0, int NPT>
+__device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const int32_t (&tok)[NPT],
+                                              const bool (&have)[NPT], int keep, uint32_t* hist, uint32_t* xch,
+                                              bool (&sel)[NPT]) {
+  uint32_t r, ties;
+  const uint32_t T = radix_threshold<THREADS, B0, NPT>(key, have, (uint32_t)keep, hist, xch, r, ties);
+  uint32_t I = 0;   // threshold on ~token among the pairs with key == T
+  if (r < ties) {   // uniform: not every tie fits, the lowest tokens win
+    uint32_t inv[NPT];
+    bool tie[NPT];
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) {
+      inv[e] = ~(uint32_t)tok[e];
+      tie[e] = have[e] && key[e] == T;
+    }
+    uint32_t r2, t2;
+    I = radix_threshold<THREADS, B0, NPT>(inv, tie, r, hist, xch, r2, t2);
+  }
+#pragma unroll
+  for (int e = 0; e < NPT; ++e)
+    sel[e] = have[e] && (key[e] > T || (key[e] == T && ~(uint32_t)tok[e] >= I));
+  return T;
+}
+
 template <int NSET, int FS_THREADS, int PG>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const sel_tab tab, int B, int Hq, int Hkv, int G, int agg, int max_pages, int share_len, int nshares, int C,
     int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt) {
   using shape = fs_shape<FS_THREADS>;
-  constexpr int FS_WAVES = shape::WAVES, SSUB = shape::SSUB, RCAP = shape::RCAP;
-  constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS;
-  __shared__ __attribute__((aligned(16))) uint32_t keys[SSUB];
-  __shared__ __attribute__((aligned(16))) uint32_t r_key[RCAP];
-  __shared__ int32_t r_idx[RCAP];
-  __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images; selection output between sub-slices
-  __shared__ uint32_t hist[FS_BINS];
+  constexpr int FS_WAVES = shape::WAVES, CAP = shape::CAP, NPT = CAP / FS_THREADS;
+  constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS, BM_WORDS = shape::SHARE_CAP / 32;
+  static_assert(BM_WORDS <= FS_THREADS && BM_WORDS <= FS_BINS, "one bitmap word per thread; prefixes alias hist");
+  __shared__ __attribute__((aligned(16))) uint32_t c_key[CAP];   // candidate buffer: keys ...
+  __shared__ __attribute__((aligned(16))) int32_t c_tok[CAP];    // ... and their token indices
+  __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images while streaming; ordered output at the end
+  __shared__ uint32_t hist[FS_BINS];      // radix histograms; prefix counts of the bitmap words at the end
+  __shared__ uint32_t bitmap[BM_WORDS];   // one bit per token of the share: orders the selected tokens
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
+  __shared__ uint32_t c_cnt;              // candidates in the buffer
 
   // Grid = (KV head, layer * B + batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
   // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
@@ -148,8 +218,9 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   int32_t* __restrict__ sel_cnt = tab.sel_cnt[layer];
   const int32_t last_page = tab.last_page[layer];
   int b = slot;
-  if (B > 1 && B <= SSUB) {
-    int32_t* lens = reinterpret_cast<int32_t*>(keys);
+  if (tid == 0) c_cnt = 0;
+  if (B > 1 && B <= CAP) {
+    int32_t* lens = c_tok;
     for (int i = tid; i < B; i += FS_THREADS) lens[i] = ctx_lens[i];
     __syncthreads();
     for (int u = tid; u < B; u += FS_THREADS) {
@@ -160,8 +231,8 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     }
     __syncthreads();
     b = (int)xch[0];
-    __syncthreads();
   }
+  __syncthreads();
   const int64_t row = (int64_t)b * Hkv + j;                      // row of this layer's outputs
   const int64_t crow = ((int64_t)layer * B + b) * Hkv + j;        // row of the pack-wide candidate arrays
   const int N = clamp_ctx(ctx_lens[b], max_pages);
@@ -179,38 +250,37 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     return;
   }
 
-  // sub-slice schedule: full sub-slices, except a shorter pseudo-random first one in long shares
-  int cur_len = SSUB;
-  if (n_share > SSUB) {
+  // The share is streamed in sub-slices that are known to fit the free part of the candidate buffer.
+  // The first one of a long share has a pseudo-random length, so that the prune phases of different
+  // compute units do not coincide (all of them pausing their K stream at once would idle the HBM).
+  int n_sub = n_share;
+  if (n_share > CAP) {
     const uint32_t wg = (uint32_t)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
-    cur_len = SSUB / 2 + 64 * (int)((wg * 2654435761u >> 16) % (SSUB / 128));
+    n_sub = CAP / 2 + 64 * (int)((wg * 2654435761u >> 16) % (CAP / 128));
   }
+  const int share_pages = (n_share + AS_PAGE - 1) / AS_PAGE;
   const int32_t* bt_row = block_table + (int64_t)b * max_pages + tok0 / AS_PAGE;
-  // lane l keeps the page id of (iteration l / PG, page l % PG) of the current sub-slice
-  auto load_pages = [&](int pos, int len) -> int32_t {
+  // lane l keeps the page id of (iteration l / PG, page l % PG) of the sub-slice that starts at token `pos`
+  // (a sub-slice has at most CAP tokens = 64 pages per wave)
+  auto load_pages = [&](int pos) -> int32_t {
     const int lp = ((lane / PG) * FS_WAVES + wave) * PG + (lane % PG);
-    const int npg = (len + AS_PAGE - 1) / AS_PAGE;
-    const int32_t pg = lp < npg ? bt_row[pos / AS_PAGE + lp] : 0;
+    const int pi = pos / AS_PAGE + lp;
+    const int32_t pg = pi < share_pages ? bt_row[pi] : 0;
     return pg < 0 ? 0 : (pg > last_page ? last_page : pg);   // a corrupt table must not leave the pool
   };
   int pos = 0;
-  int n_sub = n_share < cur_len ? n_share : cur_len;
-  int32_t my_page = load_pages(0, n_sub);
+  int32_t my_page = load_pages(0);
 
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
 
   uint4* st = stage[wave];
-  uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);        // [SSUB] pairs fit: SSUB*8 B = stage
-  int32_t* o_idx = reinterpret_cast<int32_t*>(o_key + SSUB);
-  int rn = 0;       // entries of the running set
-  int keep = 0;
+  bool have_tau = false;   // after the first prune: only keys above tau can still make the best C
+  uint32_t tau = 0;
+  int cnt = 0;             // candidates in the buffer (uniform copy of c_cnt)
 #pragma unroll 1
   while (true) {
-    // ---- histogram of the running set, then stream the sub-slice ----
-    for (int i = tid; i < FS_BINS; i += FS_THREADS) hist[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < rn; i += FS_THREADS) atomicAdd(&hist[r_key[i] >> (32 - FS_B0)], 1u);
+    // ---- stream the sub-slice: score, filter, append ----
     const int npages_sub = (n_sub + AS_PAGE - 1) / AS_PAGE;
     const int ngroups = (npages_sub + PG - 1) / PG;   // a wave takes PG pages per iteration
 #pragma unroll 1
@@ -249,66 +319,119 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 #pragma unroll
       for (int pg = 1; pg < PG; ++pg) outv = grp == pg ? res[pg] : outv;
       const int tl = (q * PG + grp) * AS_PAGE + t;  // token within the sub-slice
-      if (grp < PG && tl < n_sub) {
-        const uint32_t key = score_key(outv + 0.0f);
-        keys[tl] = key;
-        atomicAdd(&hist[key >> (32 - FS_B0)], 1u);
+      const uint32_t key = score_key(outv + 0.0f);
+      const bool pass = grp < PG && tl < n_sub && (!have_tau || key > tau);
+      const uint64_t m = __ballot(pass);
+      if (m) {   // uniform: one LDS atomic per wave reserves the slots
+        const int leader = __ffsll((long long)m) - 1;
+        uint32_t base = 0;
+        if (lane == leader) base = atomicAdd(&c_cnt, (uint32_t)__popcll(m));
+        base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
+        if (pass) {
+          const uint32_t at = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+          c_key[at] = key;
+          c_tok[at] = tok0 + pos + tl;
+        }
       }
     }
-    // page ids of the next sub-slice travel while this one is selected
-    const int next_pos = pos + n_sub;
-    const int next_len = (n_share - next_pos) < SSUB ? (n_share - next_pos) : SSUB;
-    const bool last = next_pos >= n_share;
-    if (!last) my_page = load_pages(next_pos, next_len);
+    pos += n_sub;
+    const bool last = pos >= n_share;
+    if (!last) my_page = load_pages(pos);   // page ids of the next sub-slice travel during the barrier / prune
     __syncthreads();
-
-    // ---- select the best min(C, rn + n_sub) of (running set, new keys), ascending by token;
-    //      the page images are dead, so the result is staged there ----
-    const int rn4 = (rn + 3) & ~3;
-    const int total = rn + n_sub;
-    keep = total < C ? total : C;
-    auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
-      uint4 u = make_uint4(0, 0, 0, 0);
-      if (i4 < rn4) {
-        u = *reinterpret_cast<const uint4*>(&r_key[i4]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = i4 + e < rn;
-      } else {
-        const int jj = i4 - rn4;
-        if (jj < n_sub) u = *reinterpret_cast<const uint4*>(&keys[jj]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = jj + e < n_sub;
-      }
-      k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
-    };
-    auto emit = [&](uint32_t at, int i, uint32_t key) {
-      o_key[at] = key;
-      o_idx[at] = (i < rn4) ? r_idx[i] : tok0 + pos + (i - rn4);
-    };
-    block_select<FS_THREADS, FS_B0>(rn4 + n_sub, total, keep, true, key4_of, emit, hist, xch);
-    __syncthreads();
+    cnt = (int)c_cnt;
     if (last) break;
-    for (int i = tid; i < keep; i += FS_THREADS) {   // keep <= C <= RCAP whenever a share has several sub-slices
-      r_key[i] = o_key[i];
-      r_idx[i] = o_idx[i];
+    if (CAP - cnt < CAP / 4 && C < cnt) {
+      // ---- prune: keep the best C (C <= CAP / 2 < cnt here), unordered, and raise the filter threshold ----
+      uint32_t key[NPT];
+      int32_t tok[NPT];
+      bool have[NPT], sel[NPT];
+#pragma unroll
+      for (int e = 0; e < NPT; ++e) {
+        const int i = tid + e * FS_THREADS;
+        have[e] = i < cnt;
+        key[e] = have[e] ? c_key[i] : 0u;
+        tok[e] = have[e] ? c_tok[i] : 0;
+      }
+      tau = mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, C, hist, xch, sel);
+      have_tau = true;
+      if (tid == 0) c_cnt = 0;
+      __syncthreads();     // every thread holds its candidates in registers: the buffer can be rewritten
+#pragma unroll
+      for (int e = 0; e < NPT; ++e) {
+        const uint64_t m = __ballot(sel[e]);
+        if (m) {
+          const int leader = __ffsll((long long)m) - 1;
+          uint32_t base = 0;
+          if (lane == leader) base = atomicAdd(&c_cnt, (uint32_t)__popcll(m));
+          base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
+          if (sel[e]) {
+            const uint32_t at = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            c_key[at] = key[e];
+            c_tok[at] = tok[e];
+          }
+        }
+      }
+      __syncthreads();
+      cnt = (int)c_cnt;    // == C
     }
-    rn = keep;
-    pos = next_pos;
-    n_sub = next_len;
-    __syncthreads();
+    const int room = (CAP - cnt) & ~63;
+    if (room <= 0) break;   // unreachable while the host plan keeps C <= CAP / 2 for multi-sub-slice shares
+    n_sub = (n_share - pos) < room ? (n_share - pos) : room;
   }
 
-  // ---- write out, coalesced ----
-  if (final_out) {
-    for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? o_idx[i] : -1;
-    if (tid == 0) sel_cnt[row] = keep;
-  } else {
-    const int64_t cbase = (crow * nshares + sh) * (int64_t)ccap;
-    for (int i = tid; i < keep; i += FS_THREADS) {
-      cand_key[cbase + i] = o_key[i];
-      cand_idx[cbase + i] = o_idx[i];
+  // ---- the share's best min(C, cnt), in ascending token order ----
+  const int keep = cnt < C ? cnt : C;
+  {
+    uint32_t key[NPT];
+    int32_t tok[NPT];
+    bool have[NPT], sel[NPT];
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) {
+      const int i = tid + e * FS_THREADS;
+      have[e] = i < cnt;
+      key[e] = have[e] ? c_key[i] : 0u;
+      tok[e] = have[e] ? c_tok[i] : 0;
+      sel[e] = have[e];
     }
-    if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
+    if (keep < cnt) mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, keep, hist, xch, sel);
+    // order by token through a bitmap of the share: rank of a token = set bits below it
+    if (tid < BM_WORDS) bitmap[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < NPT; ++e)
+      if (sel[e]) atomicOr(&bitmap[(tok[e] - tok0) >> 5], 1u << ((tok[e] - tok0) & 31));
+    __syncthreads();
+    const uint32_t pc = tid < BM_WORDS ? (uint32_t)__popc(bitmap[tid]) : 0u;
+    const uint32_t inc = wave_incl_scan(pc);
+    if (lane == 63) xch[wave] = inc;
+    __syncthreads();
+    uint32_t woff[1];
+    seg_wave_offsets<FS_WAVES, 1>(xch, wave, woff);
+    if (tid < BM_WORDS) hist[tid] = woff[0] + inc - pc;   // set bits in the words below this one
+    __syncthreads();
+    uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);   // [CAP] + [CAP] words fit: the page images are dead
+    int32_t* o_tok = reinterpret_cast<int32_t*>(o_key + CAP);
+#pragma unroll
+    for (int e = 0; e < NPT; ++e)
+      if (sel[e]) {
+        const int rel = tok[e] - tok0;
+        const uint32_t at = hist[rel >> 5] + (uint32_t)__popc(bitmap[rel >> 5] & ((1u << (rel & 31)) - 1u));
+        o_key[at] = key[e];
+        o_tok[at] = tok[e];
+      }
+    __syncthreads();
+    // ---- write out, coalesced ----
+    if (final_out) {
+      for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = i < keep ? o_tok[i] : -1;
+      if (tid == 0) sel_cnt[row] = keep;
+    } else {
+      const int64_t cbase = (crow * nshares + sh) * (int64_t)ccap;
+      for (int i = tid; i < keep; i += FS_THREADS) {
+        cand_key[cbase + i] = o_key[i];
+        cand_idx[cbase + i] = o_tok[i];
+      }
+      if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
+    }
   }
 }
 

@@ -68,3 +68,46 @@ def test_exact_scores_match_oracle_bit_for_bit(pattern, shape):
         assert torch.equal(sc[b, :, : ctx[b]].cpu(), ref_s[b, :, : ctx[b]])
     idx2, cnt2 = api.as_topk_select(c, p, sc, lens.cuda())
     assert torch.equal(idx2.cpu(), ridx) and torch.equal(cnt2.cpu(), rcnt)
+
+
+@pytest.mark.parametrize("pattern", ["strict_ascending", "strict_descending", "plateaus"])
+@pytest.mark.parametrize("C", [2048, 4096])
+def test_single_share_long_rows_worst_case_orders(pattern, C):
+    """256 rows of 32768 tokens (one share per row, the launch shape of BASELINE configs[2]) with exact scores
+    256*a + b: strictly increasing scores make every token a candidate and force a prune whenever the buffer
+    fills; strictly decreasing ones stop the inflow after the first prune; plateaus of 3000 equal scores put the
+    threshold inside a tie, which only the token order can resolve."""
+    print("exact-long", pattern, C, flush=True)
+    B, Hkv, G, N = 32, 8, 2, 32768
+    max_pages = N // 16
+    g = torch.Generator().manual_seed(7)
+    k = torch.zeros((B * max_pages, Hkv, 16, 128), dtype=torch.bfloat16)
+    bt = torch.zeros((B, max_pages), dtype=torch.int32)
+    n = torch.arange(N)
+    if pattern == "strict_ascending":
+        v = n - 16384
+    elif pattern == "strict_descending":
+        v = 16383 - n
+    else:
+        v = (n // 3000) * 7 % 11 - 5
+    a = torch.div(v, 256, rounding_mode="floor")
+    bb = v - 256 * a                                          # 0..255: exact in bf16
+    for b in range(B):
+        perm = torch.randperm(max_pages, generator=g) + b * max_pages
+        bt[b] = perm.to(torch.int32)
+        shift = (b * 37) % N                                  # a different rotation of the pattern per sequence
+        k[perm, :, :, 0] = torch.roll(a, shift).to(torch.bfloat16).view(max_pages, 1, 16)
+        k[perm, :, :, 1] = torch.roll(bb, shift).to(torch.bfloat16).view(max_pages, 1, 16)
+    lens = torch.full((B,), N, dtype=torch.int32)
+    lens[1] = N - 5
+    q_hat = torch.zeros((B, Hkv * G, 128), dtype=torch.float32)
+    q_hat[:, :, 0] = 256.0
+    q_hat[:, :, 1] = 1.0
+    ref_s = oracle.score_keys(k, bt, lens, q_hat, Hkv)
+    ridx, rcnt = oracle.topk_select(ref_s, lens, C)
+    p = api.make_params(B, Hkv * G, Hkv, 4, C, max_pages)
+    assert api.select_plan(p)[1] == 1                         # one share per row
+    c = api.Context(p)
+    idx, cnt = api.as_score_topk(c, p, api.kv_view(k.cuda(), None, bt.cuda(), lens.cuda()), q_hat.cuda())
+    assert torch.equal(cnt.cpu(), rcnt)
+    assert torch.equal(idx.cpu(), ridx)
