@@ -2,7 +2,8 @@
 
 Launches, on one layer of a workload, (1) the calibration kernel - the paged walk over K with
 coalesced loads and one word written per token, whose bytes are known exactly - and (2) the
-fused scoring + top-k (as_score_topk) and (3) sparse decode attention, a few times each, so
+fused scoring + top-k (as_score_topk), (3) sparse decode attention and (4) the KV re-organisation
+(as_gather_kv) followed by dense attention over the compact pool, a few times each, so
 that per-dispatch counter values can be scaled by what the same counter reads for the
 calibration kernel.
 
@@ -35,6 +36,16 @@ def main():
     torch.cuda.synchronize()
     for _ in range(reps):
         api.as_sparse_decode_attn(ctx, p, kv, inp.q_real, idx, cnt, want_lse=False)
+    torch.cuda.synchronize()
+    comp = None
+    for _ in range(reps):
+        comp = api.as_gather_kv(ctx, p, kv, idx, cnt, *(comp or ()))
+    torch.cuda.synchronize()
+    pc = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, 16, api.compact_pages(p))
+    ctx_c = api.Context(pc)
+    kvc = api.kv_view(*comp)
+    for _ in range(reps):
+        api.as_dense_decode_attn(ctx_c, pc, kvc, inp.q_real, want_lse=False)
     torch.cuda.synchronize()
     tokens = int(inp.ctx_lens.sum())
     print(f"calibration kernel per launch: reads {tokens * w.n_kv_heads * 256} B of K, writes "
