@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--budget", type=int, default=0)
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
     ap.add_argument("--ctx", type=int, default=0, help="override the workload's context length (sweeps)")
+    ap.add_argument("--q-heads", type=int, default=0, help="override the query head count (head-layout comparison)")
+    ap.add_argument("--kv-heads", type=int, default=0, help="override the KV head count")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time to spend on the oracle baseline")
     ap.add_argument("--score-variant", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -72,6 +74,10 @@ def main():
         w = wl.scaled(w, budget=a.budget)
     if a.batch:
         w = wl.scaled(w, batch=a.batch)
+    if a.q_heads:
+        w = wl.scaled(w, n_q_heads=a.q_heads)
+    if a.kv_heads:
+        w = wl.scaled(w, n_kv_heads=a.kv_heads)
     if a.ctx:
         w = wl.scaled(w, ctx=a.ctx, ctx_min=None if w.ctx_min is None else min(w.ctx_min, a.ctx))
     n_layers = a.layers or w.layers
