@@ -59,3 +59,31 @@ def test_full_size_sampled_sequences(name, budget, samples):
         assert err <= 2e-2, (b, err)
         assert (lse[b].cpu() - ref_lse[0]).abs().max().item() <= 1e-3
     print(f"  {name}: tie swaps {swaps_total} over {len(samples)} sampled sequences", flush=True)
+
+
+def test_million_token_context_and_largest_budget():
+    """One sequence of 1,000,003 tokens (ragged last page; rows cut into dozens of shares, candidates merged from
+    global memory) with budget 4096, then the largest supported budget (65536) on 70,001 tokens; the whole row is
+    checked against the oracle."""
+    for n_tok, budget, seed in ((1_000_003, 4096, 41), (70_001, 65536, 42)):
+        print("long-context", n_tok, budget, flush=True)
+        w = wl.Workload("long", 1, 8, 2, 16, budget, n_tok, page_table="permute", n_outlier=4, seed=seed)
+        cpu = wl.make_inputs(w)
+        dev = wl.Inputs(w, cpu.k_pool.cuda(), cpu.v_pool.cuda(), cpu.block_table.cuda(), cpu.ctx_lens.cuda(),
+                        cpu.q_win.cuda(), cpu.q_cur.cuda(), cpu.q_real.cuda())
+        eps = f32(1e-2)
+        p = api.make_params(1, 8, 2, 16, budget, cpu.max_pages, ridge_eps=eps, sm_scale=f32(SCALE))
+        ctx = api.Context(p)
+        kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+        gidx, gcnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+        out, lse = api.as_sparse_decode_attn(ctx, p, kv, dev.q_real, gidx, gcnt)
+        torch.cuda.synchronize()
+        rq, rs, ridx, rcnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur, budget,
+                                                eps)
+        swaps = compare_selection(gidx, gcnt, ridx, rcnt, rs, cpu.ctx_lens, budget)
+        ref, ref_lse = oracle.sparse_decode_attn(cpu.k_pool, cpu.v_pool, cpu.block_table, cpu.ctx_lens, cpu.q_real,
+                                                 gidx.cpu(), gcnt.cpu(), f32(SCALE))
+        err = (out.cpu().float() - ref.float()).abs().max().item()
+        print(f"  plan {api.select_plan(p)}, tie swaps {swaps}, attention max abs err {err:.3e}", flush=True)
+        assert err <= 2e-2
+        assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
