@@ -48,6 +48,7 @@ as_status check_kv(const as_kv_view* kv, bool need_v) {
   if (!kv || !kv->k_pool || !kv->block_table || !kv->ctx_lens) return AS_ERR_INVALID_ARG;
   if (need_v && !kv->v_pool) return AS_ERR_INVALID_ARG;
   if (kv->num_pages < 1) return AS_ERR_INVALID_ARG;
+  if (kv->num_pages > 0x7fffffffLL) return AS_ERR_UNSUPPORTED;   // page ids are int32
   return AS_OK;
 }
 
@@ -241,6 +242,7 @@ as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_po
   if (st != AS_OK) return st;
   if (!ctx || !k_pool || !v_pool || !block_table || !ctx_lens || !k_new || !v_new || num_pages < 1)
     return AS_ERR_INVALID_ARG;
+  if (num_pages > 0x7fffffffLL) return AS_ERR_UNSUPPORTED;
   return hip_status(asx::launch_kv_append(p, static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool),
                                           block_table, ctx_lens, num_pages, static_cast<const uint16_t*>(k_new),
                                           static_cast<const uint16_t*>(v_new), static_cast<hipStream_t>(stream)));
