@@ -35,7 +35,7 @@ static int g_attn_impl = 0;  // 0: matrix-core kernel (attn_mfma.hip), 1: vector
 // about six workgroups per compute unit, so that per-split costs (partials through HBM, query
 // fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens.  One
 // extra split at the end takes whatever lies beyond list_len (the dense tail of a sparse call).
-struct attn_geom { int nsplit, split_tokens; };
+struct attn_geom { int nsplit, split_tokens, nsel; };
 static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (list_len < 1) list_len = 1;
@@ -51,6 +51,7 @@ static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
   attn_geom g;
   g.split_tokens = (int)split_tokens;
   g.nsplit = (int)((list_len + split_tokens - 1) / split_tokens) + 1;
+  g.nsel = (int)nsel;   // <= nsplit - 1
   return g;
 }
 
@@ -321,7 +322,7 @@ static hipError_t launch_attn_gh(const as_params* p, const as_kv_view* kv, const
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            int nsplit, int split_tokens, hipStream_t s);
+                            int nsplit, int list_len, hipStream_t s);
 
 extern "C" void as_debug_set_attn_impl(int v) { g_attn_impl = v; }   // development knob
 
@@ -333,14 +334,18 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   if (heads == 0) return hipSuccess;
   const int G = p->n_q_heads / p->n_kv_heads;
   const bool dense = sel_idx == nullptr;
-  const attn_geom gm = attn_geometry(p, dense ? (int64_t)p->max_pages_per_seq * AS_PAGE : (int64_t)p->budget);
-  const int nsplit = gm.nsplit, split_tokens = gm.split_tokens;
+  const int64_t list_len = dense ? (int64_t)p->max_pages_per_seq * AS_PAGE : (int64_t)p->budget;
+  const attn_geom gm = attn_geometry(p, list_len);
+  // The matrix-core kernel cuts the list into equal splits (no separate tail split); the vector-ALU
+  // kernel walks whole 64-token chunks and keeps one extra split for the tail.
+  const int nsplit = g_attn_impl == 0 ? gm.nsel : gm.nsplit;
+  const int split_tokens = gm.split_tokens;
   const int cps = split_tokens / AT_CHUNK;
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
   hipError_t e;
   if (g_attn_impl == 0)
-    e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, split_tokens, s);
+    e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, (int)list_len, s);
   else
   switch (attn_gh(G)) {
     case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;

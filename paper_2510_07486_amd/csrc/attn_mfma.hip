@@ -26,19 +26,20 @@ typedef uint32_t u32x4_m __attribute__((ext_vector_type(4)));
 static constexpr int AM_STEP = 32;          // tokens per wave step
 static constexpr int AM_VROW = 288;         // bytes per V row in LDS (256 + 32: spreads the tr reads over banks)
 static constexpr int AM_KIMG = 256;         // uint4 per 16-token K image
-static constexpr int AM_WAVE_LDS = AM_KIMG * 16 + AM_STEP * AM_VROW;      // 4 KB K tile + 9 KB V per wave
+static constexpr int AM_WAVE_LDS = AM_STEP * AM_VROW;   // 9 KB per wave: the V rows of a step; the 4 KB K tile image
+                                                        // of the S phase lives in the same bytes (three workgroups per CU)
 
 __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
   const u32x4_m r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_m*>(p));
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
-__global__ __launch_bounds__(256) void attn_mfma_kernel(
+__global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
     const uint16_t* __restrict__ k_pool, const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
     float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit,
-    int split_tokens, int32_t last_page) {
+    int list_len, int32_t last_page) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * AM_WAVE_LDS];
   __shared__ float m_sh[4][16], l_sh[4][16];
 
@@ -49,7 +50,11 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
   const int32_t* idx_row = sel_idx + ((int64_t)b * Hkv + j) * C;
   // lane l (< 32, upper half mirrors) resolves token l of a 32-token step of this wave
-  auto step_token = [&](int step) -> int { return split * split_tokens + step * AM_STEP + (lane & 31); };
+  // Balanced partition of the logical token list: split s starts at s * list_len / nsplit rounded down to a
+  // whole 32-token step, the last split also takes whatever lies beyond list_len (the dense tail).
+  const int t_begin = (int)((int64_t)split * list_len / nsplit) & ~(AM_STEP - 1);
+  const int t_next = (int)((int64_t)(split + 1) * list_len / nsplit) & ~(AM_STEP - 1);
+  auto step_token = [&](int step) -> int { return t_begin + step * AM_STEP + (lane & 31); };
   auto fetch_index = [&](int step) -> int {
     const int ti = step_token(step);
     return (ti < C) ? idx_row[ti] : 0;
@@ -62,8 +67,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
   int tail0 = sel_idx ? (sel_ctx_lens ? sel_ctx_lens[b] : N) : 0;
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);
-  const int t_begin = split * split_tokens;
-  const int t_end = (split == nsplit - 1) ? L : (t_begin + split_tokens < L ? t_begin + split_tokens : L);
+  const int t_end = (split == nsplit - 1) ? L : (t_next < L ? t_next : L);
   const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G) * nsplit + split;  // + g * nsplit per head
   if (t_begin >= t_end) {                                                     // nothing here: mark empty
     if (tid < G) {
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
   unsigned char* my_lds = lds_raw + w * AM_WAVE_LDS;
   uint4* kimg = reinterpret_cast<uint4*>(my_lds);                       // [256] swizzled 16-byte slots, one 16-token tile
-  unsigned char* vimg = my_lds + AM_KIMG * 16;                          // [32][AM_VROW]
+  unsigned char* vimg = my_lds;                                         // [32][AM_VROW], written once S is done
   const int32_t* bt_row = block_table + (int64_t)b * max_pages;
 
   auto page_of = [&](int step, int raw) -> uint32_t {
@@ -122,10 +126,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     }
     uint32_t pk_next = 0;
     if (more) pk_next = page_of(step + 4, raw_next);
-    // ---- stage V (padded rows); K goes through one 16-token image, tile after tile ----
-#pragma unroll
-    for (int it = 0; it < 8; ++it) *reinterpret_cast<uint4*>(vimg + (it * 4 + slot) * AM_VROW + c * 16) = vr[it];
-    // ---- S^T = K Q^T for the two tiles: lane (head t, grp) gets tokens tile*16 + 4*grp + i ----
+    // ---- S^T = K Q^T for the two tiles (K goes through one 16-token image, tile after tile): lane (head t, grp) gets tokens tile*16 + 4*grp + i ----
     float s[8];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
@@ -145,6 +146,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
         s[tile * 4 + i] = (tok < t_end) ? acc[i] * sm_scale : -INFINITY;
       }
     }
+    // ---- the K image is dead: stage V (padded rows) over it ----
+#pragma unroll
+    for (int it = 0; it < 8; ++it) *reinterpret_cast<uint4*>(vimg + (it * 4 + slot) * AM_VROW + c * 16) = vr[it];
+    __builtin_amdgcn_wave_barrier();
     // ---- online softmax of head t over the step's 32 tokens ----
     float mx = s[0];
 #pragma unroll
@@ -237,14 +242,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            int nsplit, int split_tokens, hipStream_t s) {
+                            int nsplit, int list_len, hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
   dim3 grid(nsplit, p->n_kv_heads, p->batch);
   hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
                      sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0,
                      p->max_pages_per_seq,
-                     p->sm_scale, nsplit, split_tokens, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
+                     p->sm_scale, nsplit, list_len, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
   return hipGetLastError();
 }
 

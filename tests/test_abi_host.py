@@ -70,3 +70,15 @@ def test_pack_workspace_and_share_plan():
         assert share * shares >= 4096 and share % 64 == 0 and cand == min(256, share)
     # null layer array / bad pack sizes are rejected before anything touches the device
     assert L.as_select_step_pack(None, C.byref(small), None, 1, None) == 1
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, with no HIP or C++ in sight."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "asyncspade.h"\n'
+                   "int main(void) { as_params p; as_kv_view kv; as_layer_io io; (void)p; (void)kv; (void)io;\n"
+                   "  return (int)sizeof(as_status) > 0 && AS_MAX_PACK == 16 ? 0 : 1; }\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
