@@ -87,3 +87,28 @@ def test_million_token_context_and_largest_budget():
         print(f"  plan {api.select_plan(p)}, tie swaps {swaps}, attention max abs err {err:.3e}", flush=True)
         assert err <= 2e-2
         assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
+
+
+def test_full_size_packed_selection_two_layers():
+    """BASELINE configs[2] at full size, two layers in one as_select_step_pack call (512 rows of 32768 tokens in one
+    grid): every row equals the single-layer call bit for bit, and one sampled sequence per layer equals the oracle."""
+    w = wl.scaled(wl.CONFIGS["c3"], layers=1)
+    eps = f32(1e-2)
+    layers = [wl.make_inputs(w, "cuda", layer=l) for l in range(2)]
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, layers[0].max_pages, ridge_eps=eps,
+                        sm_scale=f32(SCALE))
+    ctx = api.Context(p, pack=2)
+    kvs = [api.kv_view(x.k_pool, x.v_pool, x.block_table, x.ctx_lens) for x in layers]
+    sel = [(torch.empty((w.batch, w.n_kv_heads, w.budget), dtype=torch.int32, device="cuda"),
+            torch.empty((w.batch, w.n_kv_heads), dtype=torch.int32, device="cuda")) for _ in layers]
+    api.as_select_step_pack(ctx, p, [api.layer_io(kvs[l], layers[l].q_win, layers[l].q_cur, sel[l][0], sel[l][1])
+                                     for l in range(2)])
+    torch.cuda.synchronize()
+    for l, b in ((0, 9), (1, 26)):
+        one_idx, one_cnt = api.as_select_step(ctx, p, kvs[l], layers[l].q_win, layers[l].q_cur)
+        assert torch.equal(one_idx, sel[l][0]) and torch.equal(one_cnt, sel[l][1])
+        one = wl.extract_sequence(layers[l], b)
+        rq, rs, ridx, rcnt = oracle.select_step(one.k_pool, one.block_table, one.ctx_lens, one.q_win, one.q_cur,
+                                                w.budget, eps)
+        swaps = compare_selection(sel[l][0][b:b + 1], sel[l][1][b:b + 1], ridx, rcnt, rs, one.ctx_lens, w.budget)
+        print(f"  layer {l} sequence {b}: tie swaps {swaps}", flush=True)
