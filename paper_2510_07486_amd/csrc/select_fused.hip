@@ -437,9 +437,11 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 
 // Reduces a row's per-slice candidates (ascending token order within and across slices) to
 // its top-C, again ascending and with ties to the lowest index.  Rows with at most
-// MG_LDS candidates are first compacted into LDS (one read of the candidates); larger rows
-// run the same selection over the global arrays.
+// MG_LDS candidates are first compacted into LDS (one read of the candidates), marked in
+// registers (mark_best) and compacted in order; larger rows run the positional radix select
+// of the stand-alone top-k over the global arrays.
 static constexpr int MG_LDS = 12288;  // (key, index) pairs: 96 KB
+static constexpr int MG_NPT = MG_LDS / TK_THREADS;
 
 __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab tab, int rows_per_layer,
                                                                   const uint32_t* __restrict__ cand_key,
@@ -496,14 +498,35 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
         }
       }
       __syncthreads();
-      auto key4_of = [&](int i4, uint32_t (&k)[4], bool (&v)[4]) {
-        const uint4 u = (i4 < total) ? *reinterpret_cast<const uint4*>(&lkey[i4]) : make_uint4(0, 0, 0, 0);
-        k[0] = u.x; k[1] = u.y; k[2] = u.z; k[3] = u.w;
+      // a thread owns MG_NPT consecutive candidates (token order): exact marking of the best `keep` in registers,
+      // then an ordered compaction of the marked ones
+      uint32_t key[MG_NPT];
+      int32_t tok[MG_NPT];
+      bool have[MG_NPT], sel[MG_NPT];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = i4 + e < total;
-      };
-      auto emit = [&](uint32_t pos, int i, uint32_t) { sel_idx[row * C + pos] = lidx[i]; };
-      block_select<TK_THREADS, 12>(total, total, keep, false, key4_of, emit, hist, xch);
+      for (int e = 0; e < MG_NPT; ++e) {
+        const int i = tid * MG_NPT + e;
+        have[e] = i < total;
+        key[e] = have[e] ? lkey[i] : 0u;
+        tok[e] = have[e] ? lidx[i] : 0;
+        sel[e] = have[e];
+      }
+      if (keep < total) mark_best<TK_THREADS, 12, MG_NPT>(key, tok, have, keep, hist, xch, sel);
+      uint32_t c = 0;
+#pragma unroll
+      for (int e = 0; e < MG_NPT; ++e) c += sel[e] ? 1u : 0u;
+      const uint32_t sinc = wave_incl_scan(c);
+      __syncthreads();                 // every thread has its candidates in registers: lidx becomes the output stage
+      if (lane == 63) xch[wave] = sinc;
+      __syncthreads();
+      uint32_t soff[1];
+      seg_wave_offsets<TK_THREADS / 64, 1>(xch, wave, soff);
+      uint32_t at = soff[0] + sinc - c;
+#pragma unroll
+      for (int e = 0; e < MG_NPT; ++e)
+        if (sel[e]) lidx[at++] = tok[e];
+      __syncthreads();
+      for (int i = tid; i < keep; i += TK_THREADS) sel_idx[row * C + i] = lidx[i];
     } else {
       auto key_of = [&](int v, bool& valid) -> uint32_t {
         valid = (v % ccap) < cnt_sh[v / ccap];
