@@ -374,6 +374,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       __syncthreads();
       cnt = (int)c_cnt;    // == C
     }
+    __syncthreads();   // every wave holds the same count before the next sub-slice starts to append
     const int room = (CAP - cnt) & ~63;
     if (room <= 0) break;   // unreachable while the host plan keeps C <= CAP / 2 for multi-sub-slice shares
     n_sub = (n_share - pos) < room ? (n_share - pos) : room;
