@@ -288,18 +288,35 @@ __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* 
                                                                    float* __restrict__ lse, int nsplit) {
   const int64_t bh = blockIdx.x;
   const int d = threadIdx.x;
-  const float* ml = part_ml + bh * nsplit * 2;
+  const float2* ml = reinterpret_cast<const float2*>(part_ml) + bh * nsplit;
+  const float* po = part_o + bh * nsplit * AS_HEAD_DIM + d;
+  // eight partials per round: their loads are independent of each other and issued together
   float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s)
-    if (ml[2 * s + 1] > 0.f) M = fmaxf(M, ml[2 * s]);
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+    float2 v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = s0 + e < nsplit ? ml[s0 + e] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (v[e].y > 0.f) M = fmaxf(M, v[e].x);
+  }
   float Lsum = 0.f, o = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float l = ml[2 * s + 1];
-    if (l > 0.f) {
-      const float wgt = expf(ml[2 * s] - M);
-      Lsum += l * wgt;
-      o += wgt * part_o[(bh * nsplit + s) * AS_HEAD_DIM + d];
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+    float2 v[8];
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool in = s0 + e < nsplit;
+      v[e] = in ? ml[s0 + e] : make_float2(-INFINITY, 0.f);
+      x[e] = in ? po[(int64_t)(s0 + e) * AS_HEAD_DIM] : 0.f;
     }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (v[e].y > 0.f) {
+        const float wgt = expf(v[e].x - M);
+        Lsum += v[e].y * wgt;
+        o += wgt * x[e];
+      }
   }
   const float r = (Lsum > 0.f) ? o / Lsum : 0.f;
   out[bh * AS_HEAD_DIM + d] = (uint16_t)f32_to_bf16_rne(r);

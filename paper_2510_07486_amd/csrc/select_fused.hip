@@ -37,7 +37,7 @@ template <int THREADS> struct fs_shape {
   static constexpr int SHARE_CAP = THREADS * 32;          // tokens per share (balance of ragged batches)
 };
 static constexpr int FS_PG = 2;             // pages a wave loads per iteration (8 KB in flight per wave)
-static constexpr int FS_MAX_SLICES = 4096;  // shares per row the merge kernel can index (4 per thread)
+static constexpr int FS_MAX_SLICES = 1024;  // shares per row the merge kernel can index (one per thread)
 static int g_fs_threads = 1024;             // development knob: workgroup shape of the slice kernel
 extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 512) ? 512 : 1024; }
 
@@ -441,14 +441,15 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 // MG_LDS candidates are first compacted into LDS (one read of the candidates), marked in
 // registers (mark_best) and compacted in order; larger rows run the positional radix select
 // of the stand-alone top-k over the global arrays.
-static constexpr int MG_LDS = 12288;  // (key, index) pairs: 96 KB
-static constexpr int MG_NPT = MG_LDS / TK_THREADS;
-
+// MG_NPT = candidates per thread the LDS path can hold (4, 8 or 16: 32 / 64 / 128 KB of pairs), chosen by the
+// host from the most candidates a row can have, so that short rows do not pay for slots they never fill.
+template <int MG_NPT>
 __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab tab, int rows_per_layer,
                                                                   const uint32_t* __restrict__ cand_key,
                                                                   const int32_t* __restrict__ cand_idx,
                                                                   const int32_t* __restrict__ cand_cnt, int nslices,
                                                                   int ccap, int C) {
+  constexpr int MG_LDS = MG_NPT * TK_THREADS;
   __shared__ int32_t cnt_sh[FS_MAX_SLICES];
   __shared__ int32_t pre_sh[FS_MAX_SLICES];
   __shared__ __attribute__((aligned(16))) uint32_t lkey[MG_LDS];
@@ -461,28 +462,17 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
   int32_t* __restrict__ sel_idx = tab.sel_idx[layer];
   int32_t* __restrict__ sel_cnt = tab.sel_cnt[layer];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // counts and their exclusive prefix over slices: a thread owns 4 consecutive slices
-  uint32_t c4[4], mine = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int sl = 4 * tid + e;
-    c4[e] = sl < nslices ? (uint32_t)cand_cnt[crow * nslices + sl] : 0u;
-    mine += c4[e];
-  }
+  // counts and their exclusive prefix over slices: thread s owns slice s
+  static_assert(FS_MAX_SLICES <= TK_THREADS, "one slice per thread");
+  const uint32_t mine = tid < nslices ? (uint32_t)cand_cnt[crow * nslices + tid] : 0u;
   const uint32_t inc = wave_incl_scan(mine);
   if (lane == 63) xch[wave] = inc;
   __syncthreads();
   uint32_t woff[1];
   const int total = (int)seg_wave_offsets<TK_THREADS / 64, 1>(xch, wave, woff);
-  uint32_t run = woff[0] + inc - mine;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int sl = 4 * tid + e;
-    if (sl < nslices) {
-      cnt_sh[sl] = (int32_t)c4[e];
-      pre_sh[sl] = (int32_t)run;
-    }
-    run += c4[e];
+  if (tid < nslices) {
+    cnt_sh[tid] = (int32_t)mine;
+    pre_sh[tid] = (int32_t)(woff[0] + inc - mine);
   }
   __syncthreads();
   const int keep = total < C ? total : C;
@@ -569,8 +559,14 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || pl.nslices == 1) return e;
-  hipLaunchKernelGGL(select_merge_kernel, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, tab,
-                     p->batch * p->n_kv_heads, cand_key, cand_idx, cand_cnt, pl.nslices, pl.ccap, p->budget);
+  const int64_t most = (int64_t)pl.nslices * pl.ccap;   // candidates a row can have
+#define AS_MERGE_LAUNCH(NPT_)                                                                                   \
+  hipLaunchKernelGGL(select_merge_kernel<NPT_>, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, tab,              \
+                     p->batch * p->n_kv_heads, cand_key, cand_idx, cand_cnt, pl.nslices, pl.ccap, p->budget)
+  if (most <= 4 * TK_THREADS) AS_MERGE_LAUNCH(4);
+  else if (most <= 8 * TK_THREADS) AS_MERGE_LAUNCH(8);
+  else AS_MERGE_LAUNCH(16);
+#undef AS_MERGE_LAUNCH
   return hipGetLastError();
 }
 
