@@ -190,6 +190,60 @@ int aso_predict_query(int B, int Hq, int W, int D, const uint16_t* q_win, const 
   return fail ? -1 : 0;
 }
 
+/*
+ * Predictor with a single ridge solve (Appendix C, Alg. 1 steps 3-5, on the window bookkeeping of
+ * Sec. 4.2): omega = (R R^T + eps I)^-1 R Q_t is solved once over all W predecessors; the weights
+ * of window size k are the softmax of beta * omega truncated to its k newest entries
+ * (truncate and renormalise), applied to the shifted window as in Eq. 4; mean over k (Eq. 5).
+ * Same arguments as aso_predict_query.
+ */
+int aso_predict_query_single_solve(int B, int Hq, int W, int D, const uint16_t* q_win, const uint16_t* q_cur,
+                                   double eps, double beta, float* q_hat, double* weights_out) {
+  if (B < 0 || Hq <= 0 || W < 1 || D <= 0 || !(eps > 0.0)) return -1;
+  int fail = 0;
+#pragma omp parallel for schedule(static)
+  for (int bh = 0; bh < B * Hq; ++bh) {
+    double* R = (double*)malloc(sizeof(double) * W * D);   /* R[i-1] = Q_{t-i}   */
+    double* S = (double*)malloc(sizeof(double) * W * D);   /* S[i-1] = Q_{t+1-i} */
+    double* T = (double*)malloc(sizeof(double) * D);
+    double* om = (double*)malloc(sizeof(double) * W);
+    double* w = (double*)malloc(sizeof(double) * W);
+    double* acc = (double*)calloc(D, sizeof(double));
+    const uint16_t* win = q_win + (size_t)bh * W * D;
+    const uint16_t* cur = q_cur + (size_t)bh * D;
+    for (int d = 0; d < D; ++d) T[d] = bf16_to_f64(cur[d]);
+    for (int i = 1; i <= W; ++i)
+      for (int d = 0; d < D; ++d) R[(i - 1) * D + d] = bf16_to_f64(win[(size_t)(W - i) * D + d]);
+    for (int d = 0; d < D; ++d) S[d] = T[d];
+    for (int i = 2; i <= W; ++i)
+      for (int d = 0; d < D; ++d) S[(i - 1) * D + d] = R[(i - 2) * D + d];
+    if (aso_ridge_weights(W, D, R, T, eps, om) != 0) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+      for (int k = 1; k <= W; ++k) {
+        double mx = beta * om[0];
+        for (int i = 1; i < k; ++i) if (beta * om[i] > mx) mx = beta * om[i];
+        double z = 0.0;
+        for (int i = 0; i < k; ++i) { w[i] = exp(beta * om[i] - mx); z += w[i]; }
+        for (int i = 0; i < k; ++i) w[i] /= z;
+        if (weights_out) {
+          double* wo = weights_out + ((size_t)bh * W + (k - 1)) * W;
+          for (int i = 0; i < W; ++i) wo[i] = i < k ? w[i] : 0.0;
+        }
+        for (int d = 0; d < D; ++d) {
+          double c = 0.0;
+          for (int i = 0; i < k; ++i) c += w[i] * S[i * D + d];
+          acc[d] += c;
+        }
+      }
+      for (int d = 0; d < D; ++d) q_hat[(size_t)bh * D + d] = (float)(acc[d] / (double)W);
+    }
+    free(R); free(S); free(T); free(om); free(w); free(acc);
+  }
+  return fail ? -1 : 0;
+}
+
 static const uint16_t* token_ptr(const uint16_t* pool, const int32_t* block_table, int max_pages,
                                  int Hkv, int P, int D, int b, int j, int n) {
   int64_t page = block_table[(int64_t)b * max_pages + n / P];

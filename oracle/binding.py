@@ -29,6 +29,7 @@ def _load():
         build()
         _lib = C.CDLL(_LIB)
         _lib.aso_predict_query.restype = C.c_int
+        _lib.aso_predict_query_single_solve.restype = C.c_int
         _lib.aso_score_keys.restype = C.c_int
         _lib.aso_topk_select.restype = C.c_int
         _lib.aso_sparse_decode_attn.restype = C.c_int
@@ -69,13 +70,14 @@ def ridge_weights(R: np.ndarray, T: np.ndarray, eps: float) -> np.ndarray:
 
 
 def predict_query(q_win: torch.Tensor, q_cur: torch.Tensor, eps: float, beta: float = 1.0,
-                  return_weights: bool = False):
+                  return_weights: bool = False, single_solve: bool = False):
     B, Hq, W, D = q_win.shape
     q_win = q_win.contiguous(); q_cur = q_cur.contiguous()
     assert q_win.dtype == torch.bfloat16 and q_cur.dtype == torch.bfloat16
     q_hat = torch.empty((B, Hq, D), dtype=torch.float32)
     wts = torch.zeros((B, Hq, W, W), dtype=torch.float64) if return_weights else None
-    rc = _load().aso_predict_query(C.c_int(B), C.c_int(Hq), C.c_int(W), C.c_int(D), _p(q_win), _p(q_cur),
+    fn = _load().aso_predict_query_single_solve if single_solve else _load().aso_predict_query
+    rc = fn(C.c_int(B), C.c_int(Hq), C.c_int(W), C.c_int(D), _p(q_win), _p(q_cur),
                                    C.c_double(eps), C.c_double(beta), _p(q_hat),
                                    _p(wts) if wts is not None else None)
     if rc != 0:
@@ -129,9 +131,9 @@ def sparse_decode_attn(k_pool, v_pool, block_table, ctx_lens, q, sel_idx, sel_cn
 
 
 def select_step(k_pool, block_table, ctx_lens, q_win, q_cur, budget: int, eps: float, beta: float = 1.0,
-                agg: int = 0):
+                agg: int = 0, single_solve: bool = False):
     """predict -> score -> top-k, the three oracle stages chained."""
-    q_hat = predict_query(q_win, q_cur, eps, beta)
+    q_hat = predict_query(q_win, q_cur, eps, beta, single_solve=single_solve)
     scores = score_keys(k_pool, block_table, ctx_lens, q_hat, k_pool.shape[1], agg)
     sel_idx, sel_cnt = topk_select(scores, ctx_lens, budget)
     return q_hat, scores, sel_idx, sel_cnt

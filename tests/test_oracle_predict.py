@@ -174,3 +174,59 @@ def test_rejects_bad_arguments():
     qc = bf(np.zeros((1, 1, 4)))
     with pytest.raises(RuntimeError):
         oracle.predict_query(qw, qc, 0.0)
+
+
+# ---- single-solve variant (Alg. 1 steps 3-5: one ridge solve, truncate and renormalise per window size) ----
+def run_single(q_win, q_cur, eps, beta=1.0):
+    qh, w = oracle.predict_query(bf(q_win)[None, None], bf(q_cur)[None, None], eps, beta, return_weights=True,
+                                 single_solve=True)
+    return qh[0, 0].numpy(), w[0, 0].numpy()
+
+
+@pytest.mark.parametrize("beta", [1.0, -1.0])
+def test_single_solve_weights_are_truncated_softmax_of_one_numpy_solve(beta):
+    rng = np.random.default_rng(11)
+    W, D, eps = 7, 32, 0.05
+    q_win = f64(bf(rng.standard_normal((W, D))))
+    cur = f64(bf(rng.standard_normal(D)))
+    got, wts = run_single(q_win, cur, eps, beta)
+    R = np.stack([q_win[W - i] for i in range(1, W + 1)])                 # newest predecessor first
+    om = np.linalg.solve(R @ R.T + eps * np.eye(W), R @ cur)              # ONE solve, all W predecessors
+    shifted = np.vstack([cur[None], R[: W - 1]])                          # Q_t, Q_{t-1}, ..., Q_{t-W+1}
+    exp = np.zeros(D)
+    for k in range(1, W + 1):
+        w = softmax(beta * om[:k])                                        # truncate to the k newest, renormalise
+        np.testing.assert_allclose(wts[k - 1, :k], w, rtol=1e-9, atol=1e-13)
+        assert np.all(wts[k - 1, k:] == 0)
+        exp += w @ shifted[:k]
+    np.testing.assert_allclose(got, (exp / W).astype(np.float32), rtol=1e-6, atol=1e-7)
+    # the last row (k = W) is what the per-window-size procedure also gets; shorter windows differ in general
+    _, wts_sub = run(q_win, cur, eps, beta, weights=True)
+    np.testing.assert_allclose(wts[W - 1], wts_sub[W - 1], rtol=1e-9, atol=1e-13)
+    assert np.max(np.abs(wts[2] - wts_sub[2])) > 1e-6
+
+
+def test_single_solve_special_cases():
+    rng = np.random.default_rng(12)
+    # W = 1: the only weight is 1 and sits on Q_t
+    cur = rng.standard_normal(128)
+    got, _ = run_single(rng.standard_normal((1, 128)), cur, 0.1)
+    assert np.array_equal(got, bf(cur).float().numpy())
+    # constant sequence: fixed point
+    v = bf(rng.standard_normal(128)).float().numpy()
+    got, _ = run_single(np.tile(v, (9, 1)), v, 0.01)
+    np.testing.assert_allclose(got, v, rtol=3e-7, atol=0)
+    # orthogonal window: the Gram matrix is diagonal, so sub-problems and truncation coincide and the
+    # single solve reproduces the per-window-size prediction exactly
+    W, D, eps = 4, 8, 0.5
+    alpha = np.array([2.0, 1.0, -1.5, 0.5])
+    q_win = np.zeros((W, D))
+    for i in range(1, W + 1):
+        q_win[W - i, i - 1] = alpha[i - 1]
+    T = np.zeros(D)
+    T[:W] = [1.0, -0.5, 2.0, 0.25]
+    T[W] = 3.0
+    a, wa = run_single(q_win, T, eps)
+    b, wb = run(q_win, T, eps, weights=True)
+    np.testing.assert_allclose(wa, wb, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(a, b, rtol=1e-7, atol=0)
