@@ -55,6 +55,13 @@ typedef enum {
 
 typedef enum { AS_AGG_MAX = 0, AS_AGG_SUM = 1 } as_agg;
 
+/* How the weights of window size k are obtained (Sec. 4.2 vs Appendix C):
+ *   AS_PRED_PER_WINDOW    one ridge problem per window size, over its k newest predecessors (Sec. 4.2,
+ *                         "Assembled Regression": the default and the reading the parity tests pin);
+ *   AS_PRED_SINGLE_SOLVE  one ridge solve over all W predecessors, the weights of window size k are the
+ *                         softmax of the solution truncated to its k newest entries (Alg. 1 steps 3-5). */
+typedef enum { AS_PRED_PER_WINDOW = 0, AS_PRED_SINGLE_SOLVE = 1 } as_predictor;
+
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128                          */
   int32_t page_size;                              /* must be 16                                    */
@@ -66,6 +73,7 @@ typedef struct {
                                                   /* -1 is the sign printed in Alg. 1 step 3       */
   float sm_scale;                                 /* attention logit scale, e.g. 1/sqrt(128)       */
   int32_t agg;                                    /* as_agg: group aggregation of the scores       */
+  int32_t predictor;                              /* as_predictor                                  */
 } as_params;
 
 typedef struct {            /* caller-owned device memory, never freed by the library */

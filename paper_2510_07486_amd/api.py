@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libasyncspade.so")
 _lib = None
 
 AS_AGG_MAX, AS_AGG_SUM = 0, 1
+AS_PRED_PER_WINDOW, AS_PRED_SINGLE_SOLVE = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
            "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",
            "as_select_step_pack", "as_kv_append", "as_window_push", "as_gather_kv", "as_overlap_ratio",
@@ -29,7 +30,7 @@ class AsParams(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_size", C.c_int32), ("window", C.c_int32), ("budget", C.c_int32),
                 ("max_pages_per_seq", C.c_int32), ("ridge_eps", C.c_float), ("softmax_beta", C.c_float),
-                ("sm_scale", C.c_float), ("agg", C.c_int32)]
+                ("sm_scale", C.c_float), ("agg", C.c_int32), ("predictor", C.c_int32)]
 
 
 class AsKvView(C.Structure):
@@ -103,11 +104,11 @@ def lib():
 
 
 def make_params(batch, n_q_heads, n_kv_heads, window, budget, max_pages_per_seq, ridge_eps=1e-2, softmax_beta=1.0,
-                sm_scale=None, agg=AS_AGG_MAX, head_dim=128, page_size=16) -> AsParams:
+                sm_scale=None, agg=AS_AGG_MAX, head_dim=128, page_size=16, predictor=AS_PRED_PER_WINDOW) -> AsParams:
     if sm_scale is None:
         sm_scale = 1.0 / math.sqrt(head_dim)
     return AsParams(batch, n_q_heads, n_kv_heads, head_dim, page_size, window, budget, max_pages_per_seq,
-                    ridge_eps, softmax_beta, sm_scale, agg)
+                    ridge_eps, softmax_beta, sm_scale, agg, predictor)
 
 
 def _ptr(t: Optional[torch.Tensor]):

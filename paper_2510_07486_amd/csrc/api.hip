@@ -36,6 +36,7 @@ as_status check_params(const as_params* p) {
   if (p->n_q_heads % p->n_kv_heads != 0) return AS_ERR_INVALID_ARG;
   if (!(p->ridge_eps > 0.f)) return AS_ERR_INVALID_ARG;
   if (p->agg != AS_AGG_MAX && p->agg != AS_AGG_SUM) return AS_ERR_INVALID_ARG;
+  if (p->predictor != AS_PRED_PER_WINDOW && p->predictor != AS_PRED_SINGLE_SOLVE) return AS_ERR_INVALID_ARG;
   if (p->head_dim != AS_HEAD_DIM || p->page_size != AS_PAGE) return AS_ERR_UNSUPPORTED;
   if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
   if (p->n_q_heads / p->n_kv_heads > AS_MAX_GROUP) return AS_ERR_UNSUPPORTED;

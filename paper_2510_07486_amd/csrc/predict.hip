@@ -21,7 +21,7 @@ __host__ __device__ inline size_t predict_lds_bytes(int W) {
 }
 
 __global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int heads_per_layer, int W, double eps,
-                                                     double beta) {
+                                                     double beta, int single) {
   extern __shared__ double smem_d[];
   double* A = smem_d;                    // [W][W+1] lower Cholesky factor in place
   double* Om = A + (size_t)W * (W + 1);  // [W][W+1] row k-1: omega^{(k)} then w^{(k)}
@@ -95,13 +95,15 @@ __global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int hea
   }
   __syncthreads();
 
-  // 5. lane kk solves L_k^T omega = y_{1:k} for k = kk+1, then softmax(beta * omega)
+  // 5. lane kk solves L_k^T omega = y_{1:k} for k = kk+1 (single-solve mode: the full system for every lane,
+  //    of which lane kk keeps the kk+1 newest entries), then softmax(beta * omega)
   if (r < W) {
     const int kk = r;
+    const int ks = single ? W - 1 : kk;
     double* om = Om + kk * (W + 1);
-    for (int i = kk; i >= 0; --i) {
+    for (int i = ks; i >= 0; --i) {
       double s = yv[i];
-      for (int m = i + 1; m <= kk; ++m) s -= A[m * (W + 1) + i] * om[m];
+      for (int m = i + 1; m <= ks; ++m) s -= A[m * (W + 1) + i] * om[m];
       om[i] = s / A[i * (W + 1) + i];
     }
     double mx = beta * om[0];
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int hea
 // exponentials spread over the 64 lanes instead of W sequential ones per lane.
 template <int W>
 __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int heads_per_layer, double eps,
-                                                       double beta) {
+                                                       double beta, int single) {
   __shared__ float Rf[(W + 1) * RS];   // row i < W = Q_{t-1-i}, row W = Q_t
   __shared__ double A[W][W + 1];       // Gram, then the Cholesky factor L
   __shared__ double Om[W][W + 1];      // row k-1: beta*omega^{(k)} - max, then exp of it
@@ -236,7 +238,8 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int h
   }
   __syncthreads();
 
-  // lane kk: L_k^T omega = y_{1:k} for k = kk+1, weights stay zero above kk
+  // lane kk: L_k^T omega = y_{1:k} for k = kk+1, weights stay zero above kk (single-solve mode: every lane
+  // solves the full system; only its kk+1 newest entries enter the softmax below)
   double om[W];
 #pragma unroll
   for (int i = 0; i < W; ++i) om[i] = 0.0;
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int h
     double s = yv[i];
 #pragma unroll
     for (int m = i + 1; m < W; ++m) s -= A[m][i] * om[m];
-    om[i] = (i <= r) ? s * invd[i] : 0.0;
+    om[i] = (single || i <= r) ? s * invd[i] : 0.0;
   }
   if (r < W) {
     double mx = beta * om[0];
@@ -295,13 +298,14 @@ hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab&
   if (heads == 0) return hipSuccess;
   if (heads > 0x7fffffff) return hipErrorInvalidValue;
   const int hpl = (int)per_layer;
+  const int single = p->predictor == AS_PRED_SINGLE_SOLVE ? 1 : 0;
   if (p->window == 16 || p->window == 8) {
     if (p->window == 16)
       hipLaunchKernelGGL(predict_kernel_w<16>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
-                         (double)p->ridge_eps, (double)p->softmax_beta);
+                         (double)p->ridge_eps, (double)p->softmax_beta, single);
     else
       hipLaunchKernelGGL(predict_kernel_w<8>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
-                         (double)p->ridge_eps, (double)p->softmax_beta);
+                         (double)p->ridge_eps, (double)p->softmax_beta, single);
     return hipGetLastError();
   }
   size_t lds = predict_lds_bytes(p->window);
@@ -311,7 +315,7 @@ hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab&
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(predict_kernel, dim3((unsigned)heads), dim3(64), lds, s, tab, hpl, p->window,
-                     (double)p->ridge_eps, (double)p->softmax_beta);
+                     (double)p->ridge_eps, (double)p->softmax_beta, single);
   return hipGetLastError();
 }
 

@@ -40,6 +40,24 @@ def test_predict_matches_oracle(W, eps, beta):
         assert torch.equal(got, qc.float())
 
 
+@pytest.mark.parametrize("W", [1, 2, 5, 8, 16, 33, 64])
+@pytest.mark.parametrize("eps,beta", [(1e-2, 1.0), (1e-3, -1.0)])
+def test_single_solve_predictor_matches_oracle(W, eps, beta):
+    """Alg. 1 steps 3-5: one ridge solve over the whole window, truncated and renormalised per window size."""
+    note("predict single-solve", W, eps, beta)
+    w = wl.Workload("p", 3, 8, 2, W, 16, 64, rho_range=(0.8, 0.99), seed=100 + W)
+    qw, qc, _ = wl.make_queries(w)
+    ref = oracle.predict_query(qw, qc, f32(eps), beta, single_solve=True)
+    p = api.make_params(3, 8, 2, W, 16, 4, ridge_eps=f32(eps), softmax_beta=beta, predictor=api.AS_PRED_SINGLE_SOLVE)
+    ctx = api.Context(p)
+    got = api.as_predict_query(ctx, p, qw.cuda(), qc.cuda()).cpu()
+    err = (got - ref).abs().max().item()
+    assert err <= 2e-6 * max(1.0, ref.abs().max().item())
+    if W > 2:      # and it is a different predictor from the per-window-size one
+        other = oracle.predict_query(qw, qc, f32(eps), beta)
+        assert (other - ref).abs().max().item() > 1e-5
+
+
 # --------------------------------------------------------------------------- scoring
 @pytest.mark.parametrize("Hq,Hkv", [(8, 2), (8, 8), (16, 2), (4, 2), (32, 2), (6, 2), (1, 1)])
 @pytest.mark.parametrize("agg", [0, 1])
@@ -190,12 +208,13 @@ def test_attn_single_token_returns_value_row():
 
 
 # --------------------------------------------------------------------------- end to end
-def end_to_end(w, eps=1e-2, beta=1.0, agg=0, streams=False):
+def end_to_end(w, eps=1e-2, beta=1.0, agg=0, streams=False, single_solve=False):
     cpu = wl.make_inputs(w)
     dev = to_dev(cpu)
     q_hat, sc, ridx, rcnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur,
-                                               w.budget, f32(eps), beta, agg)
+                                               w.budget, f32(eps), beta, agg, single_solve=single_solve)
     p = params_for(cpu, eps=eps, beta=beta, agg=agg)
+    p.predictor = api.AS_PRED_SINGLE_SOLVE if single_solve else api.AS_PRED_PER_WINDOW
     ctx = api.Context(p)
     kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
     gidx, gcnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
@@ -270,6 +289,11 @@ def test_end_to_end_scaled_configs(name, kw):
 @pytest.mark.parametrize("agg,beta", [(1, 1.0), (0, -1.0)])
 def test_end_to_end_variants(agg, beta):
     end_to_end(wl.scaled(wl.CONFIGS["c2"], ctx=4096, budget=256), agg=agg, beta=beta)
+
+
+def test_end_to_end_single_solve_predictor():
+    end_to_end(wl.scaled(wl.CONFIGS["c2"], ctx=4096, budget=256), single_solve=True)
+    end_to_end(wl.scaled(wl.CONFIGS["c1"], ctx=2048, budget=128), beta=-1.0, single_solve=True)   # Alg. 1's sign too
 
 
 def test_two_stream_overlap_equals_serial():
