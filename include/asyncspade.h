@@ -21,11 +21,12 @@
  *   - bf16 = raw 16-bit brain-float bit patterns.  head_dim must be 128 and page_size 16.
  *   - KV layout: token n of sequence b lives in page block_table[b][n / 16], slot n % 16;
  *     element offset ((page * n_kv_heads + j) * 16 + slot) * 128 in the pool (64-bit).
- *   - Query head h belongs to KV head h / G with G = n_q_heads / n_kv_heads.
+ *   - Query head h belongs to KV head h / G with G = n_q_heads / n_kv_heads (1 <= G <= 64: multi-head,
+ *     grouped-query and multi-query layouts).
  *   - Return codes only; nothing throws or aborts across this boundary.  Arguments are
  *     validated on the host before any launch: AS_ERR_INVALID_ARG for null pointers,
  *     non-positive sizes, n_q_heads % n_kv_heads != 0, ridge_eps <= 0;
- *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 16,
+ *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 64,
  *     budget > 65536; AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
  *     Contents of device arrays (page ids in range, indices unique and in range) are
  *     the caller's contract; as a guard against faults, page ids are clamped into

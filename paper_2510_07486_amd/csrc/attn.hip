@@ -39,7 +39,7 @@ struct attn_geom { int nsplit, split_tokens, nsel; };
 static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (list_len < 1) list_len = 1;
-  int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? 1 : G / attn_gh(G));
+  int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? (G + 15) / 16 : G / attn_gh(G));
   if (pairs < 1) pairs = 1;
   int64_t nsel = (1536 + pairs - 1) / pairs;
   const int64_t max_sel = (list_len + AT_SPLIT - 1) / AT_SPLIT;

@@ -43,7 +43,10 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * AM_WAVE_LDS];
   __shared__ float m_sh[4][16], l_sh[4][16];
 
-  const int b = blockIdx.z, j = blockIdx.y, split = blockIdx.x;
+  // a workgroup serves up to 16 heads of a group: larger groups (MQA) take several head blocks per KV head
+  const int hblocks = (G + 15) / 16;
+  const int b = blockIdx.z, j = blockIdx.y / hblocks, g0 = (blockIdx.y % hblocks) * 16, split = blockIdx.x;
+  const int Gb = G - g0 < 16 ? G - g0 : 16;   // heads of this block
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int t = lane & 15, grp = lane >> 4;   // operand coordinates: row / column index, k group
   const int slot = grp, c = t;                // gather coordinates: row within a 4-row load, 16-byte chunk
@@ -68,9 +71,9 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);
   const int t_end = (split == nsplit - 1) ? L : (t_next < L ? t_next : L);
-  const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G) * nsplit + split;  // + g * nsplit per head
+  const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G + g0) * nsplit + split;  // + g * nsplit per head
   if (t_begin >= t_end) {                                                     // nothing here: mark empty
-    if (tid < G) {
+    if (tid < Gb) {
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 0] = -INFINITY;
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 1] = 0.f;
     }
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     uint4 u = make_uint4(0, 0, 0, 0);
-    if (t < G) u = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + (int64_t)j * G + t) * AS_HEAD_DIM + cmap(grp, m) * 8);
+    if (t < Gb) u = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + (int64_t)j * G + g0 + t) * AS_HEAD_DIM + cmap(grp, m) * 8);
     qb[m] = __builtin_bit_cast(bf16x8, u);
   }
 
@@ -228,13 +231,13 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
     for (int nt = 0; nt < 8; ++nt) red[(w * 16 + head) * AS_HEAD_DIM + nt * 16 + t] = o_acc[nt][i] * f;
   }
   __syncthreads();
-  for (int i = tid; i < G * AS_HEAD_DIM; i += 256) {
+  for (int i = tid; i < Gb * AS_HEAD_DIM; i += 256) {
     const int g = i / AS_HEAD_DIM, d = i % AS_HEAD_DIM;
     const float v = red[(0 * 16 + g) * AS_HEAD_DIM + d] + red[(1 * 16 + g) * AS_HEAD_DIM + d] +
                     red[(2 * 16 + g) * AS_HEAD_DIM + d] + red[(3 * 16 + g) * AS_HEAD_DIM + d];
     part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
   }
-  if (w == 0 && grp == 0 && t < G) {
+  if (w == 0 && grp == 0 && t < Gb) {
     part_ml[(pbase + (int64_t)t * nsplit) * 2 + 0] = M;
     part_ml[(pbase + (int64_t)t * nsplit) * 2 + 1] = Ls;
   }
@@ -244,7 +247,7 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
                             int nsplit, int list_len, hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
-  dim3 grid(nsplit, p->n_kv_heads, p->batch);
+  dim3 grid(nsplit, p->n_kv_heads * ((G + 15) / 16), p->batch);
   hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
                      reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
                      sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0,

@@ -8,7 +8,7 @@
 #define AS_HEAD_DIM 128
 #define AS_PAGE 16
 #define AS_MAX_WINDOW 64
-#define AS_MAX_GROUP 16
+#define AS_MAX_GROUP 64
 #define AS_MAX_BUDGET 65536
 #define AS_ATTN_CHUNK 128 /* tokens per attention split */
 #define AS_PACK_MAX AS_MAX_PACK /* layers one packed selection launch can cover */

@@ -219,6 +219,12 @@ hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, c
   hipLaunchKernelGGL(KERNEL, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat, scores, stride, \
                      p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, last_page)
   const bool nt = variant >= 10;
+  if (p->agg != AS_AGG_SUM && G > 16) {
+    // MQA-sized groups: four or eight operand sets of eight heads each; only the product variant is instantiated
+    if (G > 32) AS_SCORE_LAUNCH((score_mfma_lds<8, true, true>));
+    else AS_SCORE_LAUNCH((score_mfma_lds<4, true, true>));
+    return hipGetLastError();
+  }
   switch (variant % 10) {
     case 9:
       if (nt)

@@ -104,7 +104,14 @@ static select_plan plan_for(const as_params* p, int thr, int n_layers) {
   return pl;
 }
 
-select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, g_fs_threads, n_layers); }
+// Groups above 16 heads (MQA) keep four or eight MFMA operand sets in registers: that needs the register budget
+// of the 512-thread shape (two waves per SIMD).
+static int slice_threads_for(const as_params* p) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  return (p->agg != AS_AGG_SUM && G > 16) ? 512 : g_fs_threads;
+}
+
+select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, slice_threads_for(p), n_layers); }
 
 size_t select_workspace_bytes(const as_params* p, int n_layers) {
   size_t best = 0;  // sized for either workgroup shape
@@ -546,15 +553,17 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
     cand_cnt = cand_idx + n;
   }
   dim3 grid(p->n_kv_heads, p->batch * n_layers, pl.nslices);
-  const bool two = (p->agg != AS_AGG_SUM) && G > 8;
+  const int nset = (p->agg == AS_AGG_SUM || G <= 8) ? 1 : G <= 16 ? 2 : G <= 32 ? 4 : 8;
 #define AS_SLICE_LAUNCH(NSET_, THR_)                                                                              \
   hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, tab, p->batch, p->n_q_heads, \
                      p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, p->budget, pl.ccap,   \
                      cand_key, cand_idx, cand_cnt)
-  if (g_fs_threads == 1024) {
-    if (two) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
+  if (nset > 2) {
+    if (nset == 4) AS_SLICE_LAUNCH(4, 512); else AS_SLICE_LAUNCH(8, 512);
+  } else if (slice_threads_for(p) == 1024) {
+    if (nset == 2) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
   } else {
-    if (two) AS_SLICE_LAUNCH(2, 512); else AS_SLICE_LAUNCH(1, 512);
+    if (nset == 2) AS_SLICE_LAUNCH(2, 512); else AS_SLICE_LAUNCH(1, 512);
   }
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();

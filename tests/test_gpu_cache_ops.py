@@ -145,6 +145,7 @@ def test_gather_kv_bit_exact_and_dense_attention_over_the_compact_pool(kw):
     dict(batch=3, n_q_heads=8, n_kv_heads=2, ctx=2000, ctx_min=1),
     dict(batch=1, n_q_heads=32, n_kv_heads=8, ctx=16384),                            # configs[1] shape, full context
     dict(batch=5, n_q_heads=64, n_kv_heads=8, ctx=700, ctx_min=300),                 # group of 8
+    dict(batch=2, n_q_heads=40, n_kv_heads=1, ctx=1500, ctx_min=700),                # MQA, three head blocks
 ])
 def test_dense_decode_attn_matches_oracle(kw, impl):
     """Full attention over the whole cache (the baseline of Appendix B) = the oracle's attention with an

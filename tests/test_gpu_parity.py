@@ -59,7 +59,8 @@ def test_single_solve_predictor_matches_oracle(W, eps, beta):
 
 
 # --------------------------------------------------------------------------- scoring
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (8, 8), (16, 2), (4, 2), (32, 2), (6, 2), (1, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (8, 8), (16, 2), (4, 2), (32, 2), (6, 2), (1, 1), (32, 1), (48, 2), (64, 1),
+                                    (128, 2)])
 @pytest.mark.parametrize("agg", [0, 1])
 def test_score_matches_oracle(Hq, Hkv, agg):
     note("score", Hq, Hkv, agg)
@@ -166,7 +167,7 @@ def attn_case(w, sel="topk", tail=None, budget=None):
     return err
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2), (4, 4), (6, 2), (32, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2), (4, 4), (6, 2), (32, 2), (32, 1), (48, 2), (128, 2)])
 def test_attn_matches_oracle(Hq, Hkv):
     note("attn", Hq, Hkv)
     w = wl.Workload("a", 3, Hq, Hkv, 4, 300, 2000, ctx_min=100, page_table="scatter", pool_slack=1.2, seed=Hq + Hkv)
@@ -256,6 +257,9 @@ def fused_vs_separate(w):
     dict(batch=2, n_q_heads=8, n_kv_heads=2, ctx=5000, ctx_min=3000, budget=700),    # many short slices
     dict(batch=40, n_q_heads=16, n_kv_heads=8, ctx=20000, ctx_min=15000, budget=2048),  # long slices, two per row
     dict(batch=9, n_q_heads=64, n_kv_heads=4, ctx=3333, ctx_min=100, budget=64),     # group of 16
+    dict(batch=5, n_q_heads=32, n_kv_heads=1, ctx=9000, ctx_min=3000, budget=512),   # MQA, 32 heads on one KV head
+    dict(batch=3, n_q_heads=128, n_kv_heads=2, ctx=6000, ctx_min=500, budget=300),   # groups of 64
+    dict(batch=2, n_q_heads=48, n_kv_heads=2, ctx=2000, ctx_min=900, budget=100),    # group of 24 (not a power of two)
 ])
 def test_fused_select_equals_separate_kernels(kw):
     note("fused-vs-separate", kw)
@@ -289,6 +293,13 @@ def test_end_to_end_scaled_configs(name, kw):
 @pytest.mark.parametrize("agg,beta", [(1, 1.0), (0, -1.0)])
 def test_end_to_end_variants(agg, beta):
     end_to_end(wl.scaled(wl.CONFIGS["c2"], ctx=4096, budget=256), agg=agg, beta=beta)
+
+
+def test_end_to_end_mqa_groups():
+    # multi-query layouts of the paper's batched-matmul figure: every query head on one KV head
+    end_to_end(wl.Workload("mqa32", 4, 32, 1, 16, 512, 8192, ctx_min=2000, page_table="scatter", pool_slack=1.2, seed=61))
+    end_to_end(wl.Workload("mqa64", 2, 64, 1, 16, 256, 5000, ctx_min=2000, page_table="permute", seed=62), agg=1)
+    end_to_end(wl.Workload("gqa64", 2, 128, 2, 8, 384, 4000, ctx_min=100, page_table="scatter", pool_slack=1.1, seed=63))
 
 
 def test_end_to_end_single_solve_predictor():
