@@ -169,16 +169,26 @@ def main():
             select(l, sel[t][l], s_sels[0])
     torch.cuda.synchronize()
 
-    def step_overlapped(t, score_events=None):
+    # sel_done[parity][pack]: recorded on a selection stream when that pack's selection into sel[parity] is
+    # complete; the attention that reads it (one step later) waits for exactly that event
+    sel_done = [[None] * n_packs for _ in range(2)]
+
+    def step_overlapped(t, score_events=None, join=False):
+        """One decode step.  Attention of layer l (stream ATT) reads the selection made one step earlier and waits
+        only for that pack's event; the selection of a pack for the next step starts on a selection stream as soon as
+        the pack's last layer has its step-t query / key / value (i.e. when its attention is enqueued).  With
+        join=True (graph capture: events cannot cross graph launches) every selection stream is joined at step end."""
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
         for l in range(n_layers):
+            g = l // pack
+            if l % pack == 0 and sel_done[t % 2][g] is not None and not join:
+                s_att.wait_event(sel_done[t % 2][g])
             last_of_pack = (l % pack == pack - 1) or l == n_layers - 1
             if last_of_pack:                       # a pack is selected once its last layer's q/k/v exist
-                g = l // pack
                 lane = g % n_sel
                 ev = torch.cuda.Event()
-                ev.record(s_att)                   # layer l's step-t query/key/value exist from here on
-                s_sels[lane].wait_event(ev)
+                ev.record(s_att)                   # layer l's step-t query/key/value exist from here on; every
+                s_sels[lane].wait_event(ev)        # earlier reader of sel[(t+1) % 2] has been enqueued before it
                 pair = None
                 if score_events is not None:
                     pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -187,11 +197,16 @@ def main():
                     select_pack(g, (t + 1) % 2, s_sels[lane], pair, lane)
                 else:
                     select(l, nxt[l], s_sels[lane], pair, lane)
+                if not join:
+                    done = torch.cuda.Event()
+                    done.record(s_sels[lane])
+                    sel_done[(t + 1) % 2][g] = done
             attend(l, cur[l], s_att)
-        for s_sel in s_sels:                       # the next step's attention needs every new selection
-            done = torch.cuda.Event()
-            done.record(s_sel)
-            s_att.wait_event(done)
+        if join:
+            for s_sel in s_sels:
+                done = torch.cuda.Event()
+                done.record(s_sel)
+                s_att.wait_event(done)
 
     def step_serial(t, score_events=None):
         cur, nxt = sel[t % 2], sel[(t + 1) % 2]
@@ -230,7 +245,7 @@ def main():
             with torch.cuda.graph(g, stream=s_att):
                 for s_sel in s_sels:
                     s_sel.wait_stream(s_att)       # fork
-                step_overlapped(parity)            # joins the selection streams back into s_att at its end
+                step_overlapped(parity, join=True)  # joins the selection streams back into s_att at its end
             graphs.append(g)
         torch.cuda.synchronize()
         for t in range(a.warmup):
