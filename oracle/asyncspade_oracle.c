@@ -43,6 +43,7 @@
 
 #define ASO_AGG_MAX 0
 #define ASO_AGG_SUM 1
+/* 2 = softmax-normalised sum: aso_score_keys_softmax_sum */
 
 static double bf16_to_f64(uint16_t h) {
   uint32_t u = ((uint32_t)h) << 16;
@@ -281,6 +282,50 @@ int aso_score_keys(int B, int Hq, int Hkv, int D, int P, const uint16_t* k_pool,
         f = f + 0.0f;                     /* -0 -> +0 */
         scores[((size_t)b * Hkv + j) * stride + n] = f;
       }
+    }
+  return 0;
+}
+
+/*
+ * Criticality scores with softmax-normalised group aggregation (a reading of the point the paper
+ * leaves open, how the per-query-head logits of Alg. 1 step 7 become one score per KV head):
+ * every head's logits are turned into the attention distribution that head would have,
+ *   p[g][n] = exp(scale * l[g][n] - LSE_g),  LSE_g = log sum_{n < N_b} exp(scale * l[g][n]),
+ * and the score of token n is the probability mass the group gives it, s[n] = sum_g p[g][n].
+ * Two passes per row, all in fp64; same layout and conventions as aso_score_keys.
+ */
+int aso_score_keys_softmax_sum(int B, int Hq, int Hkv, int D, int P, const uint16_t* k_pool,
+                               const int32_t* block_table, int max_pages, const int32_t* ctx_lens,
+                               const float* q_hat, double scale, float* scores, int64_t stride) {
+  if (Hkv <= 0 || Hq % Hkv != 0) return -1;
+  int G = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < Hkv; ++j) {
+      int N = ctx_lens[b];
+      if (N <= 0) continue;
+      double* logit = (double*)malloc(sizeof(double) * (size_t)N * G);
+      double* lse = (double*)malloc(sizeof(double) * G);
+      for (int g = 0; g < G; ++g) {
+        const float* q = q_hat + ((size_t)b * Hq + (size_t)j * G + g) * D;
+        double m = -INFINITY;
+        for (int n = 0; n < N; ++n) {
+          const uint16_t* kr = token_ptr(k_pool, block_table, max_pages, Hkv, P, D, b, j, n);
+          double s = 0.0;
+          for (int d = 0; d < D; ++d) s += (double)q[d] * bf16_to_f64(kr[d]);
+          logit[(size_t)g * N + n] = scale * s;
+          if (scale * s > m) m = scale * s;
+        }
+        double z = 0.0;
+        for (int n = 0; n < N; ++n) z += exp(logit[(size_t)g * N + n] - m);
+        lse[g] = m + log(z);
+      }
+      for (int n = 0; n < N; ++n) {
+        double s = 0.0;
+        for (int g = 0; g < G; ++g) s += exp(logit[(size_t)g * N + n] - lse[g]);
+        scores[((size_t)b * Hkv + j) * stride + n] = (float)s;
+      }
+      free(logit); free(lse);
     }
   return 0;
 }

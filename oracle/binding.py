@@ -31,6 +31,7 @@ def _load():
         _lib.aso_predict_query.restype = C.c_int
         _lib.aso_predict_query_single_solve.restype = C.c_int
         _lib.aso_score_keys.restype = C.c_int
+        _lib.aso_score_keys_softmax_sum.restype = C.c_int
         _lib.aso_topk_select.restype = C.c_int
         _lib.aso_sparse_decode_attn.restype = C.c_int
         _lib.aso_ridge_weights.restype = C.c_int
@@ -86,7 +87,8 @@ def predict_query(q_win: torch.Tensor, q_cur: torch.Tensor, eps: float, beta: fl
 
 
 def score_keys(k_pool, block_table, ctx_lens, q_hat, n_kv_heads: int, agg: int = 0, stride: int | None = None,
-               fill: float = float("nan")):
+               fill: float = float("nan"), sm_scale: float | None = None):
+    """agg: 0 max, 1 sum of the group's raw logits; 2 sum of the group's softmax probabilities (needs sm_scale)."""
     num_pages, Hkv, P, D = k_pool.shape
     assert Hkv == n_kv_heads
     B, Hq, _ = q_hat.shape
@@ -94,6 +96,15 @@ def score_keys(k_pool, block_table, ctx_lens, q_hat, n_kv_heads: int, agg: int =
     if stride is None:
         stride = max_pages * P
     scores = torch.full((B, Hkv, stride), fill, dtype=torch.float32)
+    if agg == 2:
+        assert sm_scale is not None
+        rc = _load().aso_score_keys_softmax_sum(
+            C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(D), C.c_int(P), _p(k_pool.contiguous()),
+            _p(block_table.contiguous()), C.c_int(max_pages), _p(ctx_lens.contiguous()), _p(q_hat.contiguous()),
+            C.c_double(sm_scale), _p(scores), C.c_int64(stride))
+        if rc != 0:
+            raise RuntimeError(f"aso_score_keys_softmax_sum rc={rc}")
+        return scores
     rc = _load().aso_score_keys(C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(D), C.c_int(P), _p(k_pool.contiguous()),
                                 _p(block_table.contiguous()), C.c_int(max_pages), _p(ctx_lens.contiguous()),
                                 _p(q_hat.contiguous()), C.c_int(agg), _p(scores), C.c_int64(stride))
@@ -131,10 +142,10 @@ def sparse_decode_attn(k_pool, v_pool, block_table, ctx_lens, q, sel_idx, sel_cn
 
 
 def select_step(k_pool, block_table, ctx_lens, q_win, q_cur, budget: int, eps: float, beta: float = 1.0,
-                agg: int = 0, single_solve: bool = False):
+                agg: int = 0, single_solve: bool = False, sm_scale: float | None = None):
     """predict -> score -> top-k, the three oracle stages chained."""
     q_hat = predict_query(q_win, q_cur, eps, beta, single_solve=single_solve)
-    scores = score_keys(k_pool, block_table, ctx_lens, q_hat, k_pool.shape[1], agg)
+    scores = score_keys(k_pool, block_table, ctx_lens, q_hat, k_pool.shape[1], agg, sm_scale=sm_scale)
     sel_idx, sel_cnt = topk_select(scores, ctx_lens, budget)
     return q_hat, scores, sel_idx, sel_cnt
 

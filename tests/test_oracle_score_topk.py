@@ -136,3 +136,57 @@ def test_selection_invariant_under_positive_scaling_of_query():
     ia, ca = oracle.topk_select(a, inp.ctx_lens, 16)
     ib, cb = oracle.topk_select(b, inp.ctx_lens, 16)
     assert torch.equal(ia, ib) and torch.equal(ca, cb)
+
+
+# ---- softmax-normalised group aggregation (agg = 2) ----
+def _softmax_case(G, Hkv=2, B=2, ctx=300, scale=0.3, seed=0):
+    w = wl.Workload("sm", B, G * Hkv, Hkv, 4, 16, ctx, ctx_min=50, page_table="scatter", pool_slack=1.3, seed=seed)
+    cpu = wl.make_inputs(w)
+    q_hat = torch.randn((B, G * Hkv, 128), generator=torch.Generator().manual_seed(seed + 1)) * 0.5
+    sc = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q_hat, Hkv, 2, fill=-7.0, sm_scale=scale)
+    return cpu, q_hat, sc
+
+
+def test_softmax_sum_matches_numpy_and_sums_to_group_size():
+    G, Hkv, scale = 4, 2, 0.3
+    cpu, q_hat, sc = _softmax_case(G, Hkv, scale=scale)
+    for b in range(2):
+        n = int(cpu.ctx_lens[b])
+        for j in range(Hkv):
+            K = gather_keys(cpu.k_pool, cpu.block_table, b, j, n)                     # [n, 128] fp64
+            ref = np.zeros(n)
+            for g in range(G):
+                l = scale * (K @ q_hat[b, j * G + g].double().numpy())
+                e = np.exp(l - l.max())
+                ref += e / e.sum()
+            np.testing.assert_allclose(sc[b, j, :n].numpy(), ref.astype(np.float32), rtol=2e-6, atol=1e-30)
+            assert abs(float(sc[b, j, :n].double().sum()) - G) < 1e-4                 # every head's mass is 1
+            assert (sc[b, j, n:] == -7.0).all()                                       # nothing written past the context
+
+
+def test_softmax_sum_with_one_head_ranks_like_the_raw_logits():
+    # G = 1: exp is monotone, so the order of the scores (hence any top-k) is that of the raw logits
+    cpu, q_hat, sc = _softmax_case(1, Hkv=3, scale=0.7, seed=5)
+    raw = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q_hat, 3, 0)
+    for b in range(2):
+        n = int(cpu.ctx_lens[b])
+        for j in range(3):
+            a = np.argsort(-sc[b, j, :n].double().numpy(), kind="stable")
+            r = np.argsort(-raw[b, j, :n].double().numpy(), kind="stable")
+            assert np.array_equal(a[:40], r[:40])
+
+
+def test_softmax_sum_is_scale_free_across_heads():
+    # multiplying one head's query by a constant changes that head's distribution only; with raw-logit max or sum
+    # aggregation the largest head dominates, here a head 100 x smaller in norm still contributes its full unit of mass
+    cpu, q_hat, sc = _softmax_case(2, Hkv=1, B=1, ctx=200, scale=1.0, seed=9)
+    q2 = q_hat.clone()
+    q2[:, 1] *= 0.01
+    sc2 = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q2, 1, 2, sm_scale=1.0)
+    n = int(cpu.ctx_lens[0])
+    assert abs(float(sc2[0, 0, :n].double().sum()) - 2.0) < 1e-4
+    # head 1 became almost uniform: its contribution is close to 1/n for every token
+    K = gather_keys(cpu.k_pool, cpu.block_table, 0, 0, n)
+    l0 = K @ q_hat[0, 0].double().numpy()
+    p0 = np.exp(l0 - l0.max()); p0 /= p0.sum()
+    np.testing.assert_allclose(sc2[0, 0, :n].double().numpy() - p0, 1.0 / n, rtol=0.35)
