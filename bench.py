@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--ctx", type=int, default=0, help="override the workload's context length (sweeps)")
     ap.add_argument("--q-heads", type=int, default=0, help="override the query head count (head-layout comparison)")
     ap.add_argument("--kv-heads", type=int, default=0, help="override the KV head count")
+    ap.add_argument("--agg", type=int, default=0, help="group aggregation: 0 max (default), 1 sum, 2 softmax-normalised sum "
+                    "(two passes over K: the scoring roofline then counts the K bytes twice)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time to spend on the oracle baseline")
     ap.add_argument("--score-variant", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -104,7 +106,7 @@ def main():
 
     eps = float(np.float32(1e-2))
     p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1], ridge_eps=eps,
-                        sm_scale=float(np.float32(1 / math.sqrt(128))))
+                        sm_scale=float(np.float32(1 / math.sqrt(128))), agg=a.agg)
     n_sel = max(1, a.sel_streams)
     pack = max(1, min(a.pack, api.AS_MAX_PACK, n_layers))
     ctx_sels = [api.Context(p, pack=pack) for _ in range(n_sel)]
@@ -269,7 +271,7 @@ def main():
     us_layer = ms_step * 1e3 / n_layers
     us_layer_serial = dt_serial / a.steps * 1e6 / n_layers
     tokens = int(ctx_lens_cpu.sum())
-    k_bytes = tokens * Hkv * 256                                   # algorithmic bytes of one scoring launch
+    k_bytes = tokens * Hkv * 256 * (2 if a.agg == 2 else 1)        # algorithmic bytes of one scoring launch
     kv_gather = int(torch.clamp(ctx_lens_cpu, max=C).sum()) * Hkv * 512
     # dominant kernel: the K-streaming part of the selection.  Its roofline uses the launches of the
     # single-stream timed pass (the kernel alone on the GPU); the rate it keeps while sharing HBM with
@@ -298,7 +300,7 @@ def main():
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128, "context": w.ctx,
                    "window": w.window, "budget": C, "page_size": 16, "layers_per_step": n_layers,
                    "layers_resident": resident, "streams": 1 if a.serial_only else 1 + n_sel,
-                   "layers_per_select_launch": pack, "launch": "hip graph replay" if a.graph else "eager"},
+                   "layers_per_select_launch": pack, "group_aggregation": ["max", "sum", "softmax-sum"][a.agg], "launch": "hip graph replay" if a.graph else "eager"},
         "serial_us_per_layer_step": round(us_layer_serial, 2),
         "step_roofline_us": round(step_roofline_us, 2),
         "step_roofline_frac": round(step_roofline_us / us_layer, 4),
@@ -356,7 +358,8 @@ def main():
             reps, cpu_s = 0, 0.0
             while cpu_s < a.cpu_seconds and reps < 200:
                 t1 = time.perf_counter()
-                q_h, sc, ridx, rcnt = oracle.select_step(ck, bt_cpu, ctx_lens_cpu, cqw, cqc, C, eps)
+                q_h, sc, ridx, rcnt = oracle.select_step(ck, bt_cpu, ctx_lens_cpu, cqw, cqc, C, eps, agg=a.agg,
+                                                         sm_scale=scale)
                 oracle.sparse_decode_attn(ck, cv, bt_cpu, ctx_lens_cpu, cqr, ridx, rcnt, scale)
                 cpu_s += time.perf_counter() - t1
                 reps += 1
@@ -369,7 +372,8 @@ def main():
             subs = [wl.extract_sequence(inp, b) for b in range(ns)]
             t1 = time.perf_counter()
             for sq in subs:
-                q_h, sc, ridx, rcnt = oracle.select_step(sq.k_pool, sq.block_table, sq.ctx_lens, sq.q_win, sq.q_cur, C, eps)
+                q_h, sc, ridx, rcnt = oracle.select_step(sq.k_pool, sq.block_table, sq.ctx_lens, sq.q_win, sq.q_cur, C, eps,
+                                                         agg=a.agg, sm_scale=scale)
                 oracle.sparse_decode_attn(sq.k_pool, sq.v_pool, sq.block_table, sq.ctx_lens, sq.q_real, ridx, rcnt, scale)
             cpu_s = time.perf_counter() - t1
             res["cpu_baseline"] = {"value": round(cpu_s / ns * B * 1e6, 1), "unit": "us/layer-step", "cores": nthreads,

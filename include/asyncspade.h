@@ -54,7 +54,14 @@ typedef enum {
   AS_ERR_HIP = 4
 } as_status;
 
-typedef enum { AS_AGG_MAX = 0, AS_AGG_SUM = 1 } as_agg;
+/* How the per-query-head logits of a GQA group become one score per KV head (the paper leaves it open):
+ *   AS_AGG_MAX          max over the group of the raw logits (default)
+ *   AS_AGG_SUM          sum over the group of the raw logits (= the logit of the summed query)
+ *   AS_AGG_SOFTMAX_SUM  sum over the group of each head's softmax probability,
+ *                       s[n] = sum_g exp(sm_scale * l[g][n] - LSE_g): scale-free across heads; costs a second
+ *                       pass over K; only the fused calls (as_score_topk, as_select_step, as_select_step_pack)
+ *                       offer it, as_score_keys returns AS_ERR_UNSUPPORTED */
+typedef enum { AS_AGG_MAX = 0, AS_AGG_SUM = 1, AS_AGG_SOFTMAX_SUM = 2 } as_agg;
 
 /* How the weights of window size k are obtained (Sec. 4.2 vs Appendix C):
  *   AS_PRED_PER_WINDOW    one ridge problem per window size, over its k newest predecessors (Sec. 4.2,

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libasyncspade.so")
 _lib = None
 
-AS_AGG_MAX, AS_AGG_SUM = 0, 1
+AS_AGG_MAX, AS_AGG_SUM, AS_AGG_SOFTMAX_SUM = 0, 1, 2
 AS_PRED_PER_WINDOW, AS_PRED_SINGLE_SOLVE = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
            "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",

@@ -35,7 +35,7 @@ as_status check_params(const as_params* p) {
     return AS_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return AS_ERR_INVALID_ARG;
   if (!(p->ridge_eps > 0.f)) return AS_ERR_INVALID_ARG;
-  if (p->agg != AS_AGG_MAX && p->agg != AS_AGG_SUM) return AS_ERR_INVALID_ARG;
+  if (p->agg != AS_AGG_MAX && p->agg != AS_AGG_SUM && p->agg != AS_AGG_SOFTMAX_SUM) return AS_ERR_INVALID_ARG;
   if (p->predictor != AS_PRED_PER_WINDOW && p->predictor != AS_PRED_SINGLE_SOLVE) return AS_ERR_INVALID_ARG;
   if (p->head_dim != AS_HEAD_DIM || p->page_size != AS_PAGE) return AS_ERR_UNSUPPORTED;
   if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
@@ -121,6 +121,7 @@ as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_hat || !scores) return AS_ERR_INVALID_ARG;
+  if (p->agg == AS_AGG_SOFTMAX_SUM) return AS_ERR_UNSUPPORTED;   // needs the row-wide normalisers: fused calls only
   if (score_stride < (int64_t)p->max_pages_per_seq * AS_PAGE) return AS_ERR_INVALID_ARG;
   return hip_status(asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, score_stride,
                                       static_cast<hipStream_t>(stream)));
@@ -190,7 +191,7 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
                                      q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
-  if (ctx->select_mode == 0)
+  if (ctx->select_mode == 0 || p->agg == AS_AGG_SOFTMAX_SUM)
     return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
   e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, l.score_stride, s);
   if (e != hipSuccess) return AS_ERR_HIP;

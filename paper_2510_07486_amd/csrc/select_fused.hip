@@ -113,15 +113,24 @@ static int slice_threads_for(const as_params* p) {
 
 select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, slice_threads_for(p), n_layers); }
 
+// bytes of the candidate arrays (rows cut into several shares) and, behind them, of the per-share (max, sum)
+// pairs of the softmax-normalised aggregation
+static size_t cand_bytes(const as_params* p, const select_plan& pl, int n_layers) {
+  if (pl.nslices <= 1) return 0;
+  const size_t rows = (size_t)p->batch * p->n_kv_heads * n_layers;
+  return (rows * pl.nslices * ((size_t)pl.ccap * 8 + 4) + 15) / 16 * 16;
+}
+static size_t lse_bytes(const as_params* p, const select_plan& pl, int n_layers) {
+  if (p->agg != AS_AGG_SOFTMAX_SUM) return 0;
+  return (size_t)p->batch * p->n_q_heads * n_layers * pl.nslices * sizeof(float2);
+}
+
 size_t select_workspace_bytes(const as_params* p, int n_layers) {
   size_t best = 0;  // sized for either workgroup shape
   for (int thr : {512, 1024}) {
     const select_plan pl = plan_for(p, thr, n_layers);
-    if (pl.nslices > 1) {
-      const size_t rows = (size_t)p->batch * p->n_kv_heads * n_layers;
-      const size_t b = rows * pl.nslices * ((size_t)pl.ccap * 8 + 4);
-      if (b > best) best = b;
-    }
+    const size_t b = cand_bytes(p, pl, n_layers) + lse_bytes(p, pl, n_layers);
+    if (b > best) best = b;
   }
   return best;
 }
@@ -190,10 +199,15 @@ __device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const 
   return T;
 }
 
-template <int NSET, int FS_THREADS, int PG>
+// MODE 0: scores are the max (or the pre-summed query's logit) over the group.  MODES 1 and 2 are the two passes
+// of the softmax-normalised aggregation s[n] = sum_g exp(scale * l[g][n] - LSE_g): pass 1 streams the share and
+// leaves one (max, sum) pair per head in lse_part, pass 2 merges the pairs of all shares of its row into LSE_g
+// and then selects exactly like mode 0 with s[n] as the score.
+template <int NSET, int FS_THREADS, int PG, int MODE>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const sel_tab tab, int B, int Hq, int Hkv, int G, int agg, int max_pages, int share_len, int nshares, int C,
-    int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt) {
+    int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt,
+    float sm_scale, float2* __restrict__ lse_part) {
   using shape = fs_shape<FS_THREADS>;
   constexpr int FS_WAVES = shape::WAVES, CAP = shape::CAP, NPT = CAP / FS_THREADS;
   constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS, BM_WORDS = shape::SHARE_CAP / 32;
@@ -247,6 +261,10 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   int n_share = N - tok0;
   n_share = n_share < 0 ? 0 : (n_share > share_len ? share_len : n_share);
   const bool final_out = (nshares == 1);
+  if (MODE == 1 && n_share == 0) {
+    if (tid < G) lse_part[(crow * nshares + sh) * G + tid] = make_float2(-INFINITY, 0.f);
+    return;
+  }
   if (n_share == 0) {
     if (final_out) {
       for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = -1;
@@ -281,6 +299,43 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
 
+  // softmax modes: the lane's accumulators of operand set s belong to heads s*8 + 2*grp and s*8 + 2*grp + 1
+  float hm[NSET][2], hl[NSET][2];   // pass 1: running (max, sum of exp) of this lane's token column; pass 2: hm = LSE
+#pragma unroll
+  for (int s = 0; s < NSET; ++s)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      hm[s][e] = MODE == 2 ? INFINITY : -INFINITY;
+      hl[s][e] = 0.f;
+    }
+  if (MODE == 2) {
+    // LSE of the group's heads over the whole row: wave w merges the per-share pairs of heads w, w + WAVES, ...
+    float* lse_sh = reinterpret_cast<float*>(hist);
+    for (int h = wave; h < G; h += FS_WAVES) {
+      float m = -INFINITY;
+      for (int s2 = lane; s2 < nshares; s2 += 64) m = fmaxf(m, lse_part[(crow * nshares + s2) * G + h].x);
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      float l = 0.f;
+      for (int s2 = lane; s2 < nshares; s2 += 64) {
+        const float2 v = lse_part[(crow * nshares + s2) * G + h];
+        l += v.y > 0.f ? v.y * __expf(v.x - m) : 0.f;
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) l += __shfl_xor(l, o);
+      if (lane == 0) lse_sh[h] = m + __logf(l);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NSET; ++s)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int h = s * 8 + 2 * grp + e;
+        if (h < G) hm[s][e] = lse_sh[h];
+      }
+    // hist is next written by a prune, which every wave reaches only through the barrier after its first sub-slice
+  }
+
   uint4* st = stage[wave];
   bool have_tau = false;   // after the first prune: only keys above tau can still make the best C
   uint32_t tau = 0;
@@ -311,17 +366,43 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 #pragma unroll
         for (int m = 0; m < 4; ++m) kk[m] = st[lds_slot(t, cmap(grp, m))];
         __builtin_amdgcn_wave_barrier();
-        float v = -INFINITY;
+        float v = MODE == 0 ? -INFINITY : 0.f;
+        const bool tok_ok = (q * PG + pg) * AS_PAGE + t < n_sub;   // this lane's token of this page
 #pragma unroll
         for (int s = 0; s < NSET; ++s) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int m = 0; m < 4; ++m)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[s][m], __builtin_bit_cast(bf16x8, kk[m]), acc, 0, 0, 0);
-          v = fmaxf(v, fold_rows(acc));
+          if (MODE == 0) {
+            v = fmaxf(v, fold_rows(acc));
+          } else {
+            const float x[2] = {(acc[0] + acc[2]) * sm_scale, (acc[1] + acc[3]) * sm_scale};
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              if (MODE == 1) {
+                if (tok_ok) {
+                  const float mn = fmaxf(hm[s][e], x[e]);
+                  hl[s][e] = hl[s][e] * __expf(hm[s][e] - mn) + __expf(x[e] - mn);
+                  hm[s][e] = mn;
+                }
+              } else {
+                v += __expf(x[e] - hm[s][e]);   // hm = +inf for head slots beyond the group: contributes 0
+              }
+            }
+          }
         }
-        res[pg] = group_max(v);
+        if (MODE == 0) {
+          res[pg] = group_max(v);
+        } else if (MODE == 2) {
+          v += __shfl_xor(v, 16);
+          v += __shfl_xor(v, 32);
+          res[pg] = v;
+        } else {
+          res[pg] = 0.f;
+        }
       }
+      if (MODE == 1) continue;   // pass 1 keeps no candidates
       float outv = res[0];
 #pragma unroll
       for (int pg = 1; pg < PG; ++pg) outv = grp == pg ? res[pg] : outv;
@@ -344,6 +425,11 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     pos += n_sub;
     const bool last = pos >= n_share;
     if (!last) my_page = load_pages(pos);   // page ids of the next sub-slice travel during the barrier / prune
+    if (MODE == 1) {                        // no candidate buffer to watch: whole-buffer-sized sub-slices, no barrier
+      if (last) break;
+      n_sub = (n_share - pos) < CAP ? (n_share - pos) : CAP;
+      continue;
+    }
     __syncthreads();
     cnt = (int)c_cnt;
     if (last) break;
@@ -385,6 +471,38 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const int room = (CAP - cnt) & ~63;
     if (room <= 0) break;   // unreachable while the host plan keeps C <= CAP / 2 for multi-sub-slice shares
     n_sub = (n_share - pos) < room ? (n_share - pos) : room;
+  }
+
+  if (MODE == 1) {
+    // ---- merge the token columns (16 lanes), then the waves, and leave one (max, sum) pair per head ----
+    float2* red = reinterpret_cast<float2*>(hist);   // [FS_WAVES][64 heads]
+#pragma unroll
+    for (int s = 0; s < NSET; ++s)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        float m = hm[s][e], l = hl[s][e];
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+          const float m2 = __shfl_xor(m, o), l2 = __shfl_xor(l, o);
+          const float mn = fmaxf(m, m2);
+          l = (m == -INFINITY ? 0.f : l * __expf(m - mn)) + (m2 == -INFINITY ? 0.f : l2 * __expf(m2 - mn));
+          m = mn;
+        }
+        const int h = s * 8 + 2 * grp + e;
+        if (t == 0 && h < 64) red[wave * 64 + h] = make_float2(m, l);
+      }
+    __syncthreads();
+    if (tid < G) {
+      float m = -INFINITY;
+      for (int w2 = 0; w2 < FS_WAVES; ++w2) m = fmaxf(m, red[w2 * 64 + tid].x);
+      float l = 0.f;
+      for (int w2 = 0; w2 < FS_WAVES; ++w2) {
+        const float2 v = red[w2 * 64 + tid];
+        l += v.x == -INFINITY ? 0.f : v.y * __expf(v.x - m);
+      }
+      lse_part[(crow * nshares + sh) * G + tid] = make_float2(m, l);
+    }
+    return;
   }
 
   // ---- the share's best min(C, cnt), in ascending token order ----
@@ -554,16 +672,28 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   }
   dim3 grid(p->n_kv_heads, p->batch * n_layers, pl.nslices);
   const int nset = (p->agg == AS_AGG_SUM || G <= 8) ? 1 : G <= 16 ? 2 : G <= 32 ? 4 : 8;
-#define AS_SLICE_LAUNCH(NSET_, THR_)                                                                              \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG>), grid, dim3(THR_), 0, s, tab, p->batch, p->n_q_heads, \
-                     p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices, p->budget, pl.ccap,   \
-                     cand_key, cand_idx, cand_cnt)
-  if (nset > 2) {
-    if (nset == 4) AS_SLICE_LAUNCH(4, 512); else AS_SLICE_LAUNCH(8, 512);
+  float2* lse_part = reinterpret_cast<float2*>(static_cast<char*>(ws) + cand_bytes(p, pl, n_layers));
+#define AS_SLICE_LAUNCH(NSET_, THR_, MODE_)                                                                       \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG, MODE_>), grid, dim3(THR_), 0, s, tab, p->batch,     \
+                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices,      \
+                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
+  if (p->agg == AS_AGG_SOFTMAX_SUM) {
+    // two passes over K with the same grid: per-share (max, sum) pairs, then selection on the normalised scores
+    if (nset == 8) { AS_SLICE_LAUNCH(8, 512, 1); AS_SLICE_LAUNCH(8, 512, 2); }
+    else if (nset == 4) { AS_SLICE_LAUNCH(4, 512, 1); AS_SLICE_LAUNCH(4, 512, 2); }
+    else if (slice_threads_for(p) == 1024) {
+      if (nset == 2) { AS_SLICE_LAUNCH(2, 1024, 1); AS_SLICE_LAUNCH(2, 1024, 2); }
+      else { AS_SLICE_LAUNCH(1, 1024, 1); AS_SLICE_LAUNCH(1, 1024, 2); }
+    } else {
+      if (nset == 2) { AS_SLICE_LAUNCH(2, 512, 1); AS_SLICE_LAUNCH(2, 512, 2); }
+      else { AS_SLICE_LAUNCH(1, 512, 1); AS_SLICE_LAUNCH(1, 512, 2); }
+    }
+  } else if (nset > 2) {
+    if (nset == 4) AS_SLICE_LAUNCH(4, 512, 0); else AS_SLICE_LAUNCH(8, 512, 0);
   } else if (slice_threads_for(p) == 1024) {
-    if (nset == 2) AS_SLICE_LAUNCH(2, 1024); else AS_SLICE_LAUNCH(1, 1024);
+    if (nset == 2) AS_SLICE_LAUNCH(2, 1024, 0); else AS_SLICE_LAUNCH(1, 1024, 0);
   } else {
-    if (nset == 2) AS_SLICE_LAUNCH(2, 512); else AS_SLICE_LAUNCH(1, 512);
+    if (nset == 2) AS_SLICE_LAUNCH(2, 512, 0); else AS_SLICE_LAUNCH(1, 512, 0);
   }
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();

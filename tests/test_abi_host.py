@@ -36,7 +36,7 @@ def test_workspace_bytes_and_param_validation():
     dummy = C.c_void_p(0)
     for kw, code in [(dict(n_q_heads=6, n_kv_heads=4), 1), (dict(ridge_eps=0.0), 1), (dict(window=0), 1),
                      (dict(budget=0), 1), (dict(head_dim=64), 2), (dict(page_size=32), 2), (dict(window=65), 2),
-                     (dict(budget=65537), 2), (dict(n_q_heads=65, n_kv_heads=1), 2), (dict(agg=7), 1),
+                     (dict(budget=65537), 2), (dict(n_q_heads=65, n_kv_heads=1), 2), (dict(agg=7), 1), (dict(agg=3), 1),
                      (dict(predictor=2), 1)]:
         args = dict(batch=1, n_q_heads=8, n_kv_heads=2, window=4, budget=16, max_pages_per_seq=4)
         args.update(kw)

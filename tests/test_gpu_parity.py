@@ -364,3 +364,60 @@ def test_select_is_invariant_to_query_scaling_and_constant_window():
                        for j in range(w.n_kv_heads)])
     note("  overlap ratio (Eq. 1), constant window:", overlap)
     assert overlap >= 0.99
+
+
+# --------------------------------------------------------------------------- softmax-normalised aggregation
+def softmax_sum_case(w, n_layers=1, eps=1e-2):
+    """Selection with agg = AS_AGG_SOFTMAX_SUM (two passes over K) against the oracle's selection of its own
+    softmax-normalised scores, through as_select_step (or the packed call)."""
+    cpus = [wl.make_inputs(w, layer=l) for l in range(n_layers)]
+    devs = [to_dev(c) for c in cpus]
+    p = params_for(cpus[0], eps=eps, agg=api.AS_AGG_SOFTMAX_SUM)
+    ctx = api.Context(p, pack=n_layers)
+    kvs = [api.kv_view(d.k_pool, d.v_pool, d.block_table, d.ctx_lens) for d in devs]
+    if n_layers == 1:
+        got = [api.as_select_step(ctx, p, kvs[0], devs[0].q_win, devs[0].q_cur)]
+    else:
+        B, Hkv, C = w.batch, w.n_kv_heads, w.budget
+        got = [(torch.empty((B, Hkv, C), dtype=torch.int32, device="cuda"),
+                torch.empty((B, Hkv), dtype=torch.int32, device="cuda")) for _ in range(n_layers)]
+        api.as_select_step_pack(ctx, p, [api.layer_io(kvs[l], devs[l].q_win, devs[l].q_cur, got[l][0], got[l][1])
+                                         for l in range(n_layers)])
+    torch.cuda.synchronize()
+    swaps = 0
+    for l, c in enumerate(cpus):
+        q_hat, sc, ridx, rcnt = oracle.select_step(c.k_pool, c.block_table, c.ctx_lens, c.q_win, c.q_cur, w.budget,
+                                                   f32(eps), agg=2, sm_scale=f32(SCALE))
+        swaps += compare_selection(got[l][0], got[l][1], ridx, rcnt, sc, c.ctx_lens, w.budget)
+    note(f"  softmax-sum {w.name}: plan {api.select_plan(p, n_layers)}, tie swaps {swaps}")
+
+
+@pytest.mark.parametrize("kw", [
+    dict(batch=40, n_q_heads=32, n_kv_heads=8, ctx=3000, ctx_min=1, budget=256),        # one share per row
+    dict(batch=2, n_q_heads=8, n_kv_heads=2, ctx=9000, ctx_min=5000, budget=700),       # rows cut into many shares
+    dict(batch=3, n_q_heads=4, n_kv_heads=4, ctx=2500, ctx_min=700, budget=64),         # G = 1
+    dict(batch=3, n_q_heads=32, n_kv_heads=2, ctx=2000, ctx_min=100, budget=128),       # G = 16: two operand sets
+    dict(batch=2, n_q_heads=48, n_kv_heads=2, ctx=1500, ctx_min=300, budget=100),       # G = 24: four sets, 512 threads
+    dict(batch=2, n_q_heads=64, n_kv_heads=1, ctx=1200, ctx_min=600, budget=2048),      # G = 64, budget above context
+])
+def test_softmax_sum_aggregation_matches_oracle(kw):
+    note("softmax-sum", kw)
+    softmax_sum_case(wl.Workload("ss", window=8, page_table="scatter", pool_slack=1.2, seed=71, **kw))
+
+
+def test_softmax_sum_long_single_share_rows_and_pack():
+    # 256 rows of 20000 tokens: one share per row, several prunes, as in the benchmark's launch shape
+    softmax_sum_case(wl.Workload("ssl", 32, 32, 8, 16, 2048, 20000, ctx_min=12000, page_table="permute", seed=72))
+    softmax_sum_case(wl.Workload("ssp", 1, 8, 2, 8, 256, 4096, page_table="identity", seed=73), n_layers=3)
+
+
+def test_softmax_sum_is_rejected_by_the_stand_alone_scoring_call():
+    w = wl.Workload("sr", 1, 8, 2, 4, 16, 64, seed=1)
+    cpu = wl.make_inputs(w)
+    dev = to_dev(cpu)
+    p = params_for(cpu, agg=api.AS_AGG_SOFTMAX_SUM)
+    ctx = api.Context(p)
+    with pytest.raises(api.AsError) as e:
+        api.as_score_keys(ctx, p, api.kv_view(dev.k_pool, None, dev.block_table, dev.ctx_lens),
+                          torch.zeros((1, 8, 128), device="cuda"))
+    assert e.value.code == 2
