@@ -27,7 +27,9 @@
  *     validated on the host before any launch: AS_ERR_INVALID_ARG for null pointers,
  *     non-positive sizes, n_q_heads % n_kv_heads != 0, ridge_eps <= 0;
  *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 64,
- *     budget > 65536; AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
+ *     budget > 65536, and for the fused selection calls when budget > 4096 is combined with a block
+ *     table of more than 8 million tokens per sequence; AS_ERR_WORKSPACE if the ctx workspace is too
+ *     small for the call.
  *     Contents of device arrays (page ids in range, indices unique and in range) are
  *     the caller's contract; as a guard against faults, page ids are clamped into
  *     [0, num_pages) and token indices into [0, ctx_lens[b]) before they are used, so a

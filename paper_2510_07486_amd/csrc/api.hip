@@ -170,6 +170,7 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  if (!asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
   const ws_layout l = layout_of(p);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   return hip_status(asx::launch_select_fused(p, kv, q_hat, static_cast<char*>(ctx->ws) + l.cand, sel_idx, sel_cnt,
@@ -182,6 +183,7 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  if (ctx->select_mode == 0 && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
   const ws_layout l = layout_of(p);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
@@ -214,6 +216,7 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     if ((st = check_kv(&layers[l].kv, false)) != AS_OK) return st;
     if (!layers[l].q_win || !layers[l].q_cur || !layers[l].sel_idx || !layers[l].sel_cnt) return AS_ERR_INVALID_ARG;
   }
+  if (!asx::select_plan_ok(p, n_layers)) return AS_ERR_UNSUPPORTED;
   const ws_layout lay = layout_of(p, n_layers);
   if (!ctx->ws || ctx->ws_bytes < lay.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);

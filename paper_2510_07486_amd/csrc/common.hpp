@@ -76,6 +76,7 @@ hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, 
 // fused scoring + top-k (select_fused.hip): rows are cut into slices of `slice_len` tokens
 struct select_plan { int slice_len, nslices, ccap; };
 select_plan plan_select(const as_params* p, int n_layers);
+bool select_plan_ok(const as_params* p, int n_layers);
 size_t select_workspace_bytes(const as_params* p, int n_layers);
 hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s);
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,

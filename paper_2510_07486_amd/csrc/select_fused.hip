@@ -58,8 +58,8 @@ static int device_cus() {
 // the longest context the block table allows.  Workgroups run in rounds of one resident set;
 // a full round streams at the chip's rate (HBM-bound, T_SHARED per token and workgroup), a
 // partly filled last round at the rate one compute unit can pull alone (T_ALONE).  Every share
-// pays a fixed start-up, one LDS select per sub-slice and, when a row has several shares, its
-// candidates through HBM plus the merge kernel.  Constants are measured on MI355X.
+// pays a fixed start-up, its selections (typically one prune and the final one when it is longer than
+// the candidate buffer) and, when a row has several shares, its candidates through HBM plus the merge kernel.  Constants are measured on MI355X.
 static select_plan plan_for(const as_params* p, int thr, int n_layers) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
@@ -112,6 +112,10 @@ static int slice_threads_for(const as_params* p) {
 }
 
 select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, slice_threads_for(p), n_layers); }
+
+// false when no share plan fits: a budget above half the candidate buffer forces buffer-sized shares, and the merge
+// kernel indexes at most FS_MAX_SLICES of them per row (contexts beyond 4-8 million tokens at such budgets)
+bool select_plan_ok(const as_params* p, int n_layers) { return plan_select(p, n_layers).nslices <= FS_MAX_SLICES; }
 
 // bytes of the candidate arrays (rows cut into several shares) and, behind them, of the per-share (max, sum)
 // pairs of the softmax-normalised aggregation

@@ -69,6 +69,12 @@ def test_pack_workspace_and_share_plan():
     for n in (1, 4, 16):
         share, shares, cand = api.select_plan(small, n)
         assert share * shares >= 4096 and share % 64 == 0 and cand == min(256, share)
+    # a budget above half the candidate buffer forces buffer-sized shares: beyond 1024 of them per row there is no plan
+    huge = api.make_params(1, 8, 2, 4, 5000, (1 << 25) // 16)
+    assert api.select_plan(huge, 1)[1] > 1024
+    assert L.as_score_topk(C.c_void_p(1), C.byref(huge), C.byref(api.AsKvView(1, 1, 1, 1, 1)), C.c_void_p(1),
+                           C.c_void_p(1), C.c_void_p(1), None) == 2
+    assert api.select_plan(api.make_params(1, 8, 2, 4, 4096, (1 << 25) // 16), 1)[1] <= 1024
     # null layer array / bad pack sizes are rejected before anything touches the device
     assert L.as_select_step_pack(None, C.byref(small), None, 1, None) == 1
 
