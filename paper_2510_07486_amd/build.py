@@ -10,6 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasyncspade.so")
 OBJ = os.path.join(HERE, "_build")
+DEMO = os.path.join(HERE, "abi_demo")
 SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip",
            "cache_ops.hip"]
 
@@ -21,7 +22,7 @@ def _run(cmd, verbose):
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         sys.stderr.write(err + "\n")
-        raise RuntimeError("hipcc failed: " + " ".join(cmd))
+        raise RuntimeError("build step failed: " + " ".join(cmd))
     if verbose and err.strip():
         print(err)
 
@@ -39,6 +40,10 @@ def build(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
         list(ex.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize", "-o", LIB] + objs, verbose)
+    # a plain-C caller of the ABI: C99 host code through gcc, linked against the library and the HIP runtime
+    _run(["gcc", "-std=c99", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
+          "-I", "/opt/rocm/include", os.path.join(CSRC, "abi_demo.c"), "-o", DEMO, "-L", HERE, "-lasyncspade",
+          "-Wl,-rpath,$ORIGIN", "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"], verbose)
     return LIB
 
 

@@ -245,3 +245,15 @@ def test_decode_loop_append_attend_push_select():
         assert torch.equal(dev.ctx_lens.cpu(), cpu.ctx_lens)
     note("  decode loop: tie swaps over 6 selections:", swaps)
     assert torch.equal(dev.k_pool.cpu(), cpu.k_pool) and torch.equal(dev.q_win.cpu(), cpu.q_win)
+
+
+def test_plain_c_caller_of_the_abi():
+    """abi_demo (C99, gcc, HIP runtime for allocations) runs predict -> selection -> attention on a hand-checkable
+    case through the C ABI and verifies the results itself."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(api.LIB_PATH), "abi_demo")
+    assert os.path.exists(exe), "run the build first"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    note(" ", r.stdout.strip().replace("\n", " | "))
+    assert r.returncode == 0 and "abi_demo: OK" in r.stdout, r.stderr
