@@ -339,7 +339,17 @@ def main():
     dense_us = avg_us(lambda: api.as_dense_decode_attn(ctx_att, p, kvs[0], L0["qr"], out=out, want_lse=False), 5)
     sparse_us = avg_us(lambda: api.as_sparse_decode_attn(ctx_att, p, kvs[0], L0["qr"], sel_hat[0], sel_hat[1], out=out,
                                                          want_lse=False), 5)
+    standalone = {}
+    if a.agg != 2:   # the stand-alone stages: scores through HBM (as_score_keys), then as_topk_select
+        sc_buf = torch.empty((B, Hkv, stride), dtype=torch.float32, device=dev)
+        q_hat0 = api.as_predict_query(ctx_att, p, L0["qw"], L0["qc"])
+        t_sk = avg_us(lambda: api.as_score_keys(ctx_att, p, kvs[0], q_hat0, sc_buf), 5)
+        t_tk = avg_us(lambda: api.as_topk_select(ctx_att, p, sc_buf, ctx_lens, sel_cur[0], sel_cur[1]), 5)
+        standalone = {"as_score_keys_us": round(t_sk, 1), "as_topk_select_us": round(t_tk, 1),
+                      "as_score_keys_gbs": round(tokens * Hkv * 256 / (t_sk * 1e-6) / 1e9, 1)}
+        del sc_buf
     res["context"] = {
+        "standalone_stages": standalone,
         "overlap_ratio_predicted_vs_real_query": round(o_hat, 4),       # Sec. 3 Eq. 1, S(q_hat) vs S(q_{t+1})
         "overlap_ratio_current_vs_real_query": round(o_cur, 4),         # S(q_t) vs S(q_{t+1}): no prediction
         "dense_attn_us_per_layer": round(dense_us, 1), "sparse_attn_us_per_layer": round(sparse_us, 1),

@@ -22,19 +22,19 @@ __global__ __launch_bounds__(256) void score_mfma_direct(const uint16_t* __restr
                                                          const int32_t* __restrict__ ctx_lens,
                                                          const float* __restrict__ q_hat, float* __restrict__ scores,
                                                          int64_t stride, int Hq, int Hkv, int G, int agg,
-                                                         int max_pages, int32_t last_page) {
+                                                         int max_pages, int32_t last_page, int ppw) {
   const int b = blockIdx.z, j = blockIdx.y;
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
-  const int p0 = blockIdx.x * SC_TP;
+  const int p0 = blockIdx.x * (4 * ppw);
   if (p0 >= npages) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t = lane & 15, grp = lane >> 4;
-  const int pw = p0 + wave * SC_PPW;  // first page of this wave
+  const int pw = p0 + wave * ppw;  // first page of this wave
   if (pw >= npages) return;
 
   int32_t my_page = 0;
-  if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  if (lane < ppw && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
   my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
 
   bf16x8 aq[NSET][4];
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void score_mfma_direct(const uint16_t* __restr
 
   float* srow = scores + ((int64_t)b * Hkv + j) * stride;
 #pragma unroll 1
-  for (int qd = 0; qd < SC_PPW / 4; ++qd) {
+  for (int qd = 0; qd < ppw / 4; ++qd) {
     if (pw + qd * 4 >= npages) break;
     uint4 kb[4][4];
 #pragma unroll
@@ -85,20 +85,20 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
                                                       const int32_t* __restrict__ ctx_lens,
                                                       const float* __restrict__ q_hat, float* __restrict__ scores,
                                                       int64_t stride, int Hq, int Hkv, int G, int agg,
-                                                      int max_pages, int32_t last_page) {
+                                                      int max_pages, int32_t last_page, int ppw) {
   __shared__ uint4 stage[4][4 * 256];  // per wave: 4 page images of 4 KB
   const int b = blockIdx.z, j = blockIdx.y;
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
-  const int p0 = blockIdx.x * SC_TP;
+  const int p0 = blockIdx.x * (4 * ppw);
   if (p0 >= npages) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t = lane & 15, grp = lane >> 4;
-  const int pw = p0 + wave * SC_PPW;
+  const int pw = p0 + wave * ppw;
   if (pw >= npages) return;
 
   int32_t my_page = 0;
-  if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  if (lane < ppw && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
   my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
 
   bf16x8 aq[NSET][4];
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
   uint4* st = stage[wave];
   float* srow = scores + ((int64_t)b * Hkv + j) * stride;
 #pragma unroll 1
-  for (int qd = 0; qd < SC_PPW / 4; ++qd) {
+  for (int qd = 0; qd < ppw / 4; ++qd) {
     if (pw + qd * 4 >= npages) break;
     if (DMA) {
 #pragma unroll
@@ -158,7 +158,10 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
     }
     float outv = grp == 0 ? res[0] : grp == 1 ? res[1] : grp == 2 ? res[2] : res[3];
     const int n = (pw + qd * 4 + grp) * AS_PAGE + t;
-    if (n < N) srow[n] = outv + 0.0f;
+    if (n < N) {
+      if (NT) __builtin_nontemporal_store(outv + 0.0f, &srow[n]);   // written once, read by another kernel: streaming
+      else srow[n] = outv + 0.0f;
+    }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
   }
@@ -173,21 +176,21 @@ __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restr
                                                          const int32_t* __restrict__ block_table,
                                                          const int32_t* __restrict__ ctx_lens,
                                                          float* __restrict__ scores, int64_t stride, int Hkv,
-                                                         int max_pages, int32_t last_page) {
+                                                         int max_pages, int32_t last_page, int ppw) {
   const int b = blockIdx.z, j = blockIdx.y;
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int npages = (N + AS_PAGE - 1) / AS_PAGE;
-  const int p0 = blockIdx.x * SC_TP;
+  const int p0 = blockIdx.x * (4 * ppw);
   if (p0 >= npages) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int pw = p0 + wave * SC_PPW;
+  const int pw = p0 + wave * ppw;
   if (pw >= npages) return;
   int32_t my_page = 0;
-  if (lane < SC_PPW && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
+  if (lane < ppw && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
   my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
   float* srow = scores + ((int64_t)b * Hkv + j) * stride;
 #pragma unroll 1
-  for (int qd = 0; qd < SC_PPW / 4; ++qd) {
+  for (int qd = 0; qd < ppw / 4; ++qd) {
     if (pw + qd * 4 >= npages) break;
     uint4 kb[4][4];
 #pragma unroll
@@ -212,12 +215,18 @@ hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, c
   if (p->batch == 0 || p->max_pages_per_seq == 0) return hipSuccess;
   const int G = p->n_q_heads / p->n_kv_heads;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
-  dim3 grid((p->max_pages_per_seq + SC_TP - 1) / SC_TP, p->n_kv_heads, p->batch);
+  // pages per wavefront: as many as leave about eight workgroups per compute unit, so that the prologue (the
+  // query operand, the page ids) is spread over up to 2048 tokens per workgroup on large batches and small
+  // batches still fill the chip
+  int ppw = 32;
+  while (ppw > 8 && (int64_t)p->batch * p->n_kv_heads * ((p->max_pages_per_seq + 4 * ppw - 1) / (4 * ppw)) < 2048)
+    ppw /= 2;
+  dim3 grid((p->max_pages_per_seq + 4 * ppw - 1) / (4 * ppw), p->n_kv_heads, p->batch);
   const bool two = (p->agg != AS_AGG_SUM) && G > 8;
   const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
 #define AS_SCORE_LAUNCH(KERNEL)                                                                              \
   hipLaunchKernelGGL(KERNEL, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat, scores, stride, \
-                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, last_page)
+                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, last_page, ppw)
   const bool nt = variant >= 10;
   if (p->agg != AS_AGG_SUM && G > 16) {
     // MQA-sized groups: four or eight operand sets of eight heads each; only the product variant is instantiated
@@ -229,10 +238,10 @@ hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, c
     case 9:
       if (nt)
         hipLaunchKernelGGL(stream_read_paged<true>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page);
+                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
       else
         hipLaunchKernelGGL(stream_read_paged<false>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page);
+                           stride, p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
       break;
     case 1:
       if (two) { if (nt) AS_SCORE_LAUNCH((score_mfma_lds<2, false, true>)); else AS_SCORE_LAUNCH((score_mfma_lds<2, false, false>)); }

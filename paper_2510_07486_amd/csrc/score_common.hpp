@@ -8,8 +8,6 @@ namespace asx {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int SC_PPW = 8;            // pages per wave
-static constexpr int SC_TP = 4 * SC_PPW;    // pages per 256-thread block
 
 // Lane (t = lane & 15, grp = lane >> 4) of MFMA step m contracts the 8 dims of chunk
 // `cmap(grp, m)`; the same map is used for the Q rows and the K columns, so any
