@@ -1,5 +1,6 @@
-// Device helpers shared by the top-k kernels: order-preserving score keys and an exact
-// block-wide radix select with ordered emission (1024-thread workgroups).
+// Device helpers shared by the top-k kernels: order-preserving score keys, an exact block-wide
+// positional radix select with ordered emission, and exact marking of the best k among
+// register-held (key, token) pairs (radix thresholds on the key, then on the token).
 #pragma once
 #include "common.hpp"
 
@@ -195,6 +196,70 @@ __device__ __forceinline__ auto key4_from_scalar(int n, KeyFn key_of) {
       if (i4 + e < n) k[e] = key_of(i4 + e, v[e]);
     }
   };
+}
+
+// ---- exact selection over an unordered candidate buffer ----------------------------------------
+// Candidates are (key, token) pairs in arbitrary order.  Tokens are unique, so the pairs are totally
+// ordered by (key descending, token ascending) and "the best `keep`" is unique: every pair with
+// key > T, plus the r pairs with the lowest tokens among those with key == T.
+
+// Value of the want-th largest of the (up to NPT per thread) values held in registers, over the
+// whole workgroup: three histogram passes (B0 bits, then the rest in two halves).  Returns T;
+// `r` = how many values equal to T are still wanted, `ties` = how many values equal T.
+template <int THREADS, int B0, int NPT>
+__device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], const bool (&ok)[NPT], uint32_t want,
+                                                    uint32_t* hist, uint32_t* xch, uint32_t& r, uint32_t& ties) {
+  constexpr int B1 = (32 - B0 + 1) / 2, B2 = 32 - B0 - B1;
+  const int tid = threadIdx.x;
+  uint32_t* wave_tot = xch;
+  uint32_t* found = xch + 16 + 128;
+  uint32_t prefix = 0, mask = 0, remaining = want;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int width = pass == 0 ? B0 : pass == 1 ? B1 : B2;
+    const int sh = pass == 0 ? 32 - B0 : pass == 1 ? B2 : 0;
+    const int nb = 1 << width;
+    for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < NPT; ++e)
+      if (ok[e] && (val[e] & mask) == prefix) atomicAdd(&hist[(val[e] >> sh) & (nb - 1)], 1u);
+    __syncthreads();
+    find_bin<THREADS>(hist, nb, remaining, wave_tot, found);
+    prefix |= found[0] << sh;
+    mask |= (uint32_t)(nb - 1) << sh;
+    remaining -= found[1];
+    if (pass == 2) ties = hist[found[0]];
+  }
+  __syncthreads();   // hist and found may be reused by the caller
+  r = remaining;
+  return prefix;
+}
+
+// Marks, among this thread's NPT candidates, the ones that belong to the best `keep` of the `total`
+// candidates of the workgroup (keep < total).  Returns the key threshold T.
+template <int THREADS, int B0, int NPT>
+__device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const int32_t (&tok)[NPT],
+                                              const bool (&have)[NPT], int keep, uint32_t* hist, uint32_t* xch,
+                                              bool (&sel)[NPT]) {
+  uint32_t r, ties;
+  const uint32_t T = radix_threshold<THREADS, B0, NPT>(key, have, (uint32_t)keep, hist, xch, r, ties);
+  uint32_t I = 0;   // threshold on ~token among the pairs with key == T
+  if (r < ties) {   // uniform: not every tie fits, the lowest tokens win
+    uint32_t inv[NPT];
+    bool tie[NPT];
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) {
+      inv[e] = ~(uint32_t)tok[e];
+      tie[e] = have[e] && key[e] == T;
+    }
+    uint32_t r2, t2;
+    I = radix_threshold<THREADS, B0, NPT>(inv, tie, r, hist, xch, r2, t2);
+  }
+#pragma unroll
+  for (int e = 0; e < NPT; ++e)
+    sel[e] = have[e] && (key[e] > T || (key[e] == T && ~(uint32_t)tok[e] >= I));
+  return T;
 }
 
 }  // namespace asx
