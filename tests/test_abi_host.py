@@ -89,3 +89,36 @@ def test_header_is_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                         "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_share_plan_invariants_over_random_shapes():
+    """Host planner: whatever the shape, the shares cover the longest context, respect the kernel's limits
+    (share <= 32768 tokens; buffer-sized shares when the budget exceeds half the candidate buffer) and the workspace
+    holds every candidate array the plan implies."""
+    import random
+    rnd = random.Random(7)
+    for _ in range(300):
+        hkv = rnd.choice([1, 2, 4, 8])
+        g = rnd.choice([1, 2, 4, 8, 16, 24, 64])
+        batch = rnd.choice([1, 2, 3, 8, 32, 64, 200])
+        pages = rnd.choice([1, 7, 64, 256, 1024, 2048, 4096, 20000])
+        budget = rnd.choice([1, 16, 256, 2048, 4096, 5000, 65536])
+        layers = rnd.choice([1, 1, 2, 4, 16])
+        agg = rnd.choice([0, 1, 2])
+        p = api.make_params(batch, hkv * g, hkv, 16, budget, pages, agg=agg)
+        share, shares, cand = api.select_plan(p, layers)
+        max_ctx = pages * 16
+        wide = g > 16 and agg != 1                     # MQA-sized groups run the 512-thread shape
+        buf, cap = (4096, 16384) if wide else (8192, 32768)
+        assert share * shares >= max_ctx and (shares - 1) * share < max(max_ctx, 1) or shares == 1
+        assert 256 <= share <= cap and share % 64 == 0
+        if budget > buf // 2:
+            assert share <= buf
+        assert cand == min(budget, share)
+        if shares <= 1024:
+            need = layers * batch * hkv * g * 128 * 4
+            if shares > 1:
+                need += layers * batch * hkv * shares * (cand * 8 + 4)
+            if agg == 2:
+                need += layers * batch * hkv * g * shares * 8
+            assert api.as_workspace_bytes_pack(p, layers) >= need
