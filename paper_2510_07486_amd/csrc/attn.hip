@@ -36,10 +36,10 @@ static int g_attn_impl = 0;  // 0: matrix-core kernel (attn_mfma.hip), 1: vector
 // fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens.  One
 // extra split at the end takes whatever lies beyond list_len (the dense tail of a sparse call).
 struct attn_geom { int nsplit, split_tokens, nsel; };
-static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
+static attn_geom attn_geometry(const as_params* p, int64_t list_len, int impl) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (list_len < 1) list_len = 1;
-  int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (g_attn_impl == 0 ? (G + 15) / 16 : G / attn_gh(G));
+  int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (impl == 0 ? (G + 15) / 16 : G / attn_gh(G));
   if (pairs < 1) pairs = 1;
   int64_t nsel = (1536 + pairs - 1) / pairs;
   const int64_t max_sel = (list_len + AT_SPLIT - 1) / AT_SPLIT;
@@ -60,13 +60,10 @@ static attn_geom attn_geometry(const as_params* p, int64_t list_len) {
 size_t attn_workspace_bytes(const as_params* p) {
   const size_t heads = (size_t)p->batch * p->n_q_heads;
   size_t ns = (size_t)attn_nsplit(p->budget);
-  const int keep = g_attn_impl;
   for (int impl = 0; impl < 2; ++impl) {
-    g_attn_impl = impl;
-    const size_t nd = (size_t)attn_geometry(p, (int64_t)p->max_pages_per_seq * AS_PAGE).nsplit;
+    const size_t nd = (size_t)attn_geometry(p, (int64_t)p->max_pages_per_seq * AS_PAGE, impl).nsplit;
     if (nd > ns) ns = nd;
   }
-  g_attn_impl = keep;
   return heads * ns * (AS_HEAD_DIM + 2) * sizeof(float);
 }
 
@@ -352,23 +349,25 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   const int G = p->n_q_heads / p->n_kv_heads;
   const bool dense = sel_idx == nullptr;
   const int64_t list_len = dense ? (int64_t)p->max_pages_per_seq * AS_PAGE : (int64_t)p->budget;
-  const attn_geom gm = attn_geometry(p, list_len);
+  const int impl = g_attn_impl;
+  const attn_geom gm = attn_geometry(p, list_len, impl);
   // The matrix-core kernel cuts the list into equal splits (no separate tail split); the vector-ALU
   // kernel walks whole 64-token chunks and keeps one extra split for the tail.
-  const int nsplit = g_attn_impl == 0 ? gm.nsel : gm.nsplit;
+  const int nsplit = impl == 0 ? gm.nsel : gm.nsplit;
   const int split_tokens = gm.split_tokens;
   const int cps = split_tokens / AT_CHUNK;
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
   hipError_t e;
-  if (g_attn_impl == 0)
+  if (impl == 0) {
     e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, (int)list_len, s);
-  else
-  switch (attn_gh(G)) {
-    case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
-    case 4: e = launch_attn_gh<4>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
-    case 2: e = launch_attn_gh<2>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
-    default: e = launch_attn_gh<1>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+  } else {
+    switch (attn_gh(G)) {
+      case 8: e = launch_attn_gh<8>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+      case 4: e = launch_attn_gh<4>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+      case 2: e = launch_attn_gh<2>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+      default: e = launch_attn_gh<1>(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, cps, s); break;
+    }
   }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)heads), dim3(AS_HEAD_DIM), 0, s, part_o, part_ml, out, lse,
