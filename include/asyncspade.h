@@ -27,9 +27,10 @@
  *     validated on the host before any launch: AS_ERR_INVALID_ARG for null pointers,
  *     non-positive sizes, n_q_heads % n_kv_heads != 0, ridge_eps <= 0;
  *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 64,
- *     budget > 65536, and for the fused selection calls when budget > 4096 is combined with a block
- *     table of more than 8 million tokens per sequence; AS_ERR_WORKSPACE if the ctx workspace is too
- *     small for the call.
+ *     budget > 65536, and for as_select_step_pack and the softmax-normalised aggregation when
+ *     budget > 4096 is combined with a block table of more than 8 million tokens per sequence
+ *     (as_score_topk and as_select_step then run the stand-alone stages);
+ *     AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
  *     Contents of device arrays (page ids in range, indices unique and in range) are
  *     the caller's contract; as a guard against faults, page ids are clamped into
  *     [0, num_pages) and token indices into [0, ctx_lens[b]) before they are used, so a
@@ -98,7 +99,9 @@ typedef struct {            /* caller-owned device memory, never freed by the li
  * (as_select_step's q_hat + score rows, and the attention split partials). */
 size_t as_workspace_bytes(const as_params* p);
 
-/* Creates a ctx on `device` with a workspace of `workspace_bytes` (hipMalloc).  */
+/* Creates a ctx on `device` with a workspace of `workspace_bytes` (hipMalloc).  as_destroy frees it
+ * (hipFree): like any allocation call, neither belongs inside an open stream capture, and work that
+ * still uses the workspace must have finished.  Every other call only enqueues kernels. */
 as_status as_create(as_ctx** out, int device, size_t workspace_bytes);
 as_status as_destroy(as_ctx* ctx);
 const char* as_status_str(as_status s);
@@ -161,7 +164,11 @@ as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view
  * Scoring and top-k in one pass (Alg. 1 step 7 + Sec. 4.3 item (2)): same result as
  * as_score_keys followed by as_topk_select, but the per-token scores never leave the chip
  * (rows are scored in slices whose keys stay in LDS; only per-slice candidates, 8 B each,
- * go through the ctx workspace).  This is the kernel pair as_select_step runs.
+ * go through the ctx workspace).  This is the kernel pair as_select_step runs.  One exception,
+ * chosen on the host from the shapes: when the rows are so few that they are cut into slices
+ * no longer than the budget (batch 1, short context), no slice could discard anything and the
+ * call runs the two stand-alone kernels over score rows in the ctx workspace instead; the
+ * result is the same.
  */
 as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
                         int32_t* sel_idx, int32_t* sel_cnt, void* stream);

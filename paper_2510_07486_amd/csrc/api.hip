@@ -55,6 +55,24 @@ as_status check_kv(const as_kv_view* kv, bool need_v) {
 
 inline as_status hip_status(hipError_t e) { return e == hipSuccess ? AS_OK : AS_ERR_HIP; }
 
+// Whether a single-layer selection runs as the two stand-alone stages (scores through the workspace) instead of
+// the fused kernels: when the fused kernels have no share plan for the shape, when the plan could not prune
+// anything, or when the development knob says so.  The softmax-normalised aggregation exists only in the fused
+// kernels.
+bool use_stages(const as_ctx* ctx, const as_params* p) {
+  if (p->agg == AS_AGG_SOFTMAX_SUM) return false;
+  if (!asx::select_plan_ok(p, 1)) return true;      // more shares per row than the merge kernel indexes
+  if (ctx->select_mode == 2) return false;
+  return ctx->select_mode == 1 || asx::select_prefers_stages(p);
+}
+
+hipError_t score_then_topk(const as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
+                           float* scores, int64_t stride, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+  const hipError_t e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, stride, s);
+  if (e != hipSuccess) return e;
+  return asx::launch_topk(p, scores, stride, kv->ctx_lens, sel_idx, sel_cnt, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -170,11 +188,15 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
-  if (!asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
+  if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
+  const bool stages = use_stages(ctx, p);
   const ws_layout l = layout_of(p);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
-  return hip_status(asx::launch_select_fused(p, kv, q_hat, static_cast<char*>(ctx->ws) + l.cand, sel_idx, sel_cnt,
-                                             static_cast<hipStream_t>(stream)));
+  char* ws = static_cast<char*>(ctx->ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(ctx, p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
+                                    sel_idx, sel_cnt, s));
 }
 
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
@@ -183,22 +205,19 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
-  if (ctx->select_mode == 0 && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
+  if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
+  const bool stages = use_stages(ctx, p);
   const ws_layout l = layout_of(p);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   float* q_hat = reinterpret_cast<float*>(ws + l.q_hat);
-  float* scores = reinterpret_cast<float*>(ws + l.scores);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
                                      q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
-  if (ctx->select_mode == 0 || p->agg == AS_AGG_SOFTMAX_SUM)
-    return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
-  e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, l.score_stride, s);
-  if (e != hipSuccess) return AS_ERR_HIP;
-  e = asx::launch_topk(p, scores, l.score_stride, kv->ctx_lens, sel_idx, sel_cnt, s);
-  return hip_status(e);
+  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(ctx, p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
+                                    sel_idx, sel_cnt, s));
 }
 
 size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers) {
@@ -285,7 +304,8 @@ as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a
 }
 
 // Development knobs (not part of the documented ABI): pick the key-scoring kernel variant of
-// as_score_keys, and whether as_select_step fuses scoring with top-k (0) or not (1).
+// as_score_keys, and whether single-layer selections fuse scoring with top-k (0: by the share plan, 1: never,
+// 2: always).
 as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
   if (!ctx) return AS_ERR_INVALID_ARG;
   ctx->score_variant = variant;

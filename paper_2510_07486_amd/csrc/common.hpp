@@ -18,7 +18,8 @@ struct as_ctx {
   void* ws;
   size_t ws_bytes;
   int score_variant; /* which key-scoring kernel as_score_keys launches */
-  int select_mode;   /* 0: fused score+top-k in as_select_step, 1: separate kernels via HBM scores */
+  int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
+                        1: always the separate kernels via HBM scores, 2: always fused */
 };
 
 namespace asx {
@@ -77,6 +78,7 @@ hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, 
 struct select_plan { int slice_len, nslices, ccap; };
 select_plan plan_select(const as_params* p, int n_layers);
 bool select_plan_ok(const as_params* p, int n_layers);
+bool select_prefers_stages(const as_params* p);
 size_t select_workspace_bytes(const as_params* p, int n_layers);
 hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s);
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,

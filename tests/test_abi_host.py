@@ -72,8 +72,13 @@ def test_pack_workspace_and_share_plan():
     # a budget above half the candidate buffer forces buffer-sized shares: beyond 1024 of them per row there is no plan
     huge = api.make_params(1, 8, 2, 4, 5000, (1 << 25) // 16)
     assert api.select_plan(huge, 1)[1] > 1024
-    assert L.as_score_topk(C.c_void_p(1), C.byref(huge), C.byref(api.AsKvView(1, 1, 1, 1, 1)), C.c_void_p(1),
+    # (single-layer calls then run the stand-alone stages; the softmax-normalised aggregation and packs, which
+    # exist only in the fused kernels, are refused before anything touches the context or the device)
+    huge_sm = api.make_params(1, 8, 2, 4, 5000, (1 << 25) // 16, agg=api.AS_AGG_SOFTMAX_SUM)
+    assert L.as_score_topk(C.c_void_p(1), C.byref(huge_sm), C.byref(api.AsKvView(1, 1, 1, 1, 1)), C.c_void_p(1),
                            C.c_void_p(1), C.c_void_p(1), None) == 2
+    fake = api.AsLayerIo(api.AsKvView(1, 1, 1, 1, 1), 1, 1, 1, 1)
+    assert L.as_select_step_pack(C.c_void_p(1), C.byref(huge), (api.AsLayerIo * 2)(fake, fake), 2, None) == 2
     assert api.select_plan(api.make_params(1, 8, 2, 4, 4096, (1 << 25) // 16), 1)[1] <= 1024
     # null layer array / bad pack sizes are rejected before anything touches the device
     assert L.as_select_step_pack(None, C.byref(small), None, 1, None) == 1

@@ -89,6 +89,32 @@ def test_million_token_context_and_largest_budget():
         assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
 
 
+def test_block_table_too_wide_for_a_share_plan_runs_the_stages():
+    """A budget above the pruning limit needs buffer-sized shares; a block table of 2^25 tokens per sequence would
+    need more of them than the merge kernel indexes.  The single-layer calls then score into the workspace and run
+    the stand-alone top-k; packs are refused.  The cached context is short, only the table is wide."""
+    budget, n_tok, max_pages = 5000, 50_001, (1 << 25) // 16
+    w = wl.Workload("wide", 1, 8, 2, 8, budget, n_tok, page_table="permute", seed=77)
+    cpu = wl.make_inputs(w)
+    bt = torch.zeros((1, max_pages), dtype=torch.int32)
+    bt[:, :cpu.max_pages] = cpu.block_table
+    eps = f32(1e-2)
+    p = api.make_params(1, 8, 2, 8, budget, max_pages, ridge_eps=eps, sm_scale=f32(SCALE))
+    assert api.select_plan(p, 1)[1] > 1024
+    ctx = api.Context(p)
+    kv = api.kv_view(cpu.k_pool.cuda(), cpu.v_pool.cuda(), bt.cuda(), cpu.ctx_lens.cuda())
+    print("wide-table", n_tok, budget, "workspace MiB", api.as_workspace_bytes(p) >> 20, flush=True)
+    gidx, gcnt = api.as_select_step(ctx, p, kv, cpu.q_win.cuda(), cpu.q_cur.cuda())
+    torch.cuda.synchronize()
+    rq, rs, ridx, rcnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur, budget, eps)
+    swaps = compare_selection(gidx, gcnt, ridx, rcnt, rs, cpu.ctx_lens, budget)
+    print(f"  tie swaps {swaps}", flush=True)
+    with pytest.raises(api.AsError) as e:
+        api.as_select_step_pack(api.Context(api.make_params(1, 8, 2, 8, 64, 16), pack=2), p,
+                                [api.layer_io(kv, cpu.q_win.cuda(), cpu.q_cur.cuda(), gidx, gcnt)] * 2)
+    assert e.value.code == 2
+
+
 def test_full_size_packed_selection_two_layers():
     """BASELINE configs[2] at full size, two layers in one as_select_step_pack call (512 rows of 32768 tokens in one
     grid): every row equals the single-layer call bit for bit, and one sampled sequence per layer equals the oracle."""

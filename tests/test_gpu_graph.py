@@ -1,6 +1,8 @@
 """The library's calls neither allocate nor synchronise, so a whole decode step can be captured into a HIP
 graph and replayed.  Replays are checked against eager execution bit for bit, several times, with eager work and
 host synchronisation between the replays and with the inputs changed in place (the graph holds pointers, not data)."""
+import gc
+
 import pytest
 import torch
 
@@ -58,6 +60,7 @@ def test_graph_replay_of_a_decode_step_equals_eager(packed):
         return [s[0].clone() for s in sel], [o.clone() for o in outs]
 
     eager()                                           # warm-up: function attributes, lazy module loading
+    gc.collect()                                      # a context collected during the capture would hipFree: not capturable
     s = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
     s.wait_stream(torch.cuda.current_stream())
@@ -107,6 +110,7 @@ def test_graph_with_selection_on_a_forked_stream():
         return [t[0].clone() for t in nxt], [o.clone() for o in outs]
 
     ref_nxt, ref_out = serial()
+    gc.collect()
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
     main.wait_stream(torch.cuda.current_stream())

@@ -231,24 +231,30 @@ def end_to_end(w, eps=1e-2, beta=1.0, agg=0, streams=False, single_solve=False):
 
 
 def fused_vs_separate(w):
-    """as_select_step's fused scoring + top-k against the separate kernels: identical index sets."""
+    """as_select_step's fused scoring + top-k against the separate kernels: identical index sets, whichever of the
+    two the library would pick for the shape by itself."""
     cpu = wl.make_inputs(w)
     dev = to_dev(cpu)
     p = params_for(cpu)
     ctx = api.Context(p)
     kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
-    a_idx, a_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
-    ctx.set_select_mode(1)
+    a_idx, a_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)       # the library's own choice
+    ctx.set_select_mode(1)                                                    # always the stand-alone stages
     b_idx, b_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
-    assert torch.equal(a_cnt, b_cnt)
-    assert torch.equal(a_idx, b_idx)
+    ctx.set_select_mode(2)                                                    # always the fused kernels
+    f_idx, f_cnt = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    assert torch.equal(a_cnt, b_cnt) and torch.equal(a_cnt, f_cnt)
+    assert torch.equal(a_idx, b_idx) and torch.equal(a_idx, f_idx)
     # stage-isolated: the fused kernel fed the oracle's q_hat reproduces the oracle's selection of its own scores
     q_hat = oracle.predict_query(cpu.q_win, cpu.q_cur, f32(1e-2))
     sc = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q_hat, w.n_kv_heads)
     ridx, rcnt = oracle.topk_select(sc, cpu.ctx_lens, w.budget)
     c_idx, c_cnt = api.as_score_topk(ctx, p, kv, q_hat.cuda())
     swaps = compare_selection(c_idx, c_cnt, ridx, rcnt, sc, cpu.ctx_lens, w.budget)
-    note("  tie swaps vs oracle:", swaps)
+    ctx.set_select_mode(0)
+    d_idx, d_cnt = api.as_score_topk(ctx, p, kv, q_hat.cuda())
+    assert torch.equal(c_idx, d_idx) and torch.equal(c_cnt, d_cnt)
+    note("  tie swaps vs oracle:", swaps, " share plan", api.select_plan(p, 1))
 
 
 @pytest.mark.parametrize("kw", [
@@ -260,6 +266,10 @@ def fused_vs_separate(w):
     dict(batch=5, n_q_heads=32, n_kv_heads=1, ctx=9000, ctx_min=3000, budget=512),   # MQA, 32 heads on one KV head
     dict(batch=3, n_q_heads=128, n_kv_heads=2, ctx=6000, ctx_min=500, budget=300),   # groups of 64
     dict(batch=2, n_q_heads=48, n_kv_heads=2, ctx=2000, ctx_min=900, budget=100),    # group of 24 (not a power of two)
+    dict(batch=1, n_q_heads=8, n_kv_heads=2, ctx=4096, budget=256),      # few rows: shares no longer than the budget,
+    dict(batch=1, n_q_heads=32, n_kv_heads=8, ctx=16384, budget=2048),   # which the library runs as separate stages
+    dict(batch=1, n_q_heads=8, n_kv_heads=2, ctx=40000, budget=9000),    # budget above the pruning limit: buffer-sized
+                                                                         # shares, merge over global candidates
 ])
 def test_fused_select_equals_separate_kernels(kw):
     note("fused-vs-separate", kw)
