@@ -2,13 +2,13 @@
 // over window sizes; Appendix C Alg. 1 steps 1-6).
 //
 // One wavefront per (sequence, query head).  The window is reordered newest-first so that
-// window size k is the LEADING k x k block of one W x W Gram matrix: a single fp64 Cholesky
-// factorisation L and a single forward solve y = L^-1 b then serve every k (both are
-// prefix-consistent), and lane k-1 finishes its own size-k back-substitution, softmax and
-// weight row independently.  Everything W x W is fp64 in LDS; the result is
+// window size k is the LEADING k x k block of one W x W Gram matrix: a single fp64
+// factorisation (Cholesky in the general kernel, L D L^T in the fixed-window one) and a single
+// forward solve then serve every k (both are prefix-consistent), and lane k-1 finishes its own
+// size-k back-substitution, softmax and weight row independently.  Everything W x W is fp64; the
+// result is
 //   q_hat = sum_i a_i S_i,  a_i = (1/W) sum_{k>=i} w^{(k)}_i,  S = (Q_t, Q_{t-1}, ..., Q_{t-W+1}).
-// ALU-bound and tiny (about 50 kflop per head at W = 16); it exists to keep the chain on
-// the device, not to be fast.
+// Latency-bound and tiny (about 50 kflop per head at W = 16): one dependent chain per head.
 #include "common.hpp"
 
 namespace asx {
@@ -134,22 +134,31 @@ __global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int hea
   }
 }
 
-// Window sizes known at compile time (the paper profiles W = 16): the same algorithm with the
-// Cholesky row, the forward-solve residual and the back-substituted weights of a lane held in
-// registers, all LDS operands at static addresses (broadcast reads the compiler can pipeline),
-// divisions replaced by one reciprocal per diagonal element, and the W(W+1)/2 softmax
-// exponentials spread over the 64 lanes instead of W sequential ones per lane.
+// Window sizes known at compile time (the paper profiles W = 16), W <= 16.  Same algorithm, laid out for one
+// wavefront:
+//  * the Gram matrix of the W predecessors is one chain of 32 fp64 matrix-core instructions
+//    (v_mfma_f64_16x16x4: G += X_s X_s^T over 32 slices of four dims; lane l supplies X[l % 16][4s + l / 16] as
+//    both operands); the result lands with lane (r = l % 16, q = l / 16) holding G[r][q + 4v], v = 0..3, i.e.
+//    every row spread over four lanes, which is the distribution the factorisation below works in;
+//  * G + eps I = L D L^T (unit lower L, no square roots) by right-looking elimination on the full symmetric
+//    trailing block: per step one reciprocal, the pivot row and column fetched with cross-lane reads, at most four
+//    multiply-adds per lane.  The right-hand side b rides along, so z = L^-1 b and y = D^-1 z come out of the
+//    same loop.  Leading blocks of L and D factor the leading blocks of G: one factorisation serves every window size;
+//  * lane k-1 then back-substitutes L_k^T omega = y_{1:k} on its own, the W(W+1)/2 softmax exponentials are
+//    spread over the 64 lanes.
 template <int W>
 __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int heads_per_layer, double eps,
                                                        double beta, int single) {
-  __shared__ float Rf[(W + 1) * RS];   // row i < W = Q_{t-1-i}, row W = Q_t
-  __shared__ double A[W][W + 1];       // Gram, then the Cholesky factor L
+  static_assert(W >= 1 && W <= 16, "one 16 x 16 matrix-core tile holds the Gram matrix");
+  typedef double f64x4 __attribute__((ext_vector_type(4)));
+  constexpr int RW = AS_HEAD_DIM + 4;  // row stride of the staged window: lanes (r, q) read banks 4r + q
+  __shared__ float Rf[(W + 1) * RW];   // row i < W = Q_{t-1-i}, row W = Q_t
+  __shared__ double Ls[W][W + 1];      // L below the diagonal
   __shared__ double Om[W][W + 1];      // row k-1: beta*omega^{(k)} - max, then exp of it
-  __shared__ double colb[W], diag[W];  // broadcast of the current Cholesky column and pivot
-  __shared__ double bv[W], yv[W], invd[W], zinv[W], av[W];
+  __shared__ double yv[W], zinv[W], av[W];
 
   const int lane = threadIdx.x;
-  const int r = lane;
+  const int r = lane & 15, q = lane >> 4;
   const int layer = blockIdx.x / heads_per_layer;
   const int64_t bh = blockIdx.x - layer * heads_per_layer;
   float* __restrict__ q_hat = tab.q_hat[layer];
@@ -158,88 +167,63 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int h
 #pragma unroll
   for (int i = 0; i < W; ++i) {
     const uint32_t w2 = win[(int64_t)(W - 1 - i) * (AS_HEAD_DIM / 2) + lane];
-    Rf[i * RS + 2 * lane] = bf16lo(w2);
-    Rf[i * RS + 2 * lane + 1] = bf16hi(w2);
+    Rf[i * RW + 2 * lane] = bf16lo(w2);
+    Rf[i * RW + 2 * lane + 1] = bf16hi(w2);
   }
   {
     const uint32_t w2 = cur[lane];
-    Rf[W * RS + 2 * lane] = bf16lo(w2);
-    Rf[W * RS + 2 * lane + 1] = bf16hi(w2);
+    Rf[W * RW + 2 * lane] = bf16lo(w2);
+    Rf[W * RW + 2 * lane + 1] = bf16hi(w2);
   }
   __syncthreads();
 
-  // Gram matrix (+ eps on the diagonal) and rhs, one (i, j) pair per lane and round
-  constexpr int NPAIRS = (W + 1) * (W + 2) / 2;
-  for (int p = lane; p < NPAIRS; p += 64) {
-    int i = (int)((sqrtf(8.0f * (float)p + 1.0f) - 1.0f) * 0.5f);
-    while (i * (i + 1) / 2 > p) --i;
-    while ((i + 1) * (i + 2) / 2 <= p) ++i;
-    const int j = p - i * (i + 1) / 2;
-    const float* ri = Rf + i * RS;
-    const float* rj = Rf + j * RS;
-    double s0 = 0.0, s1 = 0.0;
+  // Gram matrix on the matrix cores; the rhs b_r = <Q_{t-1-r}, Q_t> from the same operand values
+  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+  double b = 0.0;
+  {
+    const float* xr = Rf + (r < W ? r : 0) * RW + q;
+    const float* tr = Rf + W * RW + q;
 #pragma unroll 8
-    for (int d = 0; d < AS_HEAD_DIM; d += 2) {
-      s0 += (double)ri[d] * (double)rj[d];
-      s1 += (double)ri[d + 1] * (double)rj[d + 1];
+    for (int s4 = 0; s4 < AS_HEAD_DIM; s4 += 4) {
+      const double x = r < W ? (double)xr[s4] : 0.0;
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, x, acc, 0, 0, 0);
+      b += x * (double)tr[s4];
     }
-    const double s = s0 + s1;
-    if (i < W) A[i][j] = s + (i == j ? eps : 0.0);
-    else if (j < W) bv[j] = s;
+    b += __shfl_xor(b, 16);
+    b += __shfl_xor(b, 32);
   }
-  __syncthreads();
-
-  // Cholesky with row r in registers; column j is broadcast through LDS
-  double a[W];
+  double a[4];   // a[v] = (G + eps I)[r][q + 4v]
 #pragma unroll
-  for (int k = 0; k < W; ++k) a[k] = (r < W && k <= r) ? A[r][k] : 0.0;
+  for (int v = 0; v < 4; ++v) a[v] = acc[v] + (q + 4 * v == r ? eps : 0.0);
+
+  // L D L^T with the rhs carried along
+  auto from_lane = [](double x, int src) -> double {   // src uniform
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src);
+    return __hiloint2double(hi, lo);
+  };
 #pragma unroll
   for (int j = 0; j < W; ++j) {
-    if (r == j) diag[j] = a[j];                 // final by now: all earlier columns are folded in
-    __syncthreads();
-    const double djj = sqrt(diag[j]);
-    const double lij = a[j] / djj;              // meaningful for r > j
-    if (r == j) a[j] = djj;
-    if (r > j && r < W) {
-      a[j] = lij;
-      colb[r] = lij;
-    }
-    __syncthreads();
+    const int jq = j & 3, jv = j >> 2;                       // column j sits in lanes q = jq, register jv
+    const double inv = 1.0 / from_lane(a[jv], j + 16 * jq);  // pivot D_j
+    const double zj = from_lane(b, j);
+    const double cr = __shfl(a[jv], r + 16 * jq);            // (G)[r][j] after the earlier steps
+    const double lr = r > j ? cr * inv : 0.0;                // L[r][j]
 #pragma unroll
-    for (int k = j + 1; k < W; ++k)
-      if (k <= r && r < W) a[k] -= lij * colb[k];
-    // colb is next written after the first barrier of step j+1, which every lane passes only
-    // after these reads
-  }
-  __syncthreads();
-  if (r < W) {
-#pragma unroll
-    for (int k = 0; k < W; ++k)
-      if (k <= r) A[r][k] = a[k];
-    double dd = 1.0;
-#pragma unroll
-    for (int k = 0; k < W; ++k)
-      if (k == r) dd = a[k];
-    invd[r] = 1.0 / dd;
-  }
-  __syncthreads();
-
-  // forward solve y = L^-1 b
-  {
-    double rr = (r < W) ? bv[r] : 0.0;
-    double y = 0.0;
-#pragma unroll
-    for (int j = 0; j < W; ++j) {
-      const double yj = __shfl(rr, j) * invd[j];
-      if (r == j) y = yj;
-      if (r > j) rr -= a[j] * yj;
-    }
-    if (r < W) yv[r] = y;
+    for (int v = 0; v < 4; ++v)
+      if (4 * v + 3 > j) {                                   // some lane's column q + 4v lies right of j
+        const double rj = __shfl(a[v], j + 16 * q);          // row j, this lane's column
+        if (q + 4 * v > j) a[v] -= lr * rj;
+      }
+    b -= lr * zj;
+    if (q == 0 && r > j && r < W) Ls[r][j] = lr;
+    if (lane == 0) yv[j] = zj * inv;
   }
   __syncthreads();
 
   // lane kk: L_k^T omega = y_{1:k} for k = kk+1, weights stay zero above kk (single-solve mode: every lane
   // solves the full system; only its kk+1 newest entries enter the softmax below)
+  const int kk = lane;
   double om[W];
 #pragma unroll
   for (int i = 0; i < W; ++i) om[i] = 0.0;
@@ -247,16 +231,16 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int h
   for (int i = W - 1; i >= 0; --i) {
     double s = yv[i];
 #pragma unroll
-    for (int m = i + 1; m < W; ++m) s -= A[m][i] * om[m];
-    om[i] = (single || i <= r) ? s * invd[i] : 0.0;
+    for (int m = i + 1; m < W; ++m) s -= Ls[m][i] * om[m];
+    om[i] = (single || i <= kk) ? s : 0.0;
   }
-  if (r < W) {
+  if (kk < W) {
     double mx = beta * om[0];
 #pragma unroll
     for (int i = 1; i < W; ++i)
-      if (i <= r) mx = fmax(mx, beta * om[i]);
+      if (i <= kk) mx = fmax(mx, beta * om[i]);
 #pragma unroll
-    for (int i = 0; i < W; ++i) Om[r][i] = beta * om[i] - mx;
+    for (int i = 0; i < W; ++i) Om[kk][i] = beta * om[i] - mx;
   }
   __syncthreads();
   // exponentials of the W(W+1)/2 (k, i) pairs, spread over the lanes
@@ -268,27 +252,27 @@ __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int h
     Om[k][i] = exp(Om[k][i]);
   }
   __syncthreads();
-  if (r < W) {
+  if (kk < W) {
     double z = 0.0;
 #pragma unroll
     for (int i = 0; i < W; ++i)
-      if (i <= r) z += Om[r][i];
-    zinv[r] = 1.0 / z;
+      if (i <= kk) z += Om[kk][i];
+    zinv[kk] = 1.0 / z;
   }
   __syncthreads();
-  if (r < W) {
-    double acc = 0.0;
+  if (kk < W) {
+    double sum = 0.0;
 #pragma unroll
-    for (int kk = 0; kk < W; ++kk)
-      if (kk >= r) acc += Om[kk][r] * zinv[kk];
-    av[r] = acc / (double)W;
+    for (int k2 = 0; k2 < W; ++k2)
+      if (k2 >= kk) sum += Om[k2][kk] * zinv[k2];
+    av[kk] = sum / (double)W;
   }
   __syncthreads();
   for (int d = lane; d < AS_HEAD_DIM; d += 64) {
-    double acc = av[0] * (double)Rf[W * RS + d];
+    double o = av[0] * (double)Rf[W * RW + d];
 #pragma unroll
-    for (int i = 1; i < W; ++i) acc += av[i] * (double)Rf[(i - 1) * RS + d];
-    q_hat[bh * AS_HEAD_DIM + d] = (float)acc;
+    for (int i = 1; i < W; ++i) o += av[i] * (double)Rf[(i - 1) * RW + d];
+    q_hat[bh * AS_HEAD_DIM + d] = (float)o;
   }
 }
 
@@ -299,15 +283,18 @@ hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab&
   if (heads > 0x7fffffff) return hipErrorInvalidValue;
   const int hpl = (int)per_layer;
   const int single = p->predictor == AS_PRED_SINGLE_SOLVE ? 1 : 0;
-  if (p->window == 16 || p->window == 8) {
-    if (p->window == 16)
-      hipLaunchKernelGGL(predict_kernel_w<16>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
-                         (double)p->ridge_eps, (double)p->softmax_beta, single);
-    else
-      hipLaunchKernelGGL(predict_kernel_w<8>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,
-                         (double)p->ridge_eps, (double)p->softmax_beta, single);
+#define AS_PREDICT_W(W_)                                                                                  \
+  case W_:                                                                                               \
+    hipLaunchKernelGGL(predict_kernel_w<W_>, dim3((unsigned)heads), dim3(64), 0, s, tab, hpl,            \
+                       (double)p->ridge_eps, (double)p->softmax_beta, single);                           \
     return hipGetLastError();
+  switch (p->window) {   // windows of up to 16 queries: the Gram matrix fits one matrix-core tile
+    AS_PREDICT_W(1) AS_PREDICT_W(2) AS_PREDICT_W(3) AS_PREDICT_W(4) AS_PREDICT_W(5) AS_PREDICT_W(6)
+    AS_PREDICT_W(7) AS_PREDICT_W(8) AS_PREDICT_W(9) AS_PREDICT_W(10) AS_PREDICT_W(11) AS_PREDICT_W(12)
+    AS_PREDICT_W(13) AS_PREDICT_W(14) AS_PREDICT_W(15) AS_PREDICT_W(16)
+    default: break;
   }
+#undef AS_PREDICT_W
   size_t lds = predict_lds_bytes(p->window);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(predict_kernel),
