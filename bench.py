@@ -41,7 +41,6 @@ def parse():
     ap.add_argument("--agg", type=int, default=0, help="group aggregation: 0 max (default), 1 sum, 2 softmax-normalised sum "
                     "(two passes over K: the scoring roofline then counts the K bytes twice)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time to spend on the oracle baseline")
-    ap.add_argument("--score-variant", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=4)
     ap.add_argument("--serial-only", action="store_true")
@@ -118,9 +117,6 @@ def main():
     pack = max(1, min(a.pack, api.AS_MAX_PACK, n_layers))
     ctx_sels = [api.Context(p, pack=pack) for _ in range(n_sel)]
     ctx_att = api.Context(p)
-    if a.score_variant >= 0:
-        for c in ctx_sels:
-            c.set_score_variant(a.score_variant)
     kvs = [api.kv_view(L["k"], L["v"], bt, ctx_lens) for L in layers]
     B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
     stride = bt.shape[1] * wl.PAGE
@@ -359,6 +355,20 @@ def main():
         t_tk = avg_us(lambda: api.as_topk_select(ctx_att, p, sc_buf, ctx_lens, sel_cur[0], sel_cur[1]), 5)
         standalone = {"as_score_keys_us": round(t_sk, 1), "as_topk_select_us": round(t_tk, 1),
                       "as_score_keys_gbs": round(tokens * Hkv * 256 / (t_sk * 1e-6) / 1e9, 1)}
+        # what this access pattern can reach at all: the calibration kernel walks the same pages with the same
+        # coalesced loads and does nothing else (one word written per wavefront), rotating over the resident layers
+        ctx_att.set_score_variant(2)
+        rot = [0]
+
+        def stream_only():
+            api.as_score_keys(ctx_att, p, kvs[rot[0] % resident], q_hat0, sc_buf)
+            rot[0] += 1
+
+        t_rd = avg_us(stream_only, max(5, min(resident, 12)))
+        ctx_att.set_score_variant(0)
+        ceiling = tokens * Hkv * 256 / (t_rd * 1e-6) / 1e9
+        res["streaming_read_ceiling_gbs"] = round(ceiling, 1)
+        res["score_keys_pct_of_streaming_ceiling"] = round(100 * achieved / ceiling, 1) if a.agg != 2 else None
         del sc_buf
     res["context"] = {
         "standalone_stages": standalone,

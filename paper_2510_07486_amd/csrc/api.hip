@@ -93,7 +93,7 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->device = device;
   c->ws = nullptr;
   c->ws_bytes = workspace_bytes;
-  c->score_variant = 12;
+  c->score_variant = 0;
   c->select_mode = 0;
   if (workspace_bytes > 0) {
     if (hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
@@ -303,9 +303,9 @@ as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a
                                         static_cast<hipStream_t>(stream)));
 }
 
-// Development knobs (not part of the documented ABI): pick the key-scoring kernel variant of
-// as_score_keys, and whether single-layer selections fuse scoring with top-k (0: by the share plan, 1: never,
-// 2: always).
+// Development knobs (not part of the documented ABI): what as_score_keys launches (0: the scoring kernel,
+// 1 / 2: the streaming-read calibration kernel with / without one word written per token), and whether
+// single-layer selections fuse scoring with top-k (0: by the share plan, 1: never, 2: always).
 as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
   if (!ctx) return AS_ERR_INVALID_ARG;
   ctx->score_variant = variant;

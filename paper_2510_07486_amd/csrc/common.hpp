@@ -17,7 +17,7 @@ struct as_ctx {
   int device;
   void* ws;
   size_t ws_bytes;
-  int score_variant; /* which key-scoring kernel as_score_keys launches */
+  int score_variant; /* 0: as_score_keys scores; 1, 2: it launches the streaming-read calibration kernel */
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
                         1: always the separate kernels via HBM scores, 2: always fused */
 };

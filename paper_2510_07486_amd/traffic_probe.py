@@ -27,10 +27,11 @@ def main():
     kv = api.kv_view(inp.k_pool, inp.v_pool, inp.block_table, inp.ctx_lens)
     q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur)
     scores = torch.empty((w.batch, w.n_kv_heads, inp.max_pages * 16), dtype=torch.float32, device=dev)
-    ctx.set_score_variant(19)                       # calibration kernel behind as_score_keys
+    ctx.set_score_variant(1)                        # calibration kernel behind as_score_keys
     for _ in range(reps):
         api.as_score_keys(ctx, p, kv, q_hat, scores)
     torch.cuda.synchronize()
+    ctx.set_score_variant(0)
     for _ in range(reps):
         idx, cnt = api.as_score_topk(ctx, p, kv, q_hat)
     torch.cuda.synchronize()
