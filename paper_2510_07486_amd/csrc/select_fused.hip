@@ -8,11 +8,14 @@
 // pairs to an unordered candidate buffer in LDS (one LDS atomic per wavefront reserves the slots).
 // When the buffer is nearly full, a prune keeps exactly the best C pairs (radix threshold on the
 // key over register-held candidates, ties resolved by a second radix threshold on the token) and
-// its threshold tau then filters the stream: a later token can only matter if its key exceeds tau,
-// so the inflow decays like C / tokens-seen and a 32768-token share typically needs one prune and
-// the final selection, instead of one selection per 8192 tokens.  Because tokens are unique, the
-// pairs are totally ordered by (key descending, token ascending): the result does not depend on
-// the order in which wavefronts appended.  The final selection is put into ascending token order
+// its threshold then filters the stream: a token seen later can only matter if it beats the worst
+// kept pair (a larger key, or the same key and a lower token index), so the inflow decays like
+// C / tokens-seen and a 32768-token share typically needs one prune and the final selection,
+// instead of one selection per 8192 tokens.  Because tokens are unique, the pairs are totally
+// ordered by (key descending, token ascending): the result depends neither on the order in which
+// wavefronts appended nor on the order in which the share's pages are visited, and every workgroup
+// starts its walk at a different page (regularly laid out caches would otherwise have all
+// workgroups, advancing in lockstep, on the same memory channels).  The final selection is put into ascending token order
 // through a bitmap of the share (rank of a token = set bits below it) and goes out: straight into
 // sel_idx when the row has a single share, otherwise as (key, token) candidates that a small merge
 // kernel reduces to the row's top-C.  The top-C of a row is contained in the union of the top-C of
@@ -228,19 +231,29 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   // The share is streamed in sub-slices that are known to fit the free part of the candidate buffer.
   // The first one of a long share has a pseudo-random length, so that the prune phases of different
   // compute units do not coincide (all of them pausing their K stream at once would idle the HBM).
-  int n_sub = n_share;
-  if (n_share > CAP) {
+  int n_sub = (n_share + AS_PAGE - 1) / AS_PAGE * AS_PAGE;   // whole pages; tokens beyond the share are masked
+  if (n_sub > CAP) {
     const uint32_t wg = (uint32_t)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
     n_sub = CAP / 2 + 64 * (int)((wg * 2654435761u >> 16) % (CAP / 128));
   }
   const int share_pages = (n_share + AS_PAGE - 1) / AS_PAGE;
+  const int n_pad = share_pages * AS_PAGE;   // the share in whole pages: what the stream walks
   const int32_t* bt_row = block_table + (int64_t)b * max_pages + tok0 / AS_PAGE;
+  // The pages of the share are visited in rotated order, starting at a page that differs from workgroup to
+  // workgroup (the selection does not depend on the order in which tokens are seen): workgroups that
+  // advance in lockstep over regularly laid out sequences would otherwise keep hitting the same memory channels.
+  const uint32_t wg_id = (uint32_t)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
+  const int rot = (int)((wg_id * 2246822519u >> 12) % (uint32_t)share_pages);
+  auto real_page = [&](int vpage) -> int {   // vpage < share_pages
+    const int rp = vpage + rot;
+    return rp >= share_pages ? rp - share_pages : rp;
+  };
   // lane l keeps the page id of (iteration l / PG, page l % PG) of the sub-slice that starts at token `pos`
   // (a sub-slice has at most CAP tokens = 64 pages per wave)
   auto load_pages = [&](int pos) -> int32_t {
     const int lp = ((lane / PG) * FS_WAVES + wave) * PG + (lane % PG);
     const int pi = pos / AS_PAGE + lp;
-    const int32_t pg = pi < share_pages ? bt_row[pi] : 0;
+    const int32_t pg = pi < share_pages ? bt_row[real_page(pi)] : 0;
     return pg < 0 ? 0 : (pg > last_page ? last_page : pg);   // a corrupt table must not leave the pool
   };
   int pos = 0;
@@ -288,7 +301,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
 
   uint4* st = stage[wave];
   bool have_tau = false;   // after the first prune: only keys above tau can still make the best C
-  uint32_t tau = 0;
+  uint32_t tau = 0, tau_inv = 0;   // a pair (tau, token) still matters iff ~token >= tau_inv
   int cnt = 0;             // candidates in the buffer (uniform copy of c_cnt)
 #pragma unroll 1
   while (true) {
@@ -317,7 +330,8 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
         for (int m = 0; m < 4; ++m) kk[m] = st[lds_slot(t, cmap(grp, m))];
         __builtin_amdgcn_wave_barrier();
         float v = MODE == 0 ? -INFINITY : 0.f;
-        const bool tok_ok = (q * PG + pg) * AS_PAGE + t < n_sub;   // this lane's token of this page
+        const int vp_pg = pos / AS_PAGE + q * PG + pg;             // this page, in visiting order
+        const bool tok_ok = vp_pg < share_pages && real_page(vp_pg < share_pages ? vp_pg : 0) * AS_PAGE + t < n_share;
 #pragma unroll
         for (int s = 0; s < NSET; ++s) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -356,9 +370,11 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       float outv = res[0];
 #pragma unroll
       for (int pg = 1; pg < PG; ++pg) outv = grp == pg ? res[pg] : outv;
-      const int tl = (q * PG + grp) * AS_PAGE + t;  // token within the sub-slice
+      const int vp = pos / AS_PAGE + q * PG + grp;  // page of this lane's token, in visiting order
+      const int rel = real_page(vp < share_pages ? vp : 0) * AS_PAGE + t;   // token within the share
       const uint32_t key = score_key(outv + 0.0f);
-      const bool pass = grp < PG && tl < n_sub && (!have_tau || key > tau);
+      const bool pass = grp < PG && vp < share_pages && rel < n_share &&
+                        (!have_tau || key > tau || (key == tau && ~(uint32_t)(tok0 + rel) >= tau_inv));
       const uint64_t m = __ballot(pass);
       if (m) {   // uniform: one LDS atomic per wave reserves the slots
         const int leader = __ffsll((long long)m) - 1;
@@ -368,16 +384,16 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
         if (pass) {
           const uint32_t at = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
           c_key[at] = key;
-          c_tok[at] = tok0 + pos + tl;
+          c_tok[at] = tok0 + rel;
         }
       }
     }
     pos += n_sub;
-    const bool last = pos >= n_share;
+    const bool last = pos >= n_pad;
     if (!last) my_page = load_pages(pos);   // page ids of the next sub-slice travel during the barrier / prune
     if (MODE == 1) {                        // no candidate buffer to watch: whole-buffer-sized sub-slices, no barrier
       if (last) break;
-      n_sub = (n_share - pos) < CAP ? (n_share - pos) : CAP;
+      n_sub = (n_pad - pos) < CAP ? (n_pad - pos) : CAP;
       continue;
     }
     __syncthreads();
@@ -395,7 +411,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
         key[e] = have[e] ? c_key[i] : 0u;
         tok[e] = have[e] ? c_tok[i] : 0;
       }
-      tau = mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, C, hist, xch, sel);
+      tau = mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, C, hist, xch, sel, &tau_inv);
       have_tau = true;
       if (tid == 0) c_cnt = 0;
       __syncthreads();     // every thread holds its candidates in registers: the buffer can be rewritten
@@ -420,7 +436,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     __syncthreads();   // every wave holds the same count before the next sub-slice starts to append
     const int room = (CAP - cnt) & ~63;
     if (room <= 0) break;   // unreachable while the host plan keeps C <= CAP / 2 for multi-sub-slice shares
-    n_sub = (n_share - pos) < room ? (n_share - pos) : room;
+    n_sub = (n_pad - pos) < room ? (n_pad - pos) : room;
   }
 
   if (MODE == 1) {

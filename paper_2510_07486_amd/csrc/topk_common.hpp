@@ -237,11 +237,12 @@ __device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], 
 }
 
 // Marks, among this thread's NPT candidates, the ones that belong to the best `keep` of the `total`
-// candidates of the workgroup (keep < total).  Returns the key threshold T.
+// candidates of the workgroup (keep < total).  Returns the key threshold T; tie_inv (optional) receives the
+// cut among the pairs with key == T: such a pair is kept iff ~token >= *tie_inv (0 when every one of them is).
 template <int THREADS, int B0, int NPT>
 __device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const int32_t (&tok)[NPT],
                                               const bool (&have)[NPT], int keep, uint32_t* hist, uint32_t* xch,
-                                              bool (&sel)[NPT]) {
+                                              bool (&sel)[NPT], uint32_t* tie_inv = nullptr) {
   uint32_t r, ties;
   const uint32_t T = radix_threshold<THREADS, B0, NPT>(key, have, (uint32_t)keep, hist, xch, r, ties);
   uint32_t I = 0;   // threshold on ~token among the pairs with key == T
@@ -259,6 +260,7 @@ __device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const 
 #pragma unroll
   for (int e = 0; e < NPT; ++e)
     sel[e] = have[e] && (key[e] > T || (key[e] == T && ~(uint32_t)tok[e] >= I));
+  if (tie_inv) *tie_inv = I;
   return T;
 }
 
