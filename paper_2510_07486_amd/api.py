@@ -97,6 +97,8 @@ def lib():
         L.as_debug_select_plan.argtypes = [PP, C.c_int, C.POINTER(C.c_int32)]
         L.as_debug_set_score_variant.restype = C.c_int
         L.as_debug_set_score_variant.argtypes = [vp, C.c_int]
+        L.as_debug_workspace_gaps.restype = C.c_int
+        L.as_debug_workspace_gaps.argtypes = [vp, PP, C.c_int, C.POINTER(C.c_int32)]
         L.as_debug_set_select_mode.restype = C.c_int
         L.as_debug_set_select_mode.argtypes = [vp, C.c_int]
         _lib = L
@@ -173,6 +175,13 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def damaged_workspace_gap(self, p: AsParams, n_layers: int = 1) -> int:
+        """-1 if no kernel has written outside its region of the workspace (layout of (p, n_layers)), else the index
+        of the first damaged gap.  Synchronises; only meaningful if the context has used this one layout."""
+        bad = C.c_int32(0)
+        _check(lib().as_debug_workspace_gaps(self.handle, C.byref(p), n_layers, C.byref(bad)), "as_debug_workspace_gaps")
+        return bad.value
 
     def set_score_variant(self, v: int):
         _check(lib().as_debug_set_score_variant(self.handle, v), "as_debug_set_score_variant")

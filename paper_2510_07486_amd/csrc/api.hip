@@ -8,8 +8,12 @@ namespace {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+constexpr size_t WS_GAP = 256;          // never written by a kernel: separates the regions of the workspace
+constexpr unsigned char WS_FILL = 0xA5;  // what as_create fills the workspace with
+
 struct ws_layout {
   size_t q_hat, q_hat_layer, scores, cand, attn, total;
+  size_t gap[4];   // offsets of the gaps behind q_hat, scores, candidates, attention partials
   int64_t score_stride;
 };
 
@@ -20,11 +24,15 @@ ws_layout layout_of(const as_params* p, int n_layers = 1) {
   l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
   l.q_hat = 0;
   l.q_hat_layer = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
-  l.scores = l.q_hat + l.q_hat_layer * n_layers;
+  l.gap[0] = l.q_hat + l.q_hat_layer * n_layers;
+  l.scores = l.gap[0] + WS_GAP;
   size_t sc = n_layers > 1 ? 0 : align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
-  l.cand = l.scores + sc;
-  l.attn = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
-  l.total = l.attn + align_up(asx::attn_workspace_bytes(p));
+  l.gap[1] = l.scores + sc;
+  l.cand = l.gap[1] + WS_GAP;
+  l.gap[2] = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
+  l.attn = l.gap[2] + WS_GAP;
+  l.gap[3] = l.attn + align_up(asx::attn_workspace_bytes(p));
+  l.total = l.gap[3] + WS_GAP;
   return l;
 }
 
@@ -97,6 +105,11 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->select_mode = 0;
   if (workspace_bytes > 0) {
     if (hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
+      delete c;
+      return AS_ERR_HIP;
+    }
+    if (hipMemset(c->ws, WS_FILL, workspace_bytes) != hipSuccess) {   // the gaps between regions keep this pattern
+      hipFree(c->ws);
       delete c;
       return AS_ERR_HIP;
     }
@@ -318,6 +331,29 @@ as_status as_debug_select_plan(const as_params* p, int n_layers, int32_t* out) {
   out[0] = pl.slice_len;
   out[1] = pl.nslices;
   out[2] = pl.ccap;
+  return AS_OK;
+}
+// Checks the gaps that separate the workspace regions of the layout for (p, n_layers): a kernel that wrote beyond
+// its region has overwritten the fill pattern there.  Synchronises the device.  *first_bad = -1 if every gap is
+// intact, else the index of the first damaged one (0 q_hat, 1 score rows, 2 candidates, 3 attention partials).
+// Only meaningful for a ctx that has been used with this one layout since as_create.
+as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int n_layers, int32_t* first_bad) {
+  if (!ctx || !first_bad || check_params(p) != AS_OK || n_layers < 1 || n_layers > AS_MAX_PACK)
+    return AS_ERR_INVALID_ARG;
+  const ws_layout l = layout_of(p, n_layers);
+  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  if (hipDeviceSynchronize() != hipSuccess) return AS_ERR_HIP;
+  *first_bad = -1;
+  for (int g = 0; g < 4; ++g) {
+    unsigned char host[WS_GAP];
+    if (hipMemcpy(host, static_cast<char*>(ctx->ws) + l.gap[g], WS_GAP, hipMemcpyDeviceToHost) != hipSuccess)
+      return AS_ERR_HIP;
+    for (size_t i = 0; i < WS_GAP; ++i)
+      if (host[i] != WS_FILL) {
+        *first_bad = g;
+        return AS_OK;
+      }
+  }
   return AS_OK;
 }
 as_status as_debug_set_select_mode(as_ctx* ctx, int mode) {

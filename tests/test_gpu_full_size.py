@@ -59,6 +59,7 @@ def test_full_size_sampled_sequences(name, budget, samples):
         assert err <= 2e-2, (b, err)
         assert (lse[b].cpu() - ref_lse[0]).abs().max().item() <= 1e-3
     print(f"  {name}: tie swaps {swaps_total} over {len(samples)} sampled sequences", flush=True)
+    assert ctx.damaged_workspace_gap(p) == -1      # no kernel outgrew its region of the workspace at full size
 
 
 def test_million_token_context_and_largest_budget():
@@ -87,6 +88,7 @@ def test_million_token_context_and_largest_budget():
         print(f"  plan {api.select_plan(p)}, tie swaps {swaps}, attention max abs err {err:.3e}", flush=True)
         assert err <= 2e-2
         assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
+        assert ctx.damaged_workspace_gap(p) == -1
 
 
 def test_block_table_too_wide_for_a_share_plan_runs_the_stages():
@@ -109,6 +111,7 @@ def test_block_table_too_wide_for_a_share_plan_runs_the_stages():
     rq, rs, ridx, rcnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur, budget, eps)
     swaps = compare_selection(gidx, gcnt, ridx, rcnt, rs, cpu.ctx_lens, budget)
     print(f"  tie swaps {swaps}", flush=True)
+    assert ctx.damaged_workspace_gap(p) == -1
     with pytest.raises(api.AsError) as e:
         api.as_select_step_pack(api.Context(api.make_params(1, 8, 2, 8, 64, 16), pack=2), p,
                                 [api.layer_io(kv, cpu.q_win.cuda(), cpu.q_cur.cuda(), gidx, gcnt)] * 2)

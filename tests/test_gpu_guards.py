@@ -3,7 +3,8 @@ output of every entry point sits between two guard zones filled with a pattern, 
 after each call the guards must be intact, the inputs unchanged and the slots the header declares untouched (scores
 beyond a sequence's length, padding beyond sel_cnt excepted: that is written as -1) still hold the pattern.  Shapes
 are ragged on purpose: lengths that end inside a page, a budget that is no multiple of anything, rows cut into
-several shares, group sizes that take the 512-thread selection shape, the dense tail."""
+several shares, group sizes that take the 512-thread selection shape, the dense tail.  The library's own workspace
+is checked the same way, through the gaps it keeps between its regions."""
 import pytest
 import torch
 
@@ -58,7 +59,7 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
     kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
     inputs = (dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens, dev.q_win, dev.q_cur, dev.q_real)
     before = fingerprint(*inputs)
-    ctx = api.Context(p, pack=2)
+    ctx, ctx_pack = api.Context(p), api.Context(p, pack=2)     # one workspace layout per context (see the end)
 
     q_hat = Guarded((B, Hq, 128), torch.float32, 7.5)
     api.as_predict_query(ctx, p, dev.q_win, dev.q_cur, q_hat.t)
@@ -70,7 +71,7 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
         outs[name] = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
     api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur, outs["select_step"][0].t, outs["select_step"][1].t)
     api.as_score_topk(ctx, p, kv, q_hat.t, outs["score_topk"][0].t, outs["score_topk"][1].t)
-    api.as_select_step_pack(ctx, p, [api.layer_io(kv, dev.q_win, dev.q_cur, outs[n][0].t, outs[n][1].t)
+    api.as_select_step_pack(ctx_pack, p, [api.layer_io(kv, dev.q_win, dev.q_cur, outs[n][0].t, outs[n][1].t)
                                      for n in ("pack0", "pack1")])
     torch.cuda.synchronize()
     for name, (gi, gc) in outs.items():
@@ -121,6 +122,10 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
         assert (flat[:, keep:] == 9.0).all()
 
     assert fingerprint(*inputs) == before           # nothing wrote into the cache, the table or the queries
+    # the regions of the context workspace (q_hat, score rows, candidates, attention partials) are separated by
+    # gaps that hold the pattern as_create wrote: a kernel that outgrew the size computed for its region shows here
+    assert ctx.damaged_workspace_gap(p) == -1
+    assert ctx_pack.damaged_workspace_gap(p, 2) == -1
 
 
 def test_state_updates_touch_only_their_rows():
@@ -146,3 +151,18 @@ def test_state_updates_touch_only_their_rows():
     assert torch.equal(q_cur.t, dev.q_real) and torch.equal(q_win.t[:, :, -1], dev.q_cur)
     assert torch.equal(lens.t, dev.ctx_lens + 1)
     assert int((k_pool.t != dev.k_pool).any(dim=-1).sum()) <= B * Hkv     # one row per (sequence, head) at most
+
+
+def test_the_workspace_check_sees_a_write_into_a_gap():
+    """The check itself: after a call with one set of shapes, the gaps of a *different* layout (half the query
+    heads: its first gap lies where the call stored q_hat) no longer hold the fill pattern."""
+    w = wl.Workload("guard-check", 2, 8, 2, 4, 32, 400, page_table="identity", seed=31)
+    dev = to_dev(wl.make_inputs(w))
+    p = params_for(dev)
+    ctx = api.Context(p)
+    assert ctx.damaged_workspace_gap(p) == -1                     # fresh workspace
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    assert ctx.damaged_workspace_gap(p) == -1
+    other = api.make_params(2, 4, 2, 4, 32, dev.max_pages)
+    assert ctx.damaged_workspace_gap(other) == 0
