@@ -333,6 +333,17 @@ def main():
     o_hat = api.as_overlap_ratio(ctx_att, p, sel_hat[0], sel_hat[1], sel_real[0], sel_real[1])[1].mean().item()
     o_cur = api.as_overlap_ratio(ctx_att, p, sel_cur[0], sel_cur[1], sel_real[0], sel_real[1])[1].mean().item()
 
+    # the same on queries that regress on lag two (an AR(2) process): there the window carries information that
+    # Q_t alone does not
+    w2 = wl.scaled(w, lag2=0.85)
+    qw2, qc2, qr2 = wl.make_queries(w2, dev, 0)
+    s_hat2 = api.as_select_step(ctx_att, p, kvs[0], qw2, qc2)
+    s_real2 = api.as_score_topk(ctx_att, p, kvs[0], qr2.float().contiguous())
+    s_cur2 = api.as_score_topk(ctx_att, p, kvs[0], qc2.float().contiguous())
+    o_hat2 = api.as_overlap_ratio(ctx_att, p, s_hat2[0], s_hat2[1], s_real2[0], s_real2[1])[1].mean().item()
+    o_cur2 = api.as_overlap_ratio(ctx_att, p, s_cur2[0], s_cur2[1], s_real2[0], s_real2[1])[1].mean().item()
+    del qw2, qc2, qr2, s_hat2, s_real2, s_cur2
+
     def avg_us(fn, n):
         fn()
         torch.cuda.synchronize()
@@ -374,8 +385,11 @@ def main():
         "standalone_stages": standalone,
         "overlap_ratio_predicted_vs_real_query": round(o_hat, 4),       # Sec. 3 Eq. 1, S(q_hat) vs S(q_{t+1})
         "overlap_ratio_current_vs_real_query": round(o_cur, 4),         # S(q_t) vs S(q_{t+1}): no prediction
+        "lag2_queries": {"overlap_ratio_predicted_vs_real_query": round(o_hat2, 4),
+                         "overlap_ratio_current_vs_real_query": round(o_cur2, 4)},
         "dense_attn_us_per_layer": round(dense_us, 1), "sparse_attn_us_per_layer": round(sparse_us, 1),
-        "note": "one resident layer (warm), outside the timed region; AR(1) queries, not model traces",
+        "note": "one resident layer (warm), outside the timed region; AR(1) queries (lag2_queries: AR(2) with "
+                "coefficients 0.10 / 0.85), not model traces",
     }
 
     if not a.no_cpu_baseline:

@@ -48,6 +48,7 @@ class Workload:
     layers: int = 1
     seed: int = 0
     pool_slack: float = 1.0         # scatter: pool pages / pages in use
+    lag2: float = 0.0               # > 0: AR(2) queries x_s = (rho - lag2) x_{s-1} + lag2 x_{s-2} + (1 - rho) noise
 
     @property
     def group(self) -> int:
@@ -143,7 +144,7 @@ def make_page_table(w: Workload, ctx_lens: torch.Tensor):
 
 
 def make_queries(w: Workload, device="cpu", layer: int = 0):
-    """AR(1) chains -> (q_win, q_cur, q_real), bf16."""
+    """AR(1) chains (AR(2) when w.lag2 > 0) -> (q_win, q_cur, q_real), bf16."""
     B, H, W, D = w.batch, w.n_q_heads, w.window, HEAD_DIM
     g = _gen(w.seed, 100 + 7 * layer, device)
     if w.rho_range is not None:
@@ -153,8 +154,11 @@ def make_queries(w: Workload, device="cpu", layer: int = 0):
         rho = torch.full((B, H, 1), w.rho, device=device, dtype=torch.float32)
     x = torch.randn((B, H, D), generator=g, device=device, dtype=torch.float32)
     chain = [x]
+    prev = x
     for _ in range(W + 1):
-        x = rho * x + (1.0 - rho) * torch.randn((B, H, D), generator=g, device=device, dtype=torch.float32)
+        noise = torch.randn((B, H, D), generator=g, device=device, dtype=torch.float32)
+        nxt = (rho - w.lag2) * x + w.lag2 * prev + (1.0 - rho) * noise     # lag2 = 0: the AR(1) chain
+        prev, x = x, nxt
         chain.append(x)
     chain = torch.stack(chain, dim=2).to(torch.bfloat16)      # [B,H,W+2,D]
     return (chain[:, :, :W].contiguous(), chain[:, :, W].contiguous(), chain[:, :, W + 1].contiguous())

@@ -431,3 +431,35 @@ def test_softmax_sum_is_rejected_by_the_stand_alone_scoring_call():
         api.as_score_keys(ctx, p, api.kv_view(dev.k_pool, None, dev.block_table, dev.ctx_lens),
                           torch.zeros((1, 8, 128), device="cuda"))
     assert e.value.code == 2
+
+
+def test_predicted_query_beats_the_current_one_when_queries_regress_on_lag_two():
+    """The point of the predictor (Sec. 3 Eq. 1, Sec. 4.2): when the next query depends on the window beyond its last
+    entry, selecting with q_hat overlaps the real next query's selection more than selecting with Q_t does.  On AR(1)
+    chains Q_t is already the best guess; on an AR(2) process with a dominant lag-two coefficient it is not.  Both
+    ratios come out of the HIP path and are cross-checked against the oracle's."""
+    w = wl.Workload("lag2", 4, 8, 2, 16, 256, 4096, page_table="permute", seed=5, lag2=0.85)
+    cpu = wl.make_inputs(w)
+    dev = to_dev(cpu)
+    p = params_for(cpu)
+    ctx = api.Context(p)
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    hat = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    real = api.as_score_topk(ctx, p, kv, dev.q_real.float().contiguous())
+    cur = api.as_score_topk(ctx, p, kv, dev.q_cur.float().contiguous())
+    o_hat = api.as_overlap_ratio(ctx, p, hat[0], hat[1], real[0], real[1])[1].mean().item()
+    o_cur = api.as_overlap_ratio(ctx, p, cur[0], cur[1], real[0], real[1])[1].mean().item()
+    note(f"  overlap with the real next query's selection: predicted {o_hat:.3f}, current query {o_cur:.3f}")
+    assert o_hat > o_cur + 0.02
+
+    def oracle_sel(q):
+        s = oracle.score_keys(cpu.k_pool, cpu.block_table, cpu.ctx_lens, q.float().contiguous(), w.n_kv_heads)
+        return oracle.topk_select(s, cpu.ctx_lens, w.budget)
+
+    _, _, ridx, rcnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur, w.budget,
+                                          f32(1e-2))
+    ri, rc = oracle_sel(cpu.q_real)
+    ci, cc = oracle_sel(cpu.q_cur)
+    ref_hat = oracle.overlap_ratio(ridx, rcnt, ri, rc)[1].mean().item()
+    ref_cur = oracle.overlap_ratio(ci, cc, ri, rc)[1].mean().item()
+    assert abs(ref_hat - o_hat) <= 2e-3 and abs(ref_cur - o_cur) <= 2e-3      # tie swaps move single tokens at most
