@@ -109,7 +109,7 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
       return AS_ERR_HIP;
     }
     if (hipMemset(c->ws, WS_FILL, workspace_bytes) != hipSuccess) {   // the gaps between regions keep this pattern
-      hipFree(c->ws);
+      (void)hipFree(c->ws);
       delete c;
       return AS_ERR_HIP;
     }
