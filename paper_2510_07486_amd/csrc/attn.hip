@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(
 
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt ? sel_cnt[b * Hkv + j] : 0;   // no selection arrays: dense attention over [0, N)
-  cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
+  cnt = (cnt < 0 || N == 0) ? 0 : (cnt > C ? C : cnt);   // an empty sequence has nothing to select from
   int tail0 = sel_idx ? (sel_ctx_lens ? sel_ctx_lens[b] : N) : 0;
   tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
   const int L = cnt + (N - tail0);

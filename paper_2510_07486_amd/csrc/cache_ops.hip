@@ -72,13 +72,13 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
     int32_t* __restrict__ out_lens, int Hkv, int C, int Cp, int max_pages, int32_t last_page) {
   const int b = blockIdx.z, j = blockIdx.y, tid = threadIdx.x;
   const int64_t row = (int64_t)b * Hkv + j;
+  const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt[row];
-  cnt = cnt < 0 ? 0 : (cnt > C ? C : cnt);
+  cnt = (cnt < 0 || N == 0) ? 0 : (cnt > C ? C : cnt);   // an empty sequence has nothing to select from
   if (blockIdx.x == 0 && j == 0) {
     for (int i = tid; i < Cp; i += 256) out_table[(int64_t)b * Cp + i] = b * Cp + i;
     if (tid == 0) out_lens[b] = cnt;
   }
-  const int N = clamp_ctx(ctx_lens[b], max_pages);
   const int c = tid & 15;
   const int i0 = blockIdx.x * 64 + (tid >> 4);
   int n[4];
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   for (int e = 0; e < 4; ++e) {
     const int i = i0 + 16 * e;
     int v = (i < cnt) ? sel_idx[row * C + i] : 0;
-    n[e] = v < 0 ? 0 : (v >= N ? (N > 0 ? N - 1 : 0) : v);      // a bad index stays inside the sequence
+    n[e] = v < 0 ? 0 : (v >= N ? N - 1 : v);      // a bad index stays inside the sequence (N > 0 where cnt > 0)
   }
   uint4 kr[4], vr[4];
 #pragma unroll

@@ -166,3 +166,79 @@ def test_the_workspace_check_sees_a_write_into_a_gap():
     assert ctx.damaged_workspace_gap(p) == -1
     other = api.make_params(2, 4, 2, 4, 32, dev.max_pages)
     assert ctx.damaged_workspace_gap(other) == 0
+
+
+def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
+    """The header's promise for arrays that break the caller's contract: page ids are clamped into the pool, lengths
+    into the block table, indices into the sequence, counts into [0, C].  Sequence 1 gets every kind of damage; the
+    calls must finish, leave every guard intact, and give sequences 0 and 2 the results of the undamaged run."""
+    w = wl.Workload("corrupt", 3, 8, 2, 8, 96, 2000, ctx_min=700, page_table="scatter", pool_slack=1.2, seed=37)
+    clean = to_dev(wl.make_inputs(w))
+    p = params_for(clean)
+    B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
+    num_pages = clean.k_pool.shape[0]
+
+    def run(bt, lens, damage_selection, vector_alu=False):
+        ctx = api.Context(p)
+        kv = api.kv_view(clean.k_pool, clean.v_pool, bt, lens)
+        sel = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
+        api.as_select_step(ctx, p, kv, clean.q_win, clean.q_cur, sel[0].t, sel[1].t)
+        q_hat = api.as_predict_query(ctx, p, clean.q_win, clean.q_cur)
+        scores = Guarded((B, Hkv, bt.shape[1] * 16), torch.float32, 0.0)
+        api.as_score_keys(ctx, p, kv, q_hat, scores.t)
+        sel2 = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
+        api.as_topk_select(ctx, p, scores.t, lens, sel2[0].t, sel2[1].t)
+        idx, cnt = sel[0].t.clone(), sel[1].t.clone()
+        tail = torch.clamp(lens - 2, min=0)
+        if damage_selection:
+            idx[1, 0, :5] = torch.tensor([-9, 1 << 30, -1, 5_000_000, 3], dtype=torch.int32, device="cuda")
+            cnt[1, 0] = C + 1000
+            cnt[1, 1] = -4
+            tail[1] = -100
+        out, lse = Guarded((B, Hq, 128), torch.bfloat16, 3.0), Guarded((B, Hq), torch.float32, 3.0)
+        api.lib().as_debug_set_attn_impl(1 if vector_alu else 0)
+        try:
+            api.as_sparse_decode_attn(ctx, p, kv, clean.q_real, idx, cnt, tail, out.t, lse.t)
+            dense = Guarded((B, Hq, 128), torch.bfloat16, 3.0)
+            api.as_dense_decode_attn(ctx, p, kv, clean.q_real, dense.t, want_lse=False)
+        finally:
+            api.lib().as_debug_set_attn_impl(0)
+        cp = api.compact_pages(p)
+        k_out = Guarded((B * cp, Hkv, 16, 128), torch.bfloat16, 9.0)
+        v_out = Guarded((B * cp, Hkv, 16, 128), torch.bfloat16, 9.0)
+        tab, ln = Guarded((B, cp), torch.int32, -77), Guarded((B,), torch.int32, -77)
+        api.as_gather_kv(ctx, p, kv, idx, cnt, k_out.t, v_out.t, tab.t, ln.t)
+        inter = Guarded((B, Hkv), torch.int32, -77)
+        api.as_overlap_ratio(ctx, p, idx, cnt, sel2[0].t, sel2[1].t, inter.t)
+        k_pool, v_pool = Guarded(tuple(clean.k_pool.shape), torch.bfloat16, 5.0), Guarded(tuple(clean.v_pool.shape), torch.bfloat16, 5.0)
+        k_pool.t.copy_(clean.k_pool)
+        v_pool.t.copy_(clean.v_pool)
+        lens2 = Guarded((B,), torch.int32, -77)
+        lens2.t.copy_(lens)
+        k_new = torch.ones((B, Hkv, 128), dtype=torch.bfloat16, device="cuda")
+        api.as_kv_append(ctx, p, k_pool.t, v_pool.t, bt, lens2.t, k_new, k_new)
+        torch.cuda.synchronize()
+        guards = (sel[0], sel[1], scores, sel2[0], sel2[1], out, lse, dense, k_out, v_out, tab, ln, inter, k_pool,
+                  v_pool, lens2)
+        assert all(g.intact() for g in guards)
+        assert ctx.damaged_workspace_gap(p) == -1
+        return dict(sel=sel[0].t, cnt=sel[1].t, sel2=sel2[0].t, out=out.t, lse=lse.t, dense=dense.t, k_out=k_out.t,
+                    inter=inter.t)
+
+    ref = {impl: run(clean.block_table, clean.ctx_lens, damage_selection=False, vector_alu=impl)
+           for impl in (False, True)}           # the two attention kernels round differently
+    bt = clean.block_table.clone()
+    bt[1, 0::3] = -7                                   # negative page ids
+    bt[1, 1::3] = num_pages + 12345                    # page ids beyond the pool
+    for bad_len in (-3, 16 * bt.shape[1] + 999):       # a negative length, a length beyond the block table
+        lens = clean.ctx_lens.clone()
+        lens[1] = bad_len
+        for vector_alu in (False, True):
+            print("corrupt", bad_len, vector_alu, flush=True)
+            got = run(bt, lens, damage_selection=True, vector_alu=vector_alu)
+            for name in ("sel", "cnt", "sel2", "out", "lse", "dense", "inter"):
+                for b in (0, 2):
+                    assert torch.equal(got[name][b], ref[vector_alu][name][b]), (name, b)
+            cp = api.compact_pages(p)
+            for b in (0, 2):
+                assert torch.equal(got["k_out"][b * cp:(b + 1) * cp], ref[vector_alu]["k_out"][b * cp:(b + 1) * cp])
