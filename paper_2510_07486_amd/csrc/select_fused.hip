@@ -120,14 +120,19 @@ select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, s
 // kernel indexes at most FS_MAX_SLICES of them per row (contexts beyond 4-8 million tokens at such budgets)
 bool select_plan_ok(const as_params* p, int n_layers) { return plan_select(p, n_layers).nslices <= FS_MAX_SLICES; }
 
-// A single layer with so few rows that the plan cuts them into shares no longer than the budget: no share can
-// prune, every token would travel to the merge kernel as an 8-byte candidate and the merge would be a top-k over
-// the whole row.  The stand-alone stages do the same work with 4-byte scores and keys held in registers
-// (batch 1, 16384 tokens, budget 2048: 10 + 17 us against 15 + 22 us).
+// A single layer with so few rows that the plan cuts them into shares not much longer than the budget: the shares
+// can discard little or nothing, most tokens would travel to the merge kernel as 8-byte candidates and the merge
+// would be a top-k over (nearly) the whole row.  The stand-alone stages do the same work with 4-byte scores and
+// keys held in registers (batch 1, 16384 tokens, budget 2048: 10 + 17 us against 15 + 22 us; batch 1, 4096 tokens,
+// budget 256: 9 + 9 us against 15 + 9 us).  Chosen when at least half of a row would reach the merge and the row
+// fits the register top-k; rows beyond that only when no share could discard anything at all.
 bool select_prefers_stages(const as_params* p) {
   if (p->agg == AS_AGG_SOFTMAX_SUM) return false;   // needs the row-wide normalisers of the fused passes
   const select_plan pl = plan_select(p, 1);
-  return pl.nslices > 1 && pl.ccap == pl.slice_len;
+  if (pl.nslices <= 1) return false;
+  if (pl.ccap == pl.slice_len) return true;
+  const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
+  return max_ctx <= 32 * TK_THREADS && (int64_t)pl.nslices * pl.ccap * 2 >= max_ctx;
 }
 
 // bytes of the candidate arrays (rows cut into several shares) and, behind them, of the per-share (max, sum)
