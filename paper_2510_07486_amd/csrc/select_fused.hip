@@ -247,8 +247,10 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   // The pages of the share are visited in rotated order, starting at a page that differs from workgroup to
   // workgroup (the selection does not depend on the order in which tokens are seen): workgroups that
   // advance in lockstep over regularly laid out sequences would otherwise keep hitting the same memory channels.
-  const uint32_t wg_id = (uint32_t)((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
-  const int rot = (int)((wg_id * 2246822519u >> 12) % (uint32_t)share_pages);
+  // (the KV heads of a sequence share the start: their workgroups then read the eight 4 KB chunks of one page
+  // record at about the same time)
+  const uint32_t rot_id = (uint32_t)(blockIdx.z * gridDim.y + blockIdx.y);
+  const int rot = (int)((rot_id * 2246822519u >> 12) % (uint32_t)share_pages);
   auto real_page = [&](int vpage) -> int {   // vpage < share_pages
     const int rp = vpage + rot;
     return rp >= share_pages ? rp - share_pages : rp;
