@@ -113,128 +113,30 @@ def main():
     eps = float(np.float32(1e-2))
     p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1], ridge_eps=eps,
                         sm_scale=float(np.float32(1 / math.sqrt(128))), agg=a.agg)
-    n_sel = max(1, a.sel_streams)
-    pack = max(1, min(a.pack, api.AS_MAX_PACK, n_layers))
-    ctx_sels = [api.Context(p, pack=pack) for _ in range(n_sel)]
-    ctx_att = api.Context(p)
+    from paper_2510_07486_amd.pipeline import LayerState, SelectionPipeline
     kvs = [api.kv_view(L["k"], L["v"], bt, ctx_lens) for L in layers]
     B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
     stride = bt.shape[1] * wl.PAGE
-    q_hats = [torch.empty((B, Hq, 128), dtype=torch.float32, device=dev) for _ in range(n_sel)]
-    scores = torch.empty((B, Hkv, stride), dtype=torch.float32, device=dev) if a.unfused else None
-    # double-buffered selections: step t attends over sel[t % 2], selection writes sel[(t+1) % 2]
-    sel = [[(torch.empty((B, Hkv, C), dtype=torch.int32, device=dev),
-             torch.empty((B, Hkv), dtype=torch.int32, device=dev)) for _ in range(n_layers)] for _ in range(2)]
+    # layer l of the step uses resident copy l % resident (identical work); selections are per logical layer
+    states = [LayerState(kvs[l % resident], layers[l % resident]["qw"], layers[l % resident]["qc"],
+                         layers[l % resident]["qr"]) for l in range(n_layers)]
+    pipe = SelectionPipeline(p, states, sel_streams=a.sel_streams, pack=a.pack)
+    pack, n_sel = pipe.pack, len(pipe.s_sel)
+    ctx_att = pipe.ctx_att
+    if a.unfused:                                   # score rows through HBM, then the stand-alone top-k
+        for c in pipe.ctx_sel:
+            c.set_select_mode(1)
     out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
-    s_sels, s_att = [torch.cuda.Stream() for _ in range(n_sel)], torch.cuda.Stream()
-
-    def select(l, dst, stream, ev_pair=None, lane=0):
-        """The two calls as_select_step makes (as_predict_query, as_score_topk), issued separately so that the
-        K-streaming part can be bracketed by events on its own stream."""
-        L = layers[l % resident]
-        kv = kvs[l % resident]
-        ctx_sel, q_hat = ctx_sels[lane], q_hats[lane]
-        api.as_predict_query(ctx_sel, p, L["qw"], L["qc"], q_hat, stream=stream)
-        if ev_pair is not None:
-            ev_pair[0].record(stream)
-        if a.unfused:
-            api.as_score_keys(ctx_sel, p, kv, q_hat, scores, stream=stream)
-            if ev_pair is not None:
-                ev_pair[1].record(stream)
-            api.as_topk_select(ctx_sel, p, scores, ctx_lens, dst[0], dst[1], stream=stream)
-        else:
-            api.as_score_topk(ctx_sel, p, kv, q_hat, dst[0], dst[1], stream=stream)
-            if ev_pair is not None:
-                ev_pair[1].record(stream)
-
-    # packed selection: layers [g*pack, (g+1)*pack) in one as_select_step_pack call
-    n_packs = (n_layers + pack - 1) // pack
-    pack_ios = None
-    if pack > 1:
-        pack_ios = [[(api.AsLayerIo * len(range(g * pack, min(n_layers, (g + 1) * pack))))(
-            *[api.layer_io(kvs[l % resident], layers[l % resident]["qw"], layers[l % resident]["qc"],
-                           sel[t][l][0], sel[t][l][1]) for l in range(g * pack, min(n_layers, (g + 1) * pack))])
-            for g in range(n_packs)] for t in range(2)]
-
-    def select_pack(g, t_dst, stream, ev_pair=None, lane=0):
-        if ev_pair is not None:
-            ev_pair[0].record(stream)
-        api.as_select_step_pack(ctx_sels[lane], p, pack_ios[t_dst][g], stream=stream)
-        if ev_pair is not None:
-            ev_pair[1].record(stream)
-
-    def attend(l, src, stream):
-        L = layers[l % resident]
-        api.as_sparse_decode_attn(ctx_att, p, kvs[l % resident], L["qr"], src[0], src[1], out=out, stream=stream,
-                                  want_lse=False)
-
-    # prime both selection buffers
-    for t in range(2):
-        for l in range(n_layers):
-            select(l, sel[t][l], s_sels[0])
-    torch.cuda.synchronize()
-
-    # sel_done[parity][pack]: recorded on a selection stream when that pack's selection into sel[parity] is
-    # complete; the attention that reads it (one step later) waits for exactly that event
-    sel_done = [[None] * n_packs for _ in range(2)]
-
-    def step_overlapped(t, score_events=None, join=False):
-        """One decode step.  Attention of layer l (stream ATT) reads the selection made one step earlier and waits
-        only for that pack's event; the selection of a pack for the next step starts on a selection stream as soon as
-        the pack's last layer has its step-t query / key / value (i.e. when its attention is enqueued).  With
-        join=True (graph capture: events cannot cross graph launches) every selection stream is joined at step end."""
-        cur, nxt = sel[t % 2], sel[(t + 1) % 2]
-        for l in range(n_layers):
-            g = l // pack
-            if l % pack == 0 and sel_done[t % 2][g] is not None and not join:
-                s_att.wait_event(sel_done[t % 2][g])
-            last_of_pack = (l % pack == pack - 1) or l == n_layers - 1
-            if last_of_pack:                       # a pack is selected once its last layer's q/k/v exist
-                lane = g % n_sel
-                ev = torch.cuda.Event()
-                ev.record(s_att)                   # layer l's step-t query/key/value exist from here on; every
-                s_sels[lane].wait_event(ev)        # earlier reader of sel[(t+1) % 2] has been enqueued before it
-                pair = None
-                if score_events is not None:
-                    pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                    score_events.append(pair)
-                if pack > 1:
-                    select_pack(g, (t + 1) % 2, s_sels[lane], pair, lane)
-                else:
-                    select(l, nxt[l], s_sels[lane], pair, lane)
-                if not join:
-                    done = torch.cuda.Event()
-                    done.record(s_sels[lane])
-                    sel_done[(t + 1) % 2][g] = done
-            attend(l, cur[l], s_att)
-        if join:
-            for s_sel in s_sels:
-                done = torch.cuda.Event()
-                done.record(s_sel)
-                s_att.wait_event(done)
-
-    def step_serial(t, score_events=None):
-        cur, nxt = sel[t % 2], sel[(t + 1) % 2]
-        for l in range(n_layers):
-            if pack == 1 or l % pack == pack - 1 or l == n_layers - 1:
-                pair = None
-                if score_events is not None:
-                    pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                    score_events.append(pair)
-                if pack > 1:
-                    select_pack(l // pack, (t + 1) % 2, s_att, pair)
-                else:
-                    select(l, nxt[l], s_att, pair)
-            attend(l, cur[l], s_att)
+    pipe.prime()                                    # both selection buffers hold a selection
 
     def timed(step_fn):
         for t in range(a.warmup):
-            step_fn(t)
+            step_fn(t, out)
         torch.cuda.synchronize()
         evs = []
         t_start = time.perf_counter()
         for t in range(a.steps):
-            step_fn(a.warmup + t, evs)
+            step_fn(a.warmup + t, out, evs)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t_start
         score_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
@@ -248,11 +150,10 @@ def main():
         graphs = []
         for parity in range(2):
             g = torch.cuda.CUDAGraph()
-            s_att.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.graph(g, stream=s_att):
-                for s_sel in s_sels:
-                    s_sel.wait_stream(s_att)       # fork
-                step_overlapped(parity, join=True)  # joins the selection streams back into s_att at its end
+            pipe.s_att.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(g, stream=pipe.s_att):
+                pipe.fork()
+                pipe.step(parity, out, join=True)   # joins the selection streams back into the attention stream
             graphs.append(g)
         torch.cuda.synchronize()
         for t in range(a.warmup):
@@ -264,11 +165,11 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t_start
 
-    dt_serial, score_ms_serial = timed(step_serial)
+    dt_serial, score_ms_serial = timed(pipe.step_serial)
     if a.serial_only:
         dt_ovl, score_ms_ovl = dt_serial, score_ms_serial
     else:
-        dt_ovl, score_ms_ovl = timed(step_overlapped)
+        dt_ovl, score_ms_ovl = timed(pipe.step)
         if a.graph:
             dt_ovl = timed_graph()                 # the in-stream rate of the scoring calls stays the eager pass's
 
@@ -312,8 +213,9 @@ def main():
         "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
         "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "score_keys_gbs_while_overlapped": round(k_bytes / (score_ms_shared * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "score_keys" if a.unfused else ("score_topk (slice + merge kernels)" if pack == 1 else
-                                                              "select_step_pack (predict + slice + merge kernels)"), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "score_keys + topk_select (stand-alone kernels)" if a.unfused else ("as_score_topk (select_slice_kernel [+ select_merge_kernel]; few-row shapes: the stand-alone kernels)"
+                                                              if pack == 1 else
+                                                              "as_select_step_pack (predict + slice [+ merge] kernels)"), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4),
                      "launch_ms_p10_median_p90": [round(float(x) / (pack if pack > 1 else 1), 4)
