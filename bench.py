@@ -173,6 +173,22 @@ def main():
         if a.graph:
             dt_ovl = timed_graph()                 # the in-stream rate of the scoring calls stays the eager pass's
 
+    # the timed path did the work: what it left behind (both selection buffers of the first and the last layer, the
+    # last attention output) equals a fresh computation on the default stream, bit for bit
+    checked = []
+    for l in sorted({0, n_layers - 1}):
+        st = states[l]
+        ref_idx, ref_cnt = api.as_select_step(ctx_att, p, st.kv, st.q_win, st.q_cur)
+        for parity in range(2):
+            ok = torch.equal(pipe.sel[parity][l][0], ref_idx) and torch.equal(pipe.sel[parity][l][1], ref_cnt)
+            checked.append(bool(ok))
+    ref_out, _ = api.as_sparse_decode_attn(ctx_att, p, states[-1].kv, states[-1].q_attn, pipe.sel[0][n_layers - 1][0],
+                                           pipe.sel[0][n_layers - 1][1], want_lse=False)
+    checked.append(bool(torch.equal(ref_out, out)))
+    if not all(checked):
+        print(f"bench.py: the timed schedule's results differ from a fresh computation: {checked}", file=sys.stderr)
+        sys.exit(3)
+
     ms_step = dt_ovl / a.steps * 1e3
     us_layer = ms_step * 1e3 / n_layers
     us_layer_serial = dt_serial / a.steps * 1e6 / n_layers
@@ -223,6 +239,8 @@ def main():
                      "launches_timed": len(score_ms_serial),
                      "measured_in": "single-stream timed pass (events on the launch stream)"},
         "input_gen_s": round(gen_s, 1),
+        "results_checked": "selections of the first and last layer and the last attention output equal a fresh "
+                           "computation on the default stream",
     }
 
     # ---- context numbers (untimed region): prediction quality on this synthetic workload and the
