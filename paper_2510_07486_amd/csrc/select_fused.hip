@@ -413,10 +413,12 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       bool have[NPT], sel[NPT];
 #pragma unroll
       for (int e = 0; e < NPT; ++e) {
-        const int i = tid + e * FS_THREADS;
+        const int i = tid + e * FS_THREADS;      // < CAP: the read needs no guard, stale slots are masked
         have[e] = i < cnt;
-        key[e] = have[e] ? c_key[i] : 0u;
-        tok[e] = have[e] ? c_tok[i] : 0;
+        const uint32_t k = c_key[i];
+        const int32_t tk = c_tok[i];
+        key[e] = have[e] ? k : 0u;
+        tok[e] = have[e] ? tk : 0;
       }
       tau = mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, C, hist, xch, sel, &tau_inv);
       have_tau = true;
@@ -486,10 +488,12 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     bool have[NPT], sel[NPT];
 #pragma unroll
     for (int e = 0; e < NPT; ++e) {
-      const int i = tid + e * FS_THREADS;
+      const int i = tid + e * FS_THREADS;        // < CAP
       have[e] = i < cnt;
-      key[e] = have[e] ? c_key[i] : 0u;
-      tok[e] = have[e] ? c_tok[i] : 0;
+      const uint32_t k = c_key[i];
+      const int32_t tk = c_tok[i];
+      key[e] = have[e] ? k : 0u;
+      tok[e] = have[e] ? tk : 0;
       sel[e] = have[e];
     }
     if (keep < cnt) mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, keep, hist, xch, sel);
@@ -578,13 +582,30 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
   const int nvirt = nslices * ccap;
   if (keep > 0) {
     if (total <= MG_LDS) {
-      for (int v = tid; v < nvirt; v += TK_THREADS) {
-        const int sl = v / ccap, i = v - sl * ccap;
-        if (i < cnt_sh[sl]) {
-          const int pos = pre_sh[sl] + i;
-          lkey[pos] = cand_key[cbase + v];
-          lidx[pos] = cand_idx[cbase + v];
+      // eight candidates per thread and round, every load issued before the first is waited for (empty slots
+      // re-read candidate 0 of the row: a guarded load would sit in a branch with a wait of its own)
+      constexpr int MG_U = 8;
+#pragma unroll 1
+      for (int base = 0; base < nvirt; base += MG_U * TK_THREADS) {
+        uint32_t k[MG_U];
+        int32_t ix[MG_U];
+        int pos[MG_U];
+#pragma unroll
+        for (int u = 0; u < MG_U; ++u) {
+          const int v = base + u * TK_THREADS + tid;
+          const int sl = v < nvirt ? v / ccap : 0;
+          const int i = v - sl * ccap;
+          const bool ok = v < nvirt && i < cnt_sh[sl];
+          pos[u] = ok ? pre_sh[sl] + i : -1;
+          k[u] = cand_key[cbase + (ok ? v : 0)];
+          ix[u] = cand_idx[cbase + (ok ? v : 0)];
         }
+#pragma unroll
+        for (int u = 0; u < MG_U; ++u)
+          if (pos[u] >= 0) {
+            lkey[pos[u]] = k[u];
+            lidx[pos[u]] = ix[u];
+          }
       }
       __syncthreads();
       // a thread owns MG_NPT consecutive candidates (token order): exact marking of the best `keep` in registers,
@@ -594,10 +615,12 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
       bool have[MG_NPT], sel[MG_NPT];
 #pragma unroll
       for (int e = 0; e < MG_NPT; ++e) {
-        const int i = tid * MG_NPT + e;
+        const int i = tid * MG_NPT + e;            // < MG_LDS
         have[e] = i < total;
-        key[e] = have[e] ? lkey[i] : 0u;
-        tok[e] = have[e] ? lidx[i] : 0;
+        const uint32_t k = lkey[i];
+        const int32_t tk = lidx[i];
+        key[e] = have[e] ? k : 0u;
+        tok[e] = have[e] ? tk : 0;
         sel[e] = have[e];
       }
       if (keep < total) mark_best<TK_THREADS, 12, MG_NPT>(key, tok, have, keep, hist, xch, sel);

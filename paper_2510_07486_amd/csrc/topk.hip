@@ -69,11 +69,18 @@ __global__ __launch_bounds__(TK_THREADS) void topk_regs_kernel(const float* __re
   uint32_t key[NPT];
   int32_t tok[NPT];
   bool have[NPT], sel[NPT];
+  // every load is issued before the first one is waited for: slots beyond the row re-read its last score (N >= 1
+  // here) instead of sitting in a branch of their own, which would serialise the NPT round trips
+  float raw[NPT];
 #pragma unroll
   for (int e = 0; e < NPT; ++e) {
     tok[e] = tid + e * TK_THREADS;
     have[e] = tok[e] < N;
-    key[e] = have[e] ? score_key(s[tok[e]]) : 0u;
+    raw[e] = s[have[e] ? tok[e] : N - 1];
+  }
+#pragma unroll
+  for (int e = 0; e < NPT; ++e) {
+    key[e] = have[e] ? score_key(raw[e]) : 0u;
     sel[e] = have[e];
   }
   if (keep < N) mark_best<TK_THREADS, 12, NPT>(key, tok, have, keep, hist, xch, sel);
