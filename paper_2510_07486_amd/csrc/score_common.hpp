@@ -24,31 +24,37 @@ __device__ __forceinline__ void build_q_operand(const float* __restrict__ q_hat,
   const int slot = 2 * (r >> 2) + (r & 1);
   const int part = (r >> 1) & 1;
   const float* qb = q_hat + ((int64_t)b * Hq + (int64_t)j * G) * AS_HEAD_DIM;
+  // all loads of an operand set are issued before the first conversion (one round trip, not one per chunk)
 #pragma unroll
   for (int s = 0; s < NSET; ++s) {
+    float v[4][8];
+    if (agg == AS_AGG_SUM) {
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[m][e] = 0.f;
+      for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[m][e] += qb[g * AS_HEAD_DIM + cmap(grp, m) * 8 + e];
+      }
+    } else {
+      const int g = (s * 8 + slot) % G;
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[m][e] = qb[g * AS_HEAD_DIM + cmap(grp, m) * 8 + e];
+    }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-      const int c = cmap(grp, m);
-      float v[8];
-      if (agg == AS_AGG_SUM) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = 0.f;
-        for (int g = 0; g < G; ++g) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += qb[g * AS_HEAD_DIM + c * 8 + e];
-        }
-      } else {
-        const int g = (s * 8 + slot) % G;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = qb[g * AS_HEAD_DIM + c * 8 + e];
-      }
       uint32_t w[4];
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
-        uint32_t h0 = f32_to_bf16_rne(v[e]), h1 = f32_to_bf16_rne(v[e + 1]);
+        uint32_t h0 = f32_to_bf16_rne(v[m][e]), h1 = f32_to_bf16_rne(v[m][e + 1]);
         if (part) {
-          h0 = f32_to_bf16_rne(v[e] - __uint_as_float(h0 << 16));
-          h1 = f32_to_bf16_rne(v[e + 1] - __uint_as_float(h1 << 16));
+          h0 = f32_to_bf16_rne(v[m][e] - __uint_as_float(h0 << 16));
+          h1 = f32_to_bf16_rne(v[m][e + 1] - __uint_as_float(h1 << 16));
         }
         w[e >> 1] = h0 | (h1 << 16);
       }
