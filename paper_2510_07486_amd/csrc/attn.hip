@@ -287,29 +287,51 @@ __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* 
   const int d = threadIdx.x;
   const float2* ml = reinterpret_cast<const float2*>(part_ml) + bh * nsplit;
   const float* po = part_o + bh * nsplit * AS_HEAD_DIM + d;
-  // eight partials per round: their loads are independent of each other and issued together
+  // Partials are loaded in batches whose loads are all issued before the first is used (slots beyond nsplit re-read
+  // the last partial and are masked afterwards: a guarded load would wait for its own round trip).  The first
+  // sixteen (m, l) pairs and output values are fetched once, together, and serve both the maximum and the sum.
+  constexpr int HELD = 16;
+  const int last = nsplit - 1;
+  float2 v0[HELD];
+  float x0[HELD];
+#pragma unroll
+  for (int e = 0; e < HELD; ++e) {
+    const int si = e < nsplit ? e : last;
+    v0[e] = ml[si];
+    x0[e] = po[(int64_t)si * AS_HEAD_DIM];
+  }
   float M = -INFINITY;
-  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+#pragma unroll
+  for (int e = 0; e < HELD; ++e)
+    if (e < nsplit && v0[e].y > 0.f) M = fmaxf(M, v0[e].x);
+  for (int s0 = HELD; s0 < nsplit; s0 += 8) {
     float2 v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = s0 + e < nsplit ? ml[s0 + e] : make_float2(-INFINITY, 0.f);
+    for (int e = 0; e < 8; ++e) v[e] = ml[s0 + e < nsplit ? s0 + e : last];
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (v[e].y > 0.f) M = fmaxf(M, v[e].x);
+      if (s0 + e < nsplit && v[e].y > 0.f) M = fmaxf(M, v[e].x);
   }
   float Lsum = 0.f, o = 0.f;
-  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+#pragma unroll
+  for (int e = 0; e < HELD; ++e)
+    if (e < nsplit && v0[e].y > 0.f) {
+      const float wgt = expf(v0[e].x - M);
+      Lsum += v0[e].y * wgt;
+      o += wgt * x0[e];
+    }
+  for (int s0 = HELD; s0 < nsplit; s0 += 8) {
     float2 v[8];
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const bool in = s0 + e < nsplit;
-      v[e] = in ? ml[s0 + e] : make_float2(-INFINITY, 0.f);
-      x[e] = in ? po[(int64_t)(s0 + e) * AS_HEAD_DIM] : 0.f;
+      const int si = s0 + e < nsplit ? s0 + e : last;
+      v[e] = ml[si];
+      x[e] = po[(int64_t)si * AS_HEAD_DIM];
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (v[e].y > 0.f) {
+      if (s0 + e < nsplit && v[e].y > 0.f) {
         const float wgt = expf(v[e].x - M);
         Lsum += v[e].y * wgt;
         o += wgt * x[e];
