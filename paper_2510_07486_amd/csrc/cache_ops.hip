@@ -79,27 +79,31 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
     for (int i = tid; i < Cp; i += 256) out_table[(int64_t)b * Cp + i] = b * Cp + i;
     if (tid == 0) out_lens[b] = cnt;
   }
+  if (blockIdx.x * 64 >= cnt) return;    // nothing selected in this workgroup's range (cnt > 0 below, hence N > 0)
   const int c = tid & 15;
   const int i0 = blockIdx.x * 64 + (tid >> 4);
+  // Three dependent rounds (index, page id, row), each with all of its loads in flight together: slots beyond the
+  // count re-read the row's first index instead of sitting in a branch with a wait of its own, and are masked
+  // at the store.
   int n[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int i = i0 + 16 * e;
-    int v = (i < cnt) ? sel_idx[row * C + i] : 0;
-    n[e] = v < 0 ? 0 : (v >= N ? N - 1 : v);      // a bad index stays inside the sequence (N > 0 where cnt > 0)
+    const int v = sel_idx[row * C + (i < cnt ? i : 0)];
+    n[e] = v < 0 ? 0 : (v >= N ? N - 1 : v);      // a bad index stays inside the sequence
   }
+  int32_t pg[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) pg[e] = block_table[(int64_t)b * max_pages + (n[e] >> 4)];
   uint4 kr[4], vr[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    if (i0 + 16 * e < cnt) {
-      int32_t pg = block_table[(int64_t)b * max_pages + (n[e] >> 4)];
-      pg = pg < 0 ? 0 : (pg > last_page ? last_page : pg);
-      const int64_t off = chunk_offset(pg, Hkv, j) + (int64_t)(n[e] & 15) * AS_HEAD_DIM + c * 8;
-      const u32x4_c a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(k_pool + off));
-      const u32x4_c d = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(v_pool + off));
-      kr[e] = make_uint4(a.x, a.y, a.z, a.w);
-      vr[e] = make_uint4(d.x, d.y, d.z, d.w);
-    }
+    const int32_t p = pg[e] < 0 ? 0 : (pg[e] > last_page ? last_page : pg[e]);
+    const int64_t off = chunk_offset(p, Hkv, j) + (int64_t)(n[e] & 15) * AS_HEAD_DIM + c * 8;
+    const u32x4_c a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(k_pool + off));
+    const u32x4_c d = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(v_pool + off));
+    kr[e] = make_uint4(a.x, a.y, a.z, a.w);
+    vr[e] = make_uint4(d.x, d.y, d.z, d.w);
   }
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
