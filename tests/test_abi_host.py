@@ -127,3 +127,21 @@ def test_share_plan_invariants_over_random_shapes():
             if agg == 2:
                 need += layers * batch * hkv * g * shares * 8
             assert api.as_workspace_bytes_pack(p, layers) >= need
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path, monkeypatch):
+    """No CPU fallback anywhere above the C ABI: without the built library the binding raises, and neither the binding
+    nor the pipeline module imports the oracle."""
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "libasyncspade.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        api.as_workspace_bytes(api.make_params(1, 8, 2, 8, 64, 16))
+    with pytest.raises(RuntimeError, match="missing"):
+        api.Context(api.make_params(1, 8, 2, 8, 64, 16))
+    pkg = os.path.join(ROOT, "paper_2510_07486_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            src = open(os.path.join(pkg, name)).read()
+            assert "import oracle" not in src and "from oracle" not in src, name
+    for name in os.listdir(os.path.join(pkg, "csrc")):
+        assert "oracle" not in open(os.path.join(pkg, "csrc", name)).read(), name
