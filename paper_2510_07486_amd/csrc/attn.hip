@@ -31,27 +31,36 @@ static inline int attn_gh(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : 
 
 static int g_attn_impl = 0;  // 0: matrix-core kernel (attn_mfma.hip), 1: vector-ALU kernel below
 
-// Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head):
-// about six workgroups per compute unit, so that per-split costs (partials through HBM, query
-// fetch, reductions) stay small next to the gathered rows; never below AT_SPLIT tokens.  One
-// extra split at the end takes whatever lies beyond list_len (the dense tail of a sparse call).
+// Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head).  Measured on the
+// matrix-core kernel (32/8 and 64/8 heads, budgets 1024-4096): what counts is that all workgroups are resident at
+// once (three fit a compute unit: at most 768; a second, partly filled round costs 5-10 %) and that the four
+// wavefronts of a workgroup get the same number of 32-token steps; 512 workgroups of 1024 tokens beat 1536 of 256-341
+// by 6-9 %.  So: the largest split count that keeps the grid within one round, preferably one that divides the
+// list into multiples of 128 tokens; never below AT_SPLIT tokens per split.  One extra split at the end takes
+// whatever lies beyond list_len (the dense tail of a sparse call under the vector-ALU kernel).
 struct attn_geom { int nsplit, split_tokens, nsel; };
 static attn_geom attn_geometry(const as_params* p, int64_t list_len, int impl) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (list_len < 1) list_len = 1;
   int64_t pairs = (int64_t)p->batch * p->n_kv_heads * (impl == 0 ? (G + 15) / 16 : G / attn_gh(G));
   if (pairs < 1) pairs = 1;
-  int64_t nsel = (1536 + pairs - 1) / pairs;
+  int64_t nsel = 768 / pairs;
   const int64_t max_sel = (list_len + AT_SPLIT - 1) / AT_SPLIT;
   if (nsel > max_sel) nsel = max_sel;
   if (nsel < 1) nsel = 1;
+  const int64_t units = list_len / 128;           // a split of whole units gives every wavefront the same steps
+  for (int64_t d = nsel; d >= 1 && d * pairs >= 384; --d)
+    if (units > 0 && units % d == 0 && list_len % 128 == 0) {
+      nsel = d;
+      break;
+    }
   int64_t split_tokens = (list_len + nsel - 1) / nsel;
   split_tokens = (split_tokens + AT_CHUNK - 1) / AT_CHUNK * AT_CHUNK;
   if (split_tokens < AT_SPLIT) split_tokens = AT_SPLIT;
   attn_geom g;
   g.split_tokens = (int)split_tokens;
   g.nsplit = (int)((list_len + split_tokens - 1) / split_tokens) + 1;
-  g.nsel = (int)nsel;   // <= nsplit - 1
+  g.nsel = (int)nsel;
   return g;
 }
 
@@ -60,8 +69,9 @@ static attn_geom attn_geometry(const as_params* p, int64_t list_len, int impl) {
 size_t attn_workspace_bytes(const as_params* p) {
   const size_t heads = (size_t)p->batch * p->n_q_heads;
   size_t ns = (size_t)attn_nsplit(p->budget);
-  for (int impl = 0; impl < 2; ++impl) {
-    const size_t nd = (size_t)attn_geometry(p, (int64_t)p->max_pages_per_seq * AS_PAGE, impl).nsplit;
+  for (int impl = 0; impl < 2; ++impl) {   // the matrix-core kernel runs nsel splits, the vector-ALU one nsplit
+    const attn_geom gd = attn_geometry(p, (int64_t)p->max_pages_per_seq * AS_PAGE, impl);
+    const size_t nd = (size_t)(gd.nsplit > gd.nsel ? gd.nsplit : gd.nsel);
     if (nd > ns) ns = nd;
   }
   return heads * ns * (AS_HEAD_DIM + 2) * sizeof(float);
