@@ -1,0 +1,77 @@
+"""A seeded sweep over shapes and options that the hand-picked cases do not combine: window, group size, KV heads,
+batch, ragged lengths, budget, page-table kind, aggregation, predictor variant, sign of beta, ridge eps, a dense tail,
+single-layer against packed launches.  Every case runs predict -> select -> attend through the C ABI and is compared
+with the oracle: q_hat within tolerance, selections as sets with the tie band, attention over the GPU's own
+selection within the output tolerance, the log-sum-exp within 1e-3."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_07486_amd import api
+from paper_2510_07486_amd import workloads as wl
+from gpu_common import SCALE, f32, to_dev
+from helpers import compare_selection
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-2
+
+
+def draw_case(seed):
+    r = np.random.default_rng(seed)
+    hkv = int(r.choice([1, 2, 4, 8]))
+    group = int(r.choice([1, 2, 3, 4, 6, 8, 16, 24]))
+    ctx = int(r.choice([1, 17, 300, 1000, 2500, 5000, 9000]))
+    kw = dict(batch=int(r.integers(1, 6)), n_q_heads=hkv * group, n_kv_heads=hkv, window=int(r.integers(1, 21)),
+              budget=int(r.choice([1, 7, 64, 100, 333, 600, 2048])), ctx=ctx,
+              ctx_min=None if r.random() < 0.3 else int(r.integers(1, ctx + 1)),
+              page_table=str(r.choice(["identity", "permute", "scatter"])), pool_slack=1.0 + float(r.random()) * 0.5,
+              rho=float(r.choice([0.5, 0.9, 0.99])), n_outlier=int(r.choice([0, 4])), seed=int(seed))
+    opts = dict(agg=int(r.choice([0, 0, 1, 2])), single_solve=bool(r.random() < 0.25),
+                beta=float(r.choice([1.0, 1.0, -1.0])), eps=float(r.choice([1e-2, 1e-3, 1.0])),
+                tail=int(r.choice([0, 0, 1, 5])), n_layers=int(r.choice([1, 1, 2, 3])))
+    return kw, opts
+
+
+@pytest.mark.parametrize("seed", range(1000, 1028))
+def test_random_shape(seed):
+    kw, o = draw_case(seed)
+    print("random-shape", seed, kw, o, flush=True)
+    w = wl.Workload("rnd", **kw)
+    n_layers = o["n_layers"]
+    cpus = [wl.make_inputs(w, layer=l) for l in range(n_layers)]
+    devs = [to_dev(c) for c in cpus]
+    eps = f32(o["eps"])
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, cpus[0].max_pages, ridge_eps=eps,
+                        softmax_beta=o["beta"], sm_scale=f32(SCALE), agg=o["agg"],
+                        predictor=api.AS_PRED_SINGLE_SOLVE if o["single_solve"] else api.AS_PRED_PER_WINDOW)
+    ctx = api.Context(p, pack=n_layers)
+    kvs = [api.kv_view(d.k_pool, d.v_pool, d.block_table, d.ctx_lens) for d in devs]
+    B, Hkv, C = w.batch, w.n_kv_heads, w.budget
+    sel = [(torch.empty((B, Hkv, C), dtype=torch.int32, device="cuda"),
+            torch.empty((B, Hkv), dtype=torch.int32, device="cuda")) for _ in range(n_layers)]
+    if n_layers == 1:
+        api.as_select_step(ctx, p, kvs[0], devs[0].q_win, devs[0].q_cur, sel[0][0], sel[0][1])
+    else:
+        api.as_select_step_pack(ctx, p, [api.layer_io(kvs[l], devs[l].q_win, devs[l].q_cur, sel[l][0], sel[l][1])
+                                         for l in range(n_layers)])
+    torch.cuda.synchronize()
+    swaps = 0
+    for l, (c, d) in enumerate(zip(cpus, devs)):
+        q_hat, sc, ridx, rcnt = oracle.select_step(c.k_pool, c.block_table, c.ctx_lens, c.q_win, c.q_cur, C, eps,
+                                                   o["beta"], o["agg"], single_solve=o["single_solve"],
+                                                   sm_scale=f32(SCALE))
+        got_q = api.as_predict_query(ctx, p, d.q_win, d.q_cur).cpu()
+        assert (got_q - q_hat).abs().max().item() <= 2e-2
+        swaps += compare_selection(sel[l][0], sel[l][1], ridx, rcnt, sc, c.ctx_lens, C)
+        tail_lens = torch.clamp(c.ctx_lens - o["tail"], min=0) if o["tail"] else None
+        out, lse = api.as_sparse_decode_attn(ctx, p, kvs[l], d.q_real, sel[l][0], sel[l][1],
+                                             None if tail_lens is None else tail_lens.cuda())
+        ref, ref_lse = oracle.sparse_decode_attn(c.k_pool, c.v_pool, c.block_table, c.ctx_lens, c.q_real,
+                                                 sel[l][0].cpu(), sel[l][1].cpu(), f32(SCALE), sel_ctx_lens=tail_lens)
+        assert (out.cpu().float() - ref.float()).abs().max().item() <= OUT_TOL
+        both = torch.isfinite(ref_lse)
+        assert torch.equal(torch.isfinite(lse.cpu()), both)
+        assert (lse.cpu()[both] - ref_lse[both]).abs().max().item() <= 1e-3 if both.any() else True
+    print(f"  plan {api.select_plan(p, n_layers)}, tie swaps {swaps}", flush=True)
