@@ -141,3 +141,38 @@ def test_full_size_packed_selection_two_layers():
                                                 w.budget, eps)
         swaps = compare_selection(sel[l][0][b:b + 1], sel[l][1][b:b + 1], ridx, rcnt, rs, one.ctx_lens, w.budget)
         print(f"  layer {l} sequence {b}: tie swaps {swaps}", flush=True)
+
+
+def test_largest_batch_the_grids_allow():
+    """65535 sequences (the limit the header states), one KV head, one page each, lengths 0..16: every grid dimension that
+    carries the batch is at its maximum; the batch is also beyond the size up to which the selection kernel sorts
+    sequences by length.  Whole result against the oracle."""
+    B, C = 65535, 3
+    g = torch.Generator().manual_seed(5)
+    k = torch.randn((B, 1, 16, 128), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, 1, 16, 128), generator=g).to(torch.bfloat16)
+    bt = torch.randperm(B, generator=g).to(torch.int32).view(B, 1)
+    lens = torch.randint(0, 17, (B,), generator=g, dtype=torch.int32)
+    q_win = torch.randn((B, 1, 2, 128), generator=g).to(torch.bfloat16)
+    q_cur = torch.randn((B, 1, 128), generator=g).to(torch.bfloat16)
+    q_real = torch.randn((B, 1, 128), generator=g).to(torch.bfloat16)
+    eps = f32(1e-2)
+    p = api.make_params(B, 1, 1, 2, C, 1, ridge_eps=eps, sm_scale=f32(SCALE))
+    ctx = api.Context(p)
+    kv = api.kv_view(k.cuda(), v.cuda(), bt.cuda(), lens.cuda())
+    print("largest batch", B, "workspace MiB", api.as_workspace_bytes(p) >> 20, flush=True)
+    gidx, gcnt = api.as_select_step(ctx, p, kv, q_win.cuda(), q_cur.cuda())
+    out, lse = api.as_sparse_decode_attn(ctx, p, kv, q_real.cuda(), gidx, gcnt)
+    dense, _ = api.as_dense_decode_attn(ctx, p, kv, q_real.cuda())
+    torch.cuda.synchronize()
+    rq, rs, ridx, rcnt = oracle.select_step(k, bt, lens, q_win, q_cur, C, eps)
+    swaps = compare_selection(gidx, gcnt, ridx, rcnt, rs, lens, C)
+    ref, ref_lse = oracle.sparse_decode_attn(k, v, bt, lens, q_real, gidx.cpu(), gcnt.cpu(), f32(SCALE))
+    assert (out.cpu().float() - ref.float()).abs().max().item() <= 2e-2
+    full_idx = torch.arange(16, dtype=torch.int32).view(1, 1, 16).expand(B, 1, 16).contiguous()
+    ref_d, _ = oracle.sparse_decode_attn(k, v, bt, lens, q_real, full_idx, lens.view(B, 1).contiguous(), f32(SCALE))
+    assert (dense.cpu().float() - ref_d.float()).abs().max().item() <= 2e-2
+    fin = torch.isfinite(ref_lse)
+    assert torch.equal(torch.isfinite(lse.cpu()), fin) and (lse.cpu()[fin] - ref_lse[fin]).abs().max().item() <= 1e-3
+    assert ctx.damaged_workspace_gap(p) == -1
+    print(f"  tie swaps {swaps}", flush=True)
