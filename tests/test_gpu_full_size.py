@@ -174,5 +174,26 @@ def test_largest_batch_the_grids_allow():
     assert (dense.cpu().float() - ref_d.float()).abs().max().item() <= 2e-2
     fin = torch.isfinite(ref_lse)
     assert torch.equal(torch.isfinite(lse.cpu()), fin) and (lse.cpu()[fin] - ref_lse[fin]).abs().max().item() <= 1e-3
+    # the other entry points at the same batch: stand-alone stages, KV re-organisation, overlap ratio, state updates
+    q_hat = api.as_predict_query(ctx, p, q_win.cuda(), q_cur.cuda())
+    sc = api.as_score_keys(ctx, p, kv, q_hat)
+    sidx, scnt = api.as_topk_select(ctx, p, sc, lens.cuda())
+    assert torch.equal(sidx, gidx) and torch.equal(scnt, gcnt)
+    k_out, v_out, tab, ln = api.as_gather_kv(ctx, p, kv, gidx, gcnt)
+    rk, rv, rtab, rln = oracle.gather_kv(k, v, bt, gidx.cpu(), gcnt.cpu())
+    assert torch.equal(tab.cpu(), rtab) and torch.equal(ln.cpu(), rln)
+    for b in (0, 1, 30000, B - 1):
+        n = int(rln[b])
+        assert torch.equal(k_out[b, 0, :n].cpu(), rk[b, 0, :n]) and torch.equal(v_out[b, 0, :n].cpu(), rv[b, 0, :n])
+    inter, ratio = api.as_overlap_ratio(ctx, p, gidx, gcnt, sidx, scnt)
+    assert torch.equal(inter, gcnt)
+    lens_dev = lens.cuda()
+    kd, vd = k.cuda(), v.cuda()
+    api.as_kv_append(ctx, p, kd, vd, bt.cuda(), lens_dev, q_real.cuda(), q_real.cuda())
+    full = lens == 16
+    assert torch.equal(lens_dev.cpu(), torch.where(full, lens, lens + 1))
+    qw_dev, qc_dev = q_win.cuda(), q_cur.cuda()
+    api.as_window_push(ctx, p, qw_dev, qc_dev, q_real.cuda())
+    assert torch.equal(qc_dev.cpu(), q_real) and torch.equal(qw_dev[:, :, 1].cpu(), q_cur)
     assert ctx.damaged_workspace_gap(p) == -1
     print(f"  tie swaps {swaps}", flush=True)
