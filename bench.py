@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3", help="c1..c5 (BASELINE configs[0..4]); default c3 = Qwen3-8B shape, "
+    ap.add_argument("--workload", default="c3", help="c1..c5 (the five benchmark workloads); default c3 = Qwen3-8B shape, "
                     "batch 32, context 32768, budget 2048, 36 layers")
     ap.add_argument("--layers", type=int, default=0, help="resident layers (0 = the workload's own count)")
     ap.add_argument("--budget", type=int, default=0)

@@ -55,7 +55,7 @@ class Workload:
         return self.n_q_heads // self.n_kv_heads
 
 
-# BASELINE configs (index = position in BASELINE.json "configs").
+# The five benchmark workloads, c1..c5.
 CONFIGS = {
     "c1": Workload("c1", 1, 8, 2, 8, 256, 4096, rho=0.9, page_table="identity"),
     "c2": Workload("c2", 1, 32, 8, 16, 2048, 16384, n_outlier=4, page_table="identity"),

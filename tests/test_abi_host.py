@@ -52,8 +52,8 @@ def test_workspace_bytes_and_param_validation():
 def test_pack_workspace_and_share_plan():
     """Host logic of the depth-wise packed selection: workspace sizes and the share plan."""
     L = api.lib()
-    small = api.make_params(1, 8, 2, 8, 256, 256)          # BASELINE configs[0] shape
-    big = api.make_params(32, 32, 8, 16, 2048, 2048)       # configs[2] shape
+    small = api.make_params(1, 8, 2, 8, 256, 256)          # workload c1 shape
+    big = api.make_params(32, 32, 8, 16, 2048, 2048)       # workload c3 shape
     assert api.as_workspace_bytes_pack(small, 1) == api.as_workspace_bytes(small)
     assert api.as_workspace_bytes_pack(small, 0) == 0
     assert api.as_workspace_bytes_pack(small, api.AS_MAX_PACK + 1) == 0

@@ -143,7 +143,7 @@ def test_gather_kv_bit_exact_and_dense_attention_over_the_compact_pool(kw):
 @pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("kw", [
     dict(batch=3, n_q_heads=8, n_kv_heads=2, ctx=2000, ctx_min=1),
-    dict(batch=1, n_q_heads=32, n_kv_heads=8, ctx=16384),                            # configs[1] shape, full context
+    dict(batch=1, n_q_heads=32, n_kv_heads=8, ctx=16384),                            # workload c2 shape, full context
     dict(batch=5, n_q_heads=64, n_kv_heads=8, ctx=700, ctx_min=300),                 # group of 8
     dict(batch=2, n_q_heads=40, n_kv_heads=1, ctx=1500, ctx_min=700),                # MQA, three head blocks
 ])

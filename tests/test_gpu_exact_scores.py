@@ -73,7 +73,7 @@ def test_exact_scores_match_oracle_bit_for_bit(pattern, shape):
 @pytest.mark.parametrize("pattern", ["strict_ascending", "strict_descending", "plateaus"])
 @pytest.mark.parametrize("C", [2048, 4096])
 def test_single_share_long_rows_worst_case_orders(pattern, C):
-    """256 rows of 32768 tokens (one share per row, the launch shape of BASELINE configs[2]) with exact scores
+    """256 rows of 32768 tokens (one share per row, the launch shape of workload c3) with exact scores
     256*a + b: strictly increasing scores make every token a candidate and force a prune whenever the buffer
     fills; strictly decreasing ones stop the inflow after the first prune; plateaus of 3000 equal scores put the
     threshold inside a tie, which only the token order can resolve."""

@@ -1,4 +1,4 @@
-"""Parity at BASELINE's full sizes, in the launch configuration bench.py times: one layer of c3 / c4 / c5 is
+"""Parity at the benchmark workloads' full sizes, in the launch configuration bench.py times: one layer of c3 / c4 / c5 is
 generated on the device, the HIP path runs on the whole batch, and sampled sequences are copied to the host and
 checked against the oracle one by one (selection sets with the tie band, q_hat and attention within 2e-2)."""
 import numpy as np
@@ -119,7 +119,7 @@ def test_block_table_too_wide_for_a_share_plan_runs_the_stages():
 
 
 def test_full_size_packed_selection_two_layers():
-    """BASELINE configs[2] at full size, two layers in one as_select_step_pack call (512 rows of 32768 tokens in one
+    """Workload c3 at full size, two layers in one as_select_step_pack call (512 rows of 32768 tokens in one
     grid): every row equals the single-layer call bit for bit, and one sampled sequence per layer equals the oracle."""
     w = wl.scaled(wl.CONFIGS["c3"], layers=1)
     eps = f32(1e-2)

@@ -67,7 +67,7 @@ def test_pack_multi_share_rows_and_per_layer_tables():
 
 
 def test_pack_c2_shape_pack_of_four():
-    # Qwen3-8B head shape at batch 1 (BASELINE configs[1]), context 16384, four layers in one launch
+    # Qwen3-8B head shape at batch 1 (workload c2), context 16384, four layers in one launch
     run_pack(wl.CONFIGS["c2"], 4)
 
 
