@@ -30,6 +30,7 @@ __host__ __device__ inline int attn_nsplit(int C) { return (C + AT_SPLIT - 1) / 
 static inline int attn_gh(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 
 static int g_attn_impl = 0;  // 0: matrix-core kernel (attn_mfma.hip), 1: vector-ALU kernel below
+static int g_attn_splits = 0; // development knob: > 0 forces the number of splits per (sequence, KV head)
 
 // Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head).  Measured on the
 // matrix-core kernel (32/8 and 64/8 heads, budgets 1024-4096): what counts is that all workgroups are resident at
@@ -54,6 +55,7 @@ static attn_geom attn_geometry(const as_params* p, int64_t list_len, int impl) {
       nsel = d;
       break;
     }
+  if (g_attn_splits > 0) nsel = g_attn_splits < max_sel ? g_attn_splits : max_sel;
   int64_t split_tokens = (list_len + nsel - 1) / nsel;
   split_tokens = (split_tokens + AT_CHUNK - 1) / AT_CHUNK * AT_CHUNK;
   if (split_tokens < AT_SPLIT) split_tokens = AT_SPLIT;
@@ -371,6 +373,8 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
                             int nsplit, int list_len, hipStream_t s);
 
 extern "C" void as_debug_set_attn_impl(int v) { g_attn_impl = v; }   // development knob
+// development knob for split-count sweeps; set it before the context is created (the workspace is sized from it)
+extern "C" void as_debug_set_attn_splits(int n) { g_attn_splits = n > 0 ? n : 0; }
 
 // sel_idx == nullptr: dense attention over [0, ctx_lens[b]) (the token list is only the "tail", from 0)
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
