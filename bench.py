@@ -45,12 +45,145 @@ def parse():
     ap.add_argument("--cpu-sample-seqs", type=int, default=4)
     ap.add_argument("--serial-only", action="store_true")
     ap.add_argument("--sel-streams", type=int, default=2, help="selection streams (layers round-robin over them)")
-    ap.add_argument("--slice-threads", type=int, default=0, help="development: 512 or 1024-thread selection workgroups")
     ap.add_argument("--unfused", action="store_true", help="score and top-k as separate kernels through HBM scores")
     ap.add_argument("--graph", action="store_true", help="time the overlapped schedule as HIP graph replays (two graphs, "
                     "one per selection buffer parity) instead of eager launches")
     ap.add_argument("--pack", type=int, default=1, help="layers per packed selection launch (as_select_step_pack)")
+    ap.add_argument("--probe", default="", choices=["", "traffic", "attn-splits"],
+                    help="instead of the benchmark: 'traffic' launches the calibration kernels and every kernel of the "
+                         "path a few times on one layer (the program rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs on); "
+                         "'attn-splits' sweeps the forced attention split count (--splits)")
+    ap.add_argument("--splits", default="0,1,2,3,4,6,8,12,16", help="split counts of --probe attn-splits (0 = the rule)")
+    ap.add_argument("--reps", type=int, default=3, help="launches per kernel of --probe traffic")
     return ap.parse_args()
+
+
+def probe_traffic(a, torch, api, wl):
+    """One layer of the workload; per kernel, `reps` launches whose per-dispatch FETCH_SIZE / WRITE_SIZE a
+    rocprofv3 --pmc run records: (1) the two calibration kernels, whose bytes are known exactly (the paged walk
+    with one word written per token; the flat front-to-back read of the K pool), (2) the fused scoring + top-k,
+    (3) sparse decode attention, (4) the KV re-organisation followed by dense attention over the compact pool."""
+    w = wl.CONFIGS[a.workload]
+    dev = "cuda"
+    inp = wl.make_inputs(w, dev)
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, a.budget or w.budget, inp.max_pages)
+    ctx = api.Context(p)
+    kv = api.kv_view(inp.k_pool, inp.v_pool, inp.block_table, inp.ctx_lens)
+    q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur)
+    sink = torch.empty((w.batch, w.n_kv_heads, inp.max_pages * 16), dtype=torch.float32, device=dev)
+    for _ in range(a.reps):
+        api.stream_read_paged(ctx, p, kv, sink, True)
+    torch.cuda.synchronize()
+    for _ in range(a.reps):
+        api.stream_read_flat(ctx, inp.k_pool)
+    torch.cuda.synchronize()
+    for _ in range(a.reps):
+        idx, cnt = api.as_score_topk(ctx, p, kv, q_hat)
+    torch.cuda.synchronize()
+    for _ in range(a.reps):
+        api.as_sparse_decode_attn(ctx, p, kv, inp.q_real, idx, cnt, want_lse=False)
+    torch.cuda.synchronize()
+    comp = None
+    for _ in range(a.reps):
+        comp = api.as_gather_kv(ctx, p, kv, idx, cnt, *(comp or ()))
+    torch.cuda.synchronize()
+    pc = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, 16, api.compact_pages(p))
+    ctx_c = api.Context(pc)
+    kvc = api.kv_view(*comp)
+    for _ in range(a.reps):
+        api.as_dense_decode_attn(ctx_c, pc, kvc, inp.q_real, want_lse=False)
+    torch.cuda.synchronize()
+    tokens = int(inp.ctx_lens.sum())
+    print(json.dumps({"probe": "traffic", "workload": a.workload, "csrc_sha16": csrc_sha16(),
+                      "stream_read_paged_true": {"read_bytes": tokens * w.n_kv_heads * 256,
+                                                 "written_bytes": tokens * w.n_kv_heads * 4},
+                      "stream_read_flat": {"read_bytes": inp.k_pool.numel() * 2},
+                      "score_topk_algorithmic_read_bytes": tokens * w.n_kv_heads * 256,
+                      "sparse_attn_algorithmic_read_bytes":
+                          int(torch.clamp(inp.ctx_lens, max=p.budget).sum()) * w.n_kv_heads * 512}))
+
+
+def probe_attn_splits(a, torch, api, wl):
+    """Time of as_sparse_decode_attn per forced number of splits per (sequence, KV head) (a per-ctx development
+    knob; 0 = the library's rule).  The selection attended over is made once with as_select_step; four copies of
+    the layer are rotated so that rows come from HBM."""
+    w = wl.CONFIGS[a.workload]
+    if a.budget:
+        w = wl.scaled(w, budget=a.budget)
+    dev = torch.device("cuda:0")
+    lens_cpu = wl.draw_ctx_lens(w)
+    bt_cpu, num_pages = wl.make_page_table(w, lens_cpu)
+    copies = [wl.make_kv(w, num_pages, dev, l) for l in range(4)]
+    qw, qc, qr = wl.make_queries(w, dev, 0)
+    bt, lens = bt_cpu.to(dev), lens_cpu.to(dev)
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1])
+    kvs = [api.kv_view(k, v, bt, lens) for k, v in copies]
+    idx, cnt = api.as_select_step(api.Context(p), p, kvs[0], qw, qc)
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    rows = int(torch.clamp(lens_cpu, max=w.budget).sum()) * w.n_kv_heads
+    print(f"{a.workload}: {w.batch * w.n_kv_heads} (sequence, KV head) pairs, budget {w.budget}")
+    for n in [int(x) for x in a.splits.split(",")]:
+        ctx = api.Context(p, workspace_bytes=max(api.as_workspace_bytes_attn(p), api.attn_workspace_bytes_forced(p, n)))
+        ctx.set_attn_splits(n)
+        for i in range(4):
+            api.as_sparse_decode_attn(ctx, p, kvs[i % 4], qr, idx, cnt, out=out, want_lse=False)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 40
+        e0.record()
+        for i in range(reps):
+            api.as_sparse_decode_attn(ctx, p, kvs[i % 4], qr, idx, cnt, out=out, want_lse=False)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        label = "library's rule" if n == 0 else f"{n} splits = {n * w.batch * w.n_kv_heads} workgroups"
+        print(f"  {label:36s} {us:7.1f} us  {rows * 512 / us / 1e3:7.0f} GB/s", flush=True)
+
+
+def csrc_sha16():
+    """Fingerprint of the kernel sources the library is built from: stored byte counts (profiles/traffic.json) are
+    reported only while it matches."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2510_07486_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+TIE_REL = 1e-3      # half-width of the band around the last kept score inside which a swap is counted, not failed
+OUT_TOL = 2e-2      # max-abs bound on predicted queries and attention outputs
+
+
+def selection_parity(gidx, gcnt, ridx, rcnt, scores, lens):
+    """Compares the timed path's selection with the oracle's, row by row.  Returns (rows compared, tie swaps, rows
+    that differ outside the tie band): a difference counts as a swap only if every token of the symmetric difference
+    has an oracle score within TIE_REL of the oracle's last kept score."""
+    import numpy as np
+    gidx, gcnt, ridx, rcnt, scores = (t.cpu().numpy() for t in (gidx, gcnt, ridx, rcnt, scores))
+    rows = swaps = bad = 0
+    for b in range(ridx.shape[0]):
+        for j in range(ridx.shape[1]):
+            rows += 1
+            c = int(rcnt[b, j])
+            if int(gcnt[b, j]) != c or c != min(ridx.shape[2], int(lens[b])) or (gidx[b, j, c:] != -1).any():
+                bad += 1
+                continue
+            gs, rs = gidx[b, j, :c], ridx[b, j, :c]
+            if (gs == rs).all():
+                continue
+            if c and ((np.diff(gs) <= 0).any() or gs[0] < 0 or gs[-1] >= int(lens[b])):
+                bad += 1
+                continue
+            tau = scores[b, j, rs].min()
+            diff = np.setxor1d(gs, rs)
+            if (np.abs(scores[b, j, diff] - tau) > TIE_REL * max(abs(float(tau)), 1e-30)).any():
+                bad += 1
+            else:
+                swaps += len(diff) // 2
+    return rows, swaps, bad
 
 
 def main():
@@ -67,10 +200,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     api.lib()                                       # fails loudly if the HIP library is not built
-    if a.slice_threads:
-        api.lib().as_debug_set_slice_threads(a.slice_threads)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+    if a.probe:
+        {"traffic": probe_traffic, "attn-splits": probe_attn_splits}[a.probe](a, torch, api, wl)
+        return
 
     w = wl.CONFIGS[a.workload]
     if a.budget:
@@ -204,11 +338,18 @@ def main():
     achieved = k_bytes / (score_ms * 1e-3) / 1e9
     step_roofline_us = (k_bytes + kv_gather) / (HBM_PEAK_GBS * 1e9) * 1e6
 
-    traffic = None
+    # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs of `--probe traffic` (FETCH_SIZE and
+    # WRITE_SIZE, each scaled by what the same counter reads for the calibration kernel).  Counters cannot be read
+    # inside this process; the stored figure is reported only while the kernel sources are the ones it was measured on.
+    traffic, traffic_note = None, "no stored measurement for this workload"
     tf = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tf):
         try:
-            traffic = json.load(open(tf)).get(a.workload, {}).get("score_keys_hbm_bytes_per_launch")
+            tj = json.load(open(tf)).get(a.workload, {})
+            if tj.get("csrc_sha16") == csrc_sha16():
+                traffic, traffic_note = tj.get("score_keys_hbm_bytes_per_launch"), tj.get("source")
+            elif tj:
+                traffic_note = "stored measurement predates the current kernel sources"
         except Exception:
             traffic = None
 
@@ -232,7 +373,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "score_keys + topk_select (stand-alone kernels)" if a.unfused else ("as_score_topk (select_slice_kernel [+ select_merge_kernel]; few-row shapes: the stand-alone kernels)"
                                                               if pack == 1 else
                                                               "as_select_step_pack (predict + slice [+ merge] kernels)"), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_note,
                      "algorithmic_bytes_per_launch": k_bytes, "avg_launch_ms": round(score_ms, 4),
                      "launch_ms_p10_median_p90": [round(float(x) / (pack if pack > 1 else 1), 4)
                                                   for x in np.percentile(score_ms_serial, [10, 50, 90])],
@@ -287,18 +428,26 @@ def main():
         standalone = {"as_score_keys_us": round(t_sk, 1), "as_topk_select_us": round(t_tk, 1),
                       "as_score_keys_gbs": round(tokens * Hkv * 256 / (t_sk * 1e-6) / 1e9, 1)}
         # what this access pattern can reach at all: the calibration kernel walks the same pages with the same
-        # coalesced loads and does nothing else (one word written per wavefront), rotating over the resident layers
-        ctx_att.set_score_variant(2)
+        # coalesced loads and does nothing else (one word written per wavefront), rotating over the resident layers;
+        # and what the chip gives a plain read: the same layers' K pools front to back, no page table
         rot = [0]
 
         def stream_only():
-            api.as_score_keys(ctx_att, p, kvs[rot[0] % resident], q_hat0, sc_buf)
+            api.stream_read_paged(ctx_att, p, kvs[rot[0] % resident], sc_buf, False)
             rot[0] += 1
 
-        t_rd = avg_us(stream_only, max(5, min(resident, 12)))
-        ctx_att.set_score_variant(0)
+        flat_sink = torch.empty((api.lib().as_debug_stream_read_flat_sink_words(),), dtype=torch.int32, device=dev)
+
+        def flat_only():
+            api.stream_read_flat(ctx_att, layers[rot[0] % resident]["k"], flat_sink)
+            rot[0] += 1
+
+        nrep = max(5, min(resident, 12))
+        t_rd = avg_us(stream_only, nrep)
+        t_fl = avg_us(flat_only, nrep)
         ceiling = tokens * Hkv * 256 / (t_rd * 1e-6) / 1e9
         res["streaming_read_ceiling_gbs"] = round(ceiling, 1)
+        res["flat_read_ceiling_gbs"] = round(layers[0]["k"].numel() * 2 / (t_fl * 1e-6) / 1e9, 1)
         res["score_keys_pct_of_streaming_ceiling"] = round(100 * achieved / ceiling, 1) if a.agg != 2 else None
         del sc_buf
     res["context"] = {
@@ -332,6 +481,26 @@ def main():
             res["cpu_baseline"] = {"value": round(cpu_s / reps * 1e6, 1), "unit": "us/layer-step", "cores": nthreads,
                                    "kind": "oracle", "sample": f"all {B} sequences of one layer (full context), "
                                    f"{reps} passes, {cpu_s:.1f} s measured; per pass = one layer-step"}
+            # parity of the timed path on the benchmark's own inputs: layer 0's selections (both buffers the timed
+            # schedule left behind), predicted queries and attention output against the oracle, every row
+            g_qhat = api.as_predict_query(ctx_att, p, L0["qw"], L0["qc"])
+            rows = swaps = bad = 0
+            for parity in range(2):
+                r_, s_, b_ = selection_parity(pipe.sel[parity][0][0], pipe.sel[parity][0][1], ridx, rcnt, sc,
+                                              ctx_lens_cpu)
+                rows, swaps, bad = rows + r_, swaps + s_, bad + b_
+            g_out, g_lse = api.as_sparse_decode_attn(ctx_att, p, kvs[0], L0["qr"], pipe.sel[0][0][0], pipe.sel[0][0][1])
+            torch.cuda.synchronize()
+            r_out, r_lse = oracle.sparse_decode_attn(ck, cv, bt_cpu, ctx_lens_cpu, cqr, pipe.sel[0][0][0].cpu(),
+                                                     pipe.sel[0][0][1].cpu(), scale)
+            fin = torch.isfinite(r_lse)
+            parity_obj = {"layer": 0, "rows_compared": rows, "tie_swaps": swaps, "rows_outside_tie_band": bad,
+                          "q_hat_max_abs_err": float((g_qhat.cpu() - q_h).abs().max()),
+                          "attn_out_max_abs_err": float((g_out.cpu().float() - r_out.float()).abs().max()),
+                          "attn_lse_max_abs_err": float((g_lse.cpu()[fin] - r_lse[fin]).abs().max()) if fin.any() else 0.0,
+                          "tolerance": {"tie_band_rel": TIE_REL, "max_abs": OUT_TOL},
+                          "against": "CPU oracle, all sequences of layer 0 (selection buffers of the timed schedule)"}
+            res["parity"] = parity_obj
             if cpu_s / reps * nthreads < a.cpu_seconds:     # one more pass on a single thread, if it stays bounded
                 oracle.set_threads(1)
                 t1 = time.perf_counter()
@@ -360,6 +529,11 @@ def main():
         except (OSError, StopIteration):
             pass
     print(json.dumps(res))
+    par = res.get("parity")
+    if par and (par["rows_outside_tie_band"] or par["q_hat_max_abs_err"] > OUT_TOL or
+                par["attn_out_max_abs_err"] > OUT_TOL or par["attn_lse_max_abs_err"] > 1e-3):
+        print(f"bench.py: the timed path disagrees with the oracle: {par}", file=sys.stderr)
+        sys.exit(4)
 
 
 if __name__ == "__main__":

@@ -27,7 +27,8 @@
  *     validated on the host before any launch: AS_ERR_INVALID_ARG for null pointers,
  *     non-positive sizes, n_q_heads % n_kv_heads != 0, ridge_eps <= 0;
  *     AS_ERR_UNSUPPORTED for head_dim != 128, page_size != 16, window > 64, group > 64,
- *     budget > 65536, and for as_select_step_pack and the softmax-normalised aggregation when
+ *     budget > 65536, batch or n_kv_heads > 65535, batch * n_kv_heads > 2^31 - 1,
+ *     n_kv_heads * ceil(group / 16) > 65535, a block table of more than 2^25 tokens per sequence, and for as_select_step_pack and the softmax-normalised aggregation when
  *     budget > 4096 is combined with a block table of more than 8 million tokens per sequence
  *     (as_score_topk and as_select_step then run the stand-alone stages);
  *     AS_ERR_WORKSPACE if the ctx workspace is too small for the call.
@@ -45,6 +46,14 @@
 
 #ifdef __cplusplus
 extern "C" {
+#endif
+
+/* The library is built with hidden visibility; only the entry points declared here (and in
+ * asyncspade_debug.h) are exported. */
+#if defined(AS_BUILDING_LIBRARY)
+#define AS_API __attribute__((visibility("default")))
+#else
+#define AS_API
 #endif
 
 typedef struct as_ctx as_ctx; /* opaque: device id + scratch workspace */
@@ -95,16 +104,21 @@ typedef struct {            /* caller-owned device memory, never freed by the li
   int64_t num_pages;
 } as_kv_view;
 
-/* Bytes of ctx workspace that every call with these parameters fits in
- * (as_select_step's q_hat + score rows, and the attention split partials). */
-size_t as_workspace_bytes(const as_params* p);
+/* Bytes of ctx workspace that every call with these parameters fits in (the attention split
+ * partials, then as_select_step's q_hat, score rows and per-share candidates).  The longest
+ * context is bounded by p->max_pages_per_seq, so no separate context length is passed.
+ * as_workspace_bytes_attn is the leading part of that layout that as_sparse_decode_attn and
+ * as_dense_decode_attn need: a ctx that only ever attends can be created with just that.
+ * Both return 0 for parameters the library rejects. */
+AS_API size_t as_workspace_bytes(const as_params* p);
+AS_API size_t as_workspace_bytes_attn(const as_params* p);
 
 /* Creates a ctx on `device` with a workspace of `workspace_bytes` (hipMalloc).  as_destroy frees it
  * (hipFree): like any allocation call, neither belongs inside an open stream capture, and work that
  * still uses the workspace must have finished.  Every other call only enqueues kernels. */
-as_status as_create(as_ctx** out, int device, size_t workspace_bytes);
-as_status as_destroy(as_ctx* ctx);
-const char* as_status_str(as_status s);
+AS_API as_status as_create(as_ctx** out, int device, size_t workspace_bytes);
+AS_API as_status as_destroy(as_ctx* ctx);
+AS_API const char* as_status_str(as_status s);
 
 /*
  * Query predictor (Sec. 4.2, Eq. 2-5).  For every (b, h): for each window size k = 1..W
@@ -115,7 +129,7 @@ const char* as_status_str(as_status s);
  *   q_cur  bf16 [B][Hq][128]     (Q_t: regression target and newest shifted element)
  *   q_hat  fp32 [B][Hq][128]     out
  */
-as_status as_predict_query(as_ctx* ctx, const as_params* p, const void* q_win, const void* q_cur,
+AS_API as_status as_predict_query(as_ctx* ctx, const as_params* p, const void* q_win, const void* q_cur,
                            float* q_hat, void* stream);
 
 /*
@@ -124,7 +138,7 @@ as_status as_predict_query(as_ctx* ctx, const as_params* p, const void* q_win, c
  * fp32, with -0 written as +0.  Entries n >= ctx_lens[b] are left untouched.
  *   scores fp32 [B][Hkv][score_stride], score_stride >= 16 * max_pages_per_seq
  */
-as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
+AS_API as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
                         float* scores, int64_t score_stride, void* stream);
 
 /*
@@ -133,7 +147,7 @@ as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
  *   sel_idx int32 [B][Hkv][C]  ascending token indices, padded with -1
  *   sel_cnt int32 [B][Hkv]
  */
-as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, int64_t score_stride,
+AS_API as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, int64_t score_stride,
                          const int32_t* ctx_lens, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
 /*
@@ -146,7 +160,7 @@ as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, i
  * Empty S gives out = 0, lse = -inf.
  *   q    bf16 [B][Hq][128];  out bf16 [B][Hq][128];  lse nullable fp32 [B][Hq]
  */
-as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q,
+AS_API as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q,
                                 const int32_t* sel_idx, const int32_t* sel_cnt,
                                 const int32_t* sel_ctx_lens, void* out, float* lse, void* stream);
 
@@ -157,7 +171,7 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
  * precision as as_sparse_decode_attn; the work is split over the longest context the block
  * table allows (16 * max_pages_per_seq).
  */
-as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
+AS_API as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
                                float* lse, void* stream);
 
 /*
@@ -170,7 +184,7 @@ as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view
  * call runs the two stand-alone kernels over score rows in the ctx workspace instead; the
  * result is the same.
  */
-as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
+AS_API as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
                         int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
 /*
@@ -179,7 +193,7 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
  * the paper's Cache Rank does per layer (Sec. 4.1, Sec. 4.3); run it on its own stream
  * to overlap it with another layer's attention.
  */
-as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win,
+AS_API as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win,
                          const void* q_cur, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
 /*
@@ -202,8 +216,8 @@ typedef struct {
   int32_t* sel_idx;    /* int32 [B][Hkv][C] out             */
   int32_t* sel_cnt;    /* int32 [B][Hkv]    out             */
 } as_layer_io;
-size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers);
-as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io* layers, int32_t n_layers,
+AS_API size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers);
+AS_API as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io* layers, int32_t n_layers,
                               void* stream);
 
 /*
@@ -221,9 +235,9 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
  * as_window_push: q_win loses its oldest entry, the previous q_cur becomes its newest entry and
  * q_new becomes q_cur (all in place; q_new may not alias q_cur).
  */
-as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
+AS_API as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
                        int32_t* ctx_lens, int64_t num_pages, const void* k_new, const void* v_new, void* stream);
-as_status as_window_push(as_ctx* ctx, const as_params* p, void* q_win, void* q_cur, const void* q_new,
+AS_API as_status as_window_push(as_ctx* ctx, const as_params* p, void* q_win, void* q_cur, const void* q_new,
                          void* stream);
 
 /*
@@ -236,7 +250,7 @@ as_status as_window_push(as_ctx* ctx, const as_params* p, void* q_win, void* q_c
  * view, with max_pages_per_seq = Cp, is attention over exactly the selected tokens.
  *   k_out, v_out bf16 [B * Cp][Hkv][16][128];  out_table int32 [B][Cp];  out_lens int32 [B]
  */
-as_status as_gather_kv(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const int32_t* sel_idx,
+AS_API as_status as_gather_kv(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const int32_t* sel_idx,
                        const int32_t* sel_cnt, void* k_out, void* v_out, int32_t* out_table, int32_t* out_lens,
                        void* stream);
 
@@ -247,7 +261,7 @@ as_status as_gather_kv(as_ctx* ctx, const as_params* p, const as_kv_view* kv, co
  *   idx_a, idx_b int32 [B][Hkv][C]; cnt_a, cnt_b int32 [B][Hkv]
  *   inter int32 [B][Hkv] out; ratio nullable fp32 [B][Hkv] out
  */
-as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a, const int32_t* cnt_a,
+AS_API as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a, const int32_t* cnt_a,
                            const int32_t* idx_b, const int32_t* cnt_b, int32_t* inter, float* ratio,
                            void* stream);
 

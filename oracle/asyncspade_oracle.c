@@ -151,6 +151,12 @@ int aso_predict_query(int B, int Hq, int W, int D, const uint16_t* q_win, const 
     double* om = (double*)malloc(sizeof(double) * W);
     double* w = (double*)malloc(sizeof(double) * W);
     double* acc = (double*)calloc(D, sizeof(double));
+    if (!R || !S || !T || !om || !w || !acc) {     /* out of memory: report, do not dereference */
+#pragma omp atomic write
+      fail = 1;
+      free(R); free(S); free(T); free(om); free(w); free(acc);
+      continue;
+    }
     const uint16_t* win = q_win + (size_t)bh * W * D;
     const uint16_t* cur = q_cur + (size_t)bh * D;
     for (int d = 0; d < D; ++d) T[d] = bf16_to_f64(cur[d]);
@@ -210,6 +216,12 @@ int aso_predict_query_single_solve(int B, int Hq, int W, int D, const uint16_t* 
     double* om = (double*)malloc(sizeof(double) * W);
     double* w = (double*)malloc(sizeof(double) * W);
     double* acc = (double*)calloc(D, sizeof(double));
+    if (!R || !S || !T || !om || !w || !acc) {     /* out of memory: report, do not dereference */
+#pragma omp atomic write
+      fail = 1;
+      free(R); free(S); free(T); free(om); free(w); free(acc);
+      continue;
+    }
     const uint16_t* win = q_win + (size_t)bh * W * D;
     const uint16_t* cur = q_cur + (size_t)bh * D;
     for (int d = 0; d < D; ++d) T[d] = bf16_to_f64(cur[d]);
@@ -299,6 +311,7 @@ int aso_score_keys_softmax_sum(int B, int Hq, int Hkv, int D, int P, const uint1
                                const float* q_hat, double scale, float* scores, int64_t stride) {
   if (Hkv <= 0 || Hq % Hkv != 0) return -1;
   int G = Hq / Hkv;
+  int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j) {
@@ -306,6 +319,12 @@ int aso_score_keys_softmax_sum(int B, int Hq, int Hkv, int D, int P, const uint1
       if (N <= 0) continue;
       double* logit = (double*)malloc(sizeof(double) * (size_t)N * G);
       double* lse = (double*)malloc(sizeof(double) * G);
+      if (!logit || !lse) {               /* out of memory: report, do not dereference */
+#pragma omp atomic write
+        fail = 1;
+        free(logit); free(lse);
+        continue;
+      }
       for (int g = 0; g < G; ++g) {
         const float* q = q_hat + ((size_t)b * Hq + (size_t)j * G + g) * D;
         double m = -INFINITY;
@@ -327,7 +346,7 @@ int aso_score_keys_softmax_sum(int B, int Hq, int Hkv, int D, int P, const uint1
       }
       free(logit); free(lse);
     }
-  return 0;
+  return fail ? -2 : 0;
 }
 
 typedef struct { float s; int32_t n; } aso_cand;
@@ -356,6 +375,7 @@ static int int_cmp(const void* pa, const void* pb) {
 int aso_topk_select(int B, int Hkv, int C, const float* scores, int64_t stride,
                     const int32_t* ctx_lens, int32_t* sel_idx, int32_t* sel_cnt) {
   if (C < 1) return -1;
+  int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j) {
@@ -363,6 +383,11 @@ int aso_topk_select(int B, int Hkv, int C, const float* scores, int64_t stride,
       const float* s = scores + ((size_t)b * Hkv + j) * stride;
       int32_t* out = sel_idx + ((size_t)b * Hkv + j) * C;
       aso_cand* c = (aso_cand*)malloc(sizeof(aso_cand) * (N > 0 ? N : 1));
+      if (!c) {                           /* out of memory: report, do not dereference */
+#pragma omp atomic write
+        fail = 1;
+        continue;
+      }
       for (int n = 0; n < N; ++n) { c[n].s = s[n]; c[n].n = n; }
       qsort(c, N, sizeof(aso_cand), cand_cmp);
       int keep = N < C ? N : C;
@@ -372,7 +397,7 @@ int aso_topk_select(int B, int Hkv, int C, const float* scores, int64_t stride,
       sel_cnt[(size_t)b * Hkv + j] = keep;
       free(c);
     }
-  return 0;
+  return fail ? -2 : 0;
 }
 
 /*
@@ -389,6 +414,7 @@ int aso_sparse_decode_attn(int B, int Hq, int Hkv, int D, int P, int C, const ui
                            uint16_t* out, float* lse) {
   if (Hkv <= 0 || Hq % Hkv != 0) return -1;
   int G = Hq / Hkv;
+  int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int b = 0; b < B; ++b)
     for (int h = 0; h < Hq; ++h) {
@@ -408,6 +434,12 @@ int aso_sparse_decode_attn(int B, int Hq, int Hkv, int D, int P, int C, const ui
       int32_t* toks = (int32_t*)malloc(sizeof(int32_t) * L);
       double* logit = (double*)malloc(sizeof(double) * L);
       double* acc = (double*)calloc(D, sizeof(double));
+      if (!toks || !logit || !acc) {      /* out of memory: report, do not dereference */
+#pragma omp atomic write
+        fail = 1;
+        free(toks); free(logit); free(acc);
+        continue;
+      }
       for (int i = 0; i < cnt; ++i) toks[i] = sel_idx[((size_t)b * Hkv + j) * C + i];
       for (int n = tail0; n < N; ++n) toks[cnt + (n - tail0)] = n;
       const uint16_t* qr = q + ((size_t)b * Hq + h) * D;
@@ -430,7 +462,7 @@ int aso_sparse_decode_attn(int B, int Hq, int Hkv, int D, int P, int C, const ui
       if (lse) lse[(size_t)b * Hq + h] = (float)(m + log(z));
       free(toks); free(logit); free(acc);
     }
-  return 0;
+  return fail ? -2 : 0;
 }
 
 /*

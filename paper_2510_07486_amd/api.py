@@ -19,10 +19,14 @@ _lib = None
 
 AS_AGG_MAX, AS_AGG_SUM, AS_AGG_SOFTMAX_SUM = 0, 1, 2
 AS_PRED_PER_WINDOW, AS_PRED_SINGLE_SOLVE = 0, 1
-EXPORTS = ["as_workspace_bytes", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
+EXPORTS = ["as_workspace_bytes", "as_workspace_bytes_attn", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
            "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",
            "as_select_step_pack", "as_kv_append", "as_window_push", "as_gather_kv", "as_overlap_ratio",
            "as_dense_decode_attn"]
+# development / measurement entry points (include/asyncspade_debug.h)
+DEBUG_EXPORTS = ["as_debug_select_plan", "as_debug_workspace_gaps", "as_debug_set_select_mode",
+                 "as_debug_set_attn_splits", "as_debug_attn_workspace_bytes", "as_debug_stream_read_paged",
+                 "as_debug_stream_read_flat", "as_debug_stream_read_flat_sink_words"]
 AS_MAX_PACK = 16
 
 
@@ -59,6 +63,8 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.as_workspace_bytes.restype = C.c_size_t
         L.as_workspace_bytes.argtypes = [C.POINTER(AsParams)]
+        L.as_workspace_bytes_attn.restype = C.c_size_t
+        L.as_workspace_bytes_attn.argtypes = [C.POINTER(AsParams)]
         L.as_create.restype = C.c_int
         L.as_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_size_t]
         L.as_destroy.restype = C.c_int
@@ -94,13 +100,21 @@ def lib():
         L.as_overlap_ratio.restype = C.c_int
         L.as_overlap_ratio.argtypes = [vp, PP, vp, vp, vp, vp, vp, vp, vp]
         L.as_debug_select_plan.restype = C.c_int
-        L.as_debug_select_plan.argtypes = [PP, C.c_int, C.POINTER(C.c_int32)]
-        L.as_debug_set_score_variant.restype = C.c_int
-        L.as_debug_set_score_variant.argtypes = [vp, C.c_int]
+        L.as_debug_select_plan.argtypes = [PP, C.c_int32, C.POINTER(C.c_int32)]
         L.as_debug_workspace_gaps.restype = C.c_int
-        L.as_debug_workspace_gaps.argtypes = [vp, PP, C.c_int, C.POINTER(C.c_int32)]
+        L.as_debug_workspace_gaps.argtypes = [vp, PP, C.c_int32, C.POINTER(C.c_int32)]
         L.as_debug_set_select_mode.restype = C.c_int
-        L.as_debug_set_select_mode.argtypes = [vp, C.c_int]
+        L.as_debug_set_select_mode.argtypes = [vp, C.c_int32]
+        L.as_debug_set_attn_splits.restype = C.c_int
+        L.as_debug_set_attn_splits.argtypes = [vp, C.c_int32]
+        L.as_debug_attn_workspace_bytes.restype = C.c_size_t
+        L.as_debug_attn_workspace_bytes.argtypes = [PP, C.c_int32]
+        L.as_debug_stream_read_paged.restype = C.c_int
+        L.as_debug_stream_read_paged.argtypes = [vp, PP, KP, vp, C.c_int64, C.c_int32, vp]
+        L.as_debug_stream_read_flat.restype = C.c_int
+        L.as_debug_stream_read_flat.argtypes = [vp, vp, C.c_size_t, vp, vp]
+        L.as_debug_stream_read_flat_sink_words.restype = C.c_size_t
+        L.as_debug_stream_read_flat_sink_words.argtypes = []
         _lib = L
     return _lib
 
@@ -154,6 +168,11 @@ def as_workspace_bytes_pack(p: AsParams, n_layers: int) -> int:
     return int(lib().as_workspace_bytes_pack(C.byref(p), n_layers))
 
 
+def as_workspace_bytes_attn(p: AsParams) -> int:
+    """Leading part of the workspace that the attention calls need (a ctx that only attends)."""
+    return int(lib().as_workspace_bytes_attn(C.byref(p)))
+
+
 class Context:
     """Owns one as_ctx (device workspace).  One per concurrently used stream."""
 
@@ -183,12 +202,34 @@ class Context:
         _check(lib().as_debug_workspace_gaps(self.handle, C.byref(p), n_layers, C.byref(bad)), "as_debug_workspace_gaps")
         return bad.value
 
-    def set_score_variant(self, v: int):
-        _check(lib().as_debug_set_score_variant(self.handle, v), "as_debug_set_score_variant")
-
     def set_select_mode(self, m: int):
         """0 = as_select_step fuses scoring with top-k (default), 1 = separate kernels through HBM scores."""
         _check(lib().as_debug_set_select_mode(self.handle, m), "as_debug_set_select_mode")
+
+    def set_attn_splits(self, n: int):
+        """Forces the attention split count of this ctx (0 = the library's rule); the workspace must have been sized
+        with attn_workspace_bytes_forced for the largest count used."""
+        _check(lib().as_debug_set_attn_splits(self.handle, n), "as_debug_set_attn_splits")
+
+
+def attn_workspace_bytes_forced(p: AsParams, splits: int) -> int:
+    return int(lib().as_debug_attn_workspace_bytes(C.byref(p), splits))
+
+
+def stream_read_paged(ctx: Context, p: AsParams, kv: AsKvView, sink, words_per_token: bool, stream=None):
+    """Calibration kernel: the scoring kernels' paged walk over K with no arithmetic; sink fp32 [B][Hkv][stride]."""
+    _check(lib().as_debug_stream_read_paged(ctx.handle, C.byref(p), C.byref(kv), _ptr(sink), sink.shape[2],
+                                            1 if words_per_token else 0, _stream(stream)), "as_debug_stream_read_paged")
+
+
+def stream_read_flat(ctx: Context, buf, sink=None, stream=None):
+    """Calibration kernel: plain front-to-back 128-bit read of the tensor `buf` (no page table)."""
+    if sink is None:
+        sink = torch.empty((lib().as_debug_stream_read_flat_sink_words(),), dtype=torch.int32, device=buf.device)
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().as_debug_stream_read_flat(ctx.handle, _ptr(buf), nbytes - nbytes % 16, _ptr(sink), _stream(stream)),
+           "as_debug_stream_read_flat")
+    return sink
 
 
 def as_predict_query(ctx: Context, p: AsParams, q_win, q_cur, q_hat=None, stream=None):

@@ -31,7 +31,7 @@ def build(verbose: bool = True) -> str:
     """Compiles every source to an object (in parallel, always from scratch) and links the shared library."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-DAS_BUILDING_LIBRARY",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
              "-fno-gpu-sanitize", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     os.makedirs(OBJ, exist_ok=True)
@@ -39,7 +39,8 @@ def build(verbose: bool = True) -> str:
     jobs = [[hipcc] + flags + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
     with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
         list(ex.map(lambda c: _run(c, verbose), jobs))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize", "-o", LIB] + objs, verbose)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize",
+          "-Wl,--version-script=" + os.path.join(CSRC, "exports.map"), "-o", LIB] + objs, verbose)
     # a plain-C caller of the ABI: C99 host code through gcc, linked against the library and the HIP runtime
     _run(["gcc", "-std=c99", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
           "-I", "/opt/rocm/include", os.path.join(CSRC, "abi_demo.c"), "-o", DEMO, "-L", HERE, "-lasyncspade",

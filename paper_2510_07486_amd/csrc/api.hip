@@ -12,26 +12,29 @@ constexpr size_t WS_GAP = 256;          // never written by a kernel: separates 
 constexpr unsigned char WS_FILL = 0xA5;  // what as_create fills the workspace with
 
 struct ws_layout {
-  size_t q_hat, q_hat_layer, scores, cand, attn, total;
-  size_t gap[4];   // offsets of the gaps behind q_hat, scores, candidates, attention partials
+  size_t attn, q_hat, q_hat_layer, scores, cand, total;
+  size_t attn_end;   // what the attention calls need: the attention region and the gap behind it
+  size_t gap[4];     // offsets of the gaps behind the attention partials, q_hat, the score rows, the candidates
   int64_t score_stride;
 };
 
-// n_layers > 1: the layout of a packed selection (one q_hat block per layer, candidates of the
-// whole pack); the single-layer layout also holds the score rows of the unfused path.
-ws_layout layout_of(const as_params* p, int n_layers = 1) {
+// The attention partials come first, so that a ctx that only attends needs nothing else.  n_layers > 1: the
+// layout of a packed selection (one q_hat block per layer, candidates of the whole pack); the single-layer
+// layout also holds the score rows of the unfused path.  attn_splits: the forced split count of the ctx (0 = rule).
+ws_layout layout_of(const as_params* p, int n_layers = 1, int attn_splits = 0) {
   ws_layout l;
   l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  l.q_hat = 0;
+  l.attn = 0;
+  l.gap[0] = l.attn + align_up(asx::attn_workspace_bytes(p, attn_splits));
+  l.attn_end = l.gap[0] + WS_GAP;
+  l.q_hat = l.attn_end;
   l.q_hat_layer = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
-  l.gap[0] = l.q_hat + l.q_hat_layer * n_layers;
-  l.scores = l.gap[0] + WS_GAP;
+  l.gap[1] = l.q_hat + l.q_hat_layer * n_layers;
+  l.scores = l.gap[1] + WS_GAP;
   size_t sc = n_layers > 1 ? 0 : align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
-  l.gap[1] = l.scores + sc;
-  l.cand = l.gap[1] + WS_GAP;
-  l.gap[2] = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
-  l.attn = l.gap[2] + WS_GAP;
-  l.gap[3] = l.attn + align_up(asx::attn_workspace_bytes(p));
+  l.gap[2] = l.scores + sc;
+  l.cand = l.gap[2] + WS_GAP;
+  l.gap[3] = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
   l.total = l.gap[3] + WS_GAP;
   return l;
 }
@@ -48,7 +51,9 @@ as_status check_params(const as_params* p) {
   if (p->head_dim != AS_HEAD_DIM || p->page_size != AS_PAGE) return AS_ERR_UNSUPPORTED;
   if (p->window > AS_MAX_WINDOW || p->budget > AS_MAX_BUDGET) return AS_ERR_UNSUPPORTED;
   if (p->n_q_heads / p->n_kv_heads > AS_MAX_GROUP) return AS_ERR_UNSUPPORTED;
-  if (p->batch > 65535 || p->n_kv_heads > 65535) return AS_ERR_UNSUPPORTED;
+  if (p->batch > 65535 || p->n_kv_heads > 65535) return AS_ERR_UNSUPPORTED;                 // grid dimensions
+  if ((int64_t)p->batch * p->n_kv_heads > 0x7fffffffLL) return AS_ERR_UNSUPPORTED;          // rows are grid.x of the top-k
+  if ((int64_t)p->n_kv_heads * ((p->n_q_heads / p->n_kv_heads + 15) / 16) > 65535) return AS_ERR_UNSUPPORTED;  // grid.y of attention
   if ((int64_t)p->max_pages_per_seq * AS_PAGE > (int64_t)1 << 25) return AS_ERR_UNSUPPORTED;
   return AS_OK;
 }
@@ -74,9 +79,9 @@ bool use_stages(const as_ctx* ctx, const as_params* p) {
   return ctx->select_mode == 1 || asx::select_prefers_stages(p);
 }
 
-hipError_t score_then_topk(const as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
-                           float* scores, int64_t stride, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
-  const hipError_t e = asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, stride, s);
+hipError_t score_then_topk(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
+                           int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+  const hipError_t e = asx::launch_score(p, kv, q_hat, scores, stride, s);
   if (e != hipSuccess) return e;
   return asx::launch_topk(p, scores, stride, kv->ctx_lens, sel_idx, sel_cnt, s);
 }
@@ -90,6 +95,11 @@ size_t as_workspace_bytes(const as_params* p) {
   return layout_of(p).total;
 }
 
+size_t as_workspace_bytes_attn(const as_params* p) {
+  if (check_params(p) != AS_OK) return 0;
+  return layout_of(p).attn_end;
+}
+
 as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   if (!out) return AS_ERR_INVALID_ARG;
   *out = nullptr;
@@ -101,8 +111,8 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->device = device;
   c->ws = nullptr;
   c->ws_bytes = workspace_bytes;
-  c->score_variant = 0;
   c->select_mode = 0;
+  c->attn_splits = 0;
   if (workspace_bytes > 0) {
     if (hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
       delete c;
@@ -154,8 +164,7 @@ as_status as_score_keys(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (!ctx || !q_hat || !scores) return AS_ERR_INVALID_ARG;
   if (p->agg == AS_AGG_SOFTMAX_SUM) return AS_ERR_UNSUPPORTED;   // needs the row-wide normalisers: fused calls only
   if (score_stride < (int64_t)p->max_pages_per_seq * AS_PAGE) return AS_ERR_INVALID_ARG;
-  return hip_status(asx::launch_score(ctx->score_variant, p, kv, q_hat, scores, score_stride,
-                                      static_cast<hipStream_t>(stream)));
+  return hip_status(asx::launch_score(p, kv, q_hat, scores, score_stride, static_cast<hipStream_t>(stream)));
 }
 
 as_status as_topk_select(as_ctx* ctx, const as_params* p, const float* scores, int64_t score_stride,
@@ -175,11 +184,11 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, true)) != AS_OK) return st;
   if (!ctx || !q || !sel_idx || !sel_cnt || !out) return AS_ERR_INVALID_ARG;
-  const ws_layout l = layout_of(p);
-  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  const ws_layout l = layout_of(p, 1, ctx->attn_splits);
+  if (!ctx->ws || ctx->ws_bytes < l.attn_end) return AS_ERR_WORKSPACE;   // the attention region leads the layout
   return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), sel_idx, sel_cnt, sel_ctx_lens,
                                      static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
-                                     static_cast<hipStream_t>(stream)));
+                                     ctx->attn_splits, static_cast<hipStream_t>(stream)));
 }
 
 as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
@@ -188,11 +197,11 @@ as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view
   if (st != AS_OK) return st;
   if ((st = check_kv(kv, true)) != AS_OK) return st;
   if (!ctx || !q || !out) return AS_ERR_INVALID_ARG;
-  const ws_layout l = layout_of(p);
-  if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
+  const ws_layout l = layout_of(p, 1, ctx->attn_splits);
+  if (!ctx->ws || ctx->ws_bytes < l.attn_end) return AS_ERR_WORKSPACE;
   return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), nullptr, nullptr, nullptr,
                                      static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
-                                     static_cast<hipStream_t>(stream)));
+                                     ctx->attn_splits, static_cast<hipStream_t>(stream)));
 }
 
 as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat, int32_t* sel_idx,
@@ -203,13 +212,13 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
   if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
   const bool stages = use_stages(ctx, p);
-  const ws_layout l = layout_of(p);
+  const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
-  return hip_status(score_then_topk(ctx, p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
-                                    sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
+                                    sel_cnt, s));
 }
 
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
@@ -220,7 +229,7 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   if (!ctx || !q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
   if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
   const bool stages = use_stages(ctx, p);
-  const ws_layout l = layout_of(p);
+  const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   float* q_hat = reinterpret_cast<float*>(ws + l.q_hat);
@@ -229,8 +238,8 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
                                      q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
   if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
-  return hip_status(score_then_topk(ctx, p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
-                                    sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
+                                    sel_cnt, s));
 }
 
 size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers) {
@@ -249,7 +258,7 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     if (!layers[l].q_win || !layers[l].q_cur || !layers[l].sel_idx || !layers[l].sel_cnt) return AS_ERR_INVALID_ARG;
   }
   if (!asx::select_plan_ok(p, n_layers)) return AS_ERR_UNSUPPORTED;
-  const ws_layout lay = layout_of(p, n_layers);
+  const ws_layout lay = layout_of(p, n_layers, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < lay.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   asx::pred_tab pt = {};
@@ -316,16 +325,9 @@ as_status as_overlap_ratio(as_ctx* ctx, const as_params* p, const int32_t* idx_a
                                         static_cast<hipStream_t>(stream)));
 }
 
-// Development knobs (not part of the documented ABI): what as_score_keys launches (0: the scoring kernel,
-// 1 / 2: the streaming-read calibration kernel with / without one word written per token), and whether
-// single-layer selections fuse scoring with top-k (0: by the share plan, 1: never, 2: always).
-as_status as_debug_set_score_variant(as_ctx* ctx, int variant) {
-  if (!ctx) return AS_ERR_INVALID_ARG;
-  ctx->score_variant = variant;
-  return AS_OK;
-}
-// share plan of the fused selection for a pack of n_layers layers: out = {share length, shares per row, candidates per share}
-as_status as_debug_select_plan(const as_params* p, int n_layers, int32_t* out) {
+// ---- development and measurement entry points (asyncspade_debug.h) ----
+
+as_status as_debug_select_plan(const as_params* p, int32_t n_layers, int32_t* out) {
   if (check_params(p) != AS_OK || !out || n_layers < 1) return AS_ERR_INVALID_ARG;
   const asx::select_plan pl = asx::plan_select(p, n_layers);
   out[0] = pl.slice_len;
@@ -333,14 +335,11 @@ as_status as_debug_select_plan(const as_params* p, int n_layers, int32_t* out) {
   out[2] = pl.ccap;
   return AS_OK;
 }
-// Checks the gaps that separate the workspace regions of the layout for (p, n_layers): a kernel that wrote beyond
-// its region has overwritten the fill pattern there.  Synchronises the device.  *first_bad = -1 if every gap is
-// intact, else the index of the first damaged one (0 q_hat, 1 score rows, 2 candidates, 3 attention partials).
-// Only meaningful for a ctx that has been used with this one layout since as_create.
-as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int n_layers, int32_t* first_bad) {
+
+as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_layers, int32_t* first_bad) {
   if (!ctx || !first_bad || check_params(p) != AS_OK || n_layers < 1 || n_layers > AS_MAX_PACK)
     return AS_ERR_INVALID_ARG;
-  const ws_layout l = layout_of(p, n_layers);
+  const ws_layout l = layout_of(p, n_layers, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   if (hipDeviceSynchronize() != hipSuccess) return AS_ERR_HIP;
   *first_bad = -1;
@@ -356,10 +355,40 @@ as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int n_layers,
   }
   return AS_OK;
 }
-as_status as_debug_set_select_mode(as_ctx* ctx, int mode) {
-  if (!ctx) return AS_ERR_INVALID_ARG;
+
+as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode) {
+  if (!ctx || mode < 0 || mode > 2) return AS_ERR_INVALID_ARG;
   ctx->select_mode = mode;
   return AS_OK;
 }
+
+as_status as_debug_set_attn_splits(as_ctx* ctx, int32_t splits) {
+  if (!ctx || splits < 0) return AS_ERR_INVALID_ARG;
+  ctx->attn_splits = splits;
+  return AS_OK;
+}
+
+size_t as_debug_attn_workspace_bytes(const as_params* p, int32_t splits) {
+  if (check_params(p) != AS_OK || splits < 0) return 0;
+  return layout_of(p, 1, splits).attn_end;
+}
+
+as_status as_debug_stream_read_paged(as_ctx* ctx, const as_params* p, const as_kv_view* kv, float* sink,
+                                     int64_t stride, int32_t words_per_token, void* stream) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, false)) != AS_OK) return st;
+  if (!ctx || !sink) return AS_ERR_INVALID_ARG;
+  if (stride < (int64_t)p->max_pages_per_seq * AS_PAGE) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_stream_read_paged(p, kv, sink, stride, words_per_token != 0,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
+as_status as_debug_stream_read_flat(as_ctx* ctx, const void* buf, size_t nbytes, uint32_t* sink, void* stream) {
+  if (!ctx || !buf || !sink || nbytes % 16 != 0) return AS_ERR_INVALID_ARG;
+  return hip_status(asx::launch_stream_read_flat(buf, nbytes, sink, static_cast<hipStream_t>(stream)));
+}
+
+size_t as_debug_stream_read_flat_sink_words(void) { return asx::stream_read_flat_sink_words(); }
 
 }  // extern "C"

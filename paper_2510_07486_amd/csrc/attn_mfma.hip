@@ -1,8 +1,8 @@
 // Sparse decode attention on the matrix cores (Sec. 4.1; the 4*q*h*C term of Appendix B).
 //
-// The vector-ALU formulation (attn.hip) is issue-bound: about 75 instructions per gathered row
-// and head group of 4, twice that at group size 8, which caps it near 4 TB/s and 2.4 TB/s.
-// Here both contractions of a 32-token step run as v_mfma_f32_16x16x32_bf16 and the whole GQA
+// A vector-ALU formulation (v_dot2c_f32_bf16 + DPP reductions) is issue-bound: about 75 instructions
+// per gathered row and head group of 4, twice that at group size 8, which capped it near 4 TB/s and
+// 2.4 TB/s when it was measured.  Here both contractions of a 32-token step run as v_mfma_f32_16x16x32_bf16 and the whole GQA
 // group (up to 16 heads) shares every gathered row at no extra cost:
 //   S^T[token][head] = K_tile[16 x 128] * Q^T[128 x 16]     (two 16-token tiles, 4 MFMAs each)
 //   O[head][dim]    += P[16 x 32] * V[32 x 128]             (8 dim tiles, P split hi + lo)
@@ -66,9 +66,9 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
 
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt ? sel_cnt[b * Hkv + j] : 0;   // no selection arrays: dense attention over [0, N)
-  cnt = (cnt < 0 || N == 0) ? 0 : (cnt > C ? C : cnt);   // an empty sequence has nothing to select from
+  cnt = clamp_count(cnt, C, N);   // an empty sequence has nothing to select from
   int tail0 = sel_idx ? (sel_ctx_lens ? sel_ctx_lens[b] : N) : 0;
-  tail0 = tail0 < 0 ? 0 : (tail0 > N ? N : tail0);
+  tail0 = clamp_tail(tail0, N);
   const int L = cnt + (N - tail0);
   const int t_end = (split == nsplit - 1) ? L : (t_next < L ? t_next : L);
   const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G + g0) * nsplit + split;  // + g * nsplit per head
@@ -100,9 +100,9 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
     const int ti = step_token(step);
     int n = 0;
     if (ti < t_end) n = (ti < cnt) ? raw : tail0 + (ti - cnt);
-    n = n < 0 ? 0 : (n >= N ? N - 1 : n);                               // keeps a bad index inside the sequence
+    n = clamp_token(n, N);                                              // keeps a bad index inside the sequence
     int32_t pg = bt_row[n >> 4];
-    pg = pg < 0 ? 0 : (pg > last_page ? last_page : pg);                // a corrupt table must not leave the pool
+    pg = clamp_page(pg, last_page);                                     // a corrupt table must not leave the pool
     return ((uint32_t)pg << 4) | (uint32_t)(n & 15);
   };
 

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(uint16_t* __restrict__ k
   __syncthreads();
   if (n < 0 || n >= max_pages * AS_PAGE) return;      // no room (or a corrupt length): leave the sequence alone
   int32_t pg = block_table[(int64_t)b * max_pages + (n >> 4)];
-  pg = pg < 0 ? 0 : (pg > last_page ? last_page : pg);
+  pg = clamp_page(pg, last_page);
   const int c = tid & 15;
   for (int r = tid >> 4; r < 2 * Hkv; r += 16) {      // rows: K of head r / 2 when r is even, V when odd
     const int j = r >> 1;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   const int64_t row = (int64_t)b * Hkv + j;
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt[row];
-  cnt = (cnt < 0 || N == 0) ? 0 : (cnt > C ? C : cnt);   // an empty sequence has nothing to select from
+  cnt = clamp_count(cnt, C, N);   // an empty sequence has nothing to select from
   if (blockIdx.x == 0 && j == 0) {
     for (int i = tid; i < Cp; i += 256) out_table[(int64_t)b * Cp + i] = b * Cp + i;
     if (tid == 0) out_lens[b] = cnt;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   for (int e = 0; e < 4; ++e) {
     const int i = i0 + 16 * e;
     const int v = sel_idx[row * C + (i < cnt ? i : 0)];
-    n[e] = v < 0 ? 0 : (v >= N ? N - 1 : v);      // a bad index stays inside the sequence
+    n[e] = clamp_token(v, N);      // a bad index stays inside the sequence
   }
   int32_t pg[4];
 #pragma unroll
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   uint4 kr[4], vr[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const int32_t p = pg[e] < 0 ? 0 : (pg[e] > last_page ? last_page : pg[e]);
+    const int32_t p = clamp_page(pg[e], last_page);
     const int64_t off = chunk_offset(p, Hkv, j) + (int64_t)(n[e] & 15) * AS_HEAD_DIM + c * 8;
     const u32x4_c a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(k_pool + off));
     const u32x4_c d = __builtin_nontemporal_load(reinterpret_cast<const u32x4_c*>(v_pool + off));

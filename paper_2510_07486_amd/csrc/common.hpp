@@ -4,6 +4,8 @@
 #include <stdint.h>
 
 #include "asyncspade.h"
+#include "asyncspade_debug.h"
+#include "guards.hpp"
 
 #define AS_HEAD_DIM 128
 #define AS_PAGE 16
@@ -17,9 +19,9 @@ struct as_ctx {
   int device;
   void* ws;
   size_t ws_bytes;
-  int score_variant; /* 0: as_score_keys scores; 1, 2: it launches the streaming-read calibration kernel */
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
                         1: always the separate kernels via HBM scores, 2: always fused */
+  int attn_splits;   /* > 0: forced number of attention splits per (sequence, KV head) */
 };
 
 namespace asx {
@@ -34,12 +36,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
-}
-
-// context length as the kernels use it: a corrupt entry must not index past the block table
-__device__ __forceinline__ int clamp_ctx(int n, int max_pages) {
-  const int cap = max_pages * AS_PAGE;
-  return n < 0 ? 0 : (n > cap ? cap : n);
 }
 
 // element offset of token `slot` of (page, kv head j) in a [pages][Hkv][16][128] pool
@@ -70,8 +66,13 @@ struct sel_tab {
 hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab& tab, hipStream_t s);
 hipError_t launch_predict(const as_params* p, const uint16_t* q_win, const uint16_t* q_cur, float* q_hat,
                           hipStream_t s);
-hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
-                        int64_t stride, hipStream_t s);
+hipError_t launch_score(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
+                        hipStream_t s);
+// calibration kernels (score.hip): the paged walk of the scoring kernels, and a plain front-to-back read
+hipError_t launch_stream_read_paged(const as_params* p, const as_kv_view* kv, float* sink, int64_t stride,
+                                    bool words_per_token, hipStream_t s);
+hipError_t launch_stream_read_flat(const void* buf, size_t nbytes, uint32_t* sink, hipStream_t s);
+size_t stream_read_flat_sink_words();
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,
                        int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // fused scoring + top-k (select_fused.hip): rows are cut into slices of `slice_len` tokens
@@ -84,10 +85,11 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
                                int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // partial buffers live in the ctx workspace
-size_t attn_workspace_bytes(const as_params* p);
+// forced_splits > 0 overrides the split rule (development knob of a ctx)
+size_t attn_workspace_bytes(const as_params* p, int forced_splits);
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
-                       hipStream_t s);
+                       int forced_splits, hipStream_t s);
 
 // cache-side bookkeeping (cache_ops.hip)
 hipError_t launch_kv_append(const as_params* p, uint16_t* k_pool, uint16_t* v_pool, const int32_t* block_table,

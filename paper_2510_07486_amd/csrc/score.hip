@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
 
   int32_t my_page = 0;
   if (lane < ppw && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
-  my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
+  my_page = clamp_page(my_page, last_page);  // a corrupt table must not leave the pool
 
   bf16x8 aq[NSET][4];
   build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
@@ -89,10 +89,10 @@ __global__ __launch_bounds__(256) void score_mfma_lds(const uint16_t* __restrict
   }
 }
 
-// Calibration kernel (development variants 1 and 2 of as_score_keys): the same paged walk over K with fully
-// coalesced non-temporal loads and no arithmetic beyond an XOR fold.  WORDS = true writes one word per token
-// where the scores would go: a known-size reference for scaling profiler byte counters.  WORDS = false writes
-// one word per wavefront: the streaming-read rate this access pattern can reach at all.
+// Calibration kernels (as_debug_stream_read_paged / _flat): the same paged walk over K with fully coalesced
+// non-temporal loads and no arithmetic beyond an XOR fold.  WORDS = true writes one word per token where the
+// scores would go: a known-size reference for scaling profiler byte counters.  WORDS = false writes one word
+// per wavefront: the streaming-read rate this access pattern can reach at all.
 template <bool WORDS>
 __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restrict__ k_pool,
                                                          const int32_t* __restrict__ block_table,
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restr
   if (pw >= npages) return;
   int32_t my_page = 0;
   if (lane < ppw && pw + lane < npages) my_page = block_table[(int64_t)b * max_pages + pw + lane];
-  my_page = my_page < 0 ? 0 : (my_page > last_page ? last_page : my_page);  // a corrupt table must not leave the pool
+  my_page = clamp_page(my_page, last_page);  // a corrupt table must not leave the pool
   float* srow = scores + ((int64_t)b * Hkv + j) * stride;
   uint32_t fold = 0;
 #pragma unroll 1
@@ -142,37 +142,87 @@ __global__ __launch_bounds__(256) void stream_read_paged(const uint16_t* __restr
   }
 }
 
-hipError_t launch_score(int variant, const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
-                        int64_t stride, hipStream_t s) {
-  if (p->batch == 0 || p->max_pages_per_seq == 0) return hipSuccess;
-  const int G = p->n_q_heads / p->n_kv_heads;
-  const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
-  // pages per wavefront: as many as leave about eight workgroups per compute unit, so that the prologue (the
-  // query operand, the page ids) is spread over up to 2048 tokens per workgroup on large batches and small
-  // batches still fill the chip
+// The plain streaming read: a buffer of n16 16-byte words read front to back, no page table.  Each workgroup
+// takes FLAT_TILE contiguous bytes per round (a wavefront load covers 1 KB, sixteen loads in flight per lane)
+// and the workgroups stride over the buffer; one word written per workgroup.
+static constexpr int FLAT_WGS = 2048;                 // workgroups of the flat read (8 per compute unit)
+static constexpr int FLAT_U = 16;                     // 16-byte loads in flight per lane
+static constexpr int64_t FLAT_TILE = 256 * FLAT_U;    // 16-byte words per workgroup and round (64 KB)
+__global__ __launch_bounds__(256) void stream_read_flat(const uint4* __restrict__ buf, int64_t n16,
+                                                        uint32_t* __restrict__ sink) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  uint32_t fold = 0;
+  for (int64_t base = (int64_t)blockIdx.x * FLAT_TILE; base < n16; base += (int64_t)gridDim.x * FLAT_TILE) {
+    uint4 v[FLAT_U];
+    const int64_t w0 = base + (int64_t)wave * (64 * FLAT_U) + lane;   // a wave owns 16 KB of the tile
+#pragma unroll
+    for (int u = 0; u < FLAT_U; ++u) {
+      const int64_t i = w0 + u * 64;
+      v[u] = ld16<true>(buf + (i < n16 ? i : n16 - 1));   // the ragged end re-reads the last word
+    }
+#pragma unroll
+    for (int u = 0; u < FLAT_U; ++u) fold ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) fold ^= (uint32_t)__shfl_xor((int)fold, o);
+  __shared__ uint32_t part[4];
+  if (lane == 0) part[wave] = fold;
+  __syncthreads();
+  if (tid == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+// pages per wavefront: as many as leave about eight workgroups per compute unit, so that the prologue (the
+// query operand, the page ids) is spread over up to 2048 tokens per workgroup on large batches and small
+// batches still fill the chip
+static int pages_per_wave(const as_params* p) {
   int ppw = 32;
   while (ppw > 8 && (int64_t)p->batch * p->n_kv_heads * ((p->max_pages_per_seq + 4 * ppw - 1) / (4 * ppw)) < 2048)
     ppw /= 2;
+  return ppw;
+}
+
+hipError_t launch_score(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
+                        hipStream_t s) {
+  if (p->batch == 0 || p->max_pages_per_seq == 0) return hipSuccess;
+  const int G = p->n_q_heads / p->n_kv_heads;
+  const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
+  const int ppw = pages_per_wave(p);
   dim3 grid((p->max_pages_per_seq + 4 * ppw - 1) / (4 * ppw), p->n_kv_heads, p->batch);
   const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
 #define AS_SCORE_LAUNCH(KERNEL)                                                                              \
   hipLaunchKernelGGL(KERNEL, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, q_hat, scores, stride, \
                      p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, last_page, ppw)
-  if (variant == 1 || variant == 2) {
-    if (variant == 1)
-      hipLaunchKernelGGL(stream_read_paged<true>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                         stride, p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
-    else
-      hipLaunchKernelGGL(stream_read_paged<false>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, scores,
-                         stride, p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
-    return hipGetLastError();
-  }
   // operand sets of eight heads each: one up to 8 heads per KV head, two up to 16, four or eight for MQA-sized groups
   if (p->agg == AS_AGG_SUM || G <= 8) AS_SCORE_LAUNCH(score_mfma_lds<1>);
   else if (G <= 16) AS_SCORE_LAUNCH(score_mfma_lds<2>);
   else if (G <= 32) AS_SCORE_LAUNCH(score_mfma_lds<4>);
   else AS_SCORE_LAUNCH(score_mfma_lds<8>);
 #undef AS_SCORE_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_stream_read_paged(const as_params* p, const as_kv_view* kv, float* sink, int64_t stride,
+                                    bool words_per_token, hipStream_t s) {
+  if (p->batch == 0 || p->max_pages_per_seq == 0) return hipSuccess;
+  const uint16_t* kp = reinterpret_cast<const uint16_t*>(kv->k_pool);
+  const int ppw = pages_per_wave(p);
+  dim3 grid((p->max_pages_per_seq + 4 * ppw - 1) / (4 * ppw), p->n_kv_heads, p->batch);
+  const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
+  if (words_per_token)
+    hipLaunchKernelGGL(stream_read_paged<true>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, sink, stride,
+                       p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
+  else
+    hipLaunchKernelGGL(stream_read_paged<false>, grid, dim3(256), 0, s, kp, kv->block_table, kv->ctx_lens, sink, stride,
+                       p->n_kv_heads, p->max_pages_per_seq, last_page, ppw);
+  return hipGetLastError();
+}
+
+size_t stream_read_flat_sink_words() { return FLAT_WGS; }
+
+hipError_t launch_stream_read_flat(const void* buf, size_t nbytes, uint32_t* sink, hipStream_t s) {
+  const int64_t n16 = (int64_t)(nbytes / 16);
+  if (n16 == 0) return hipSuccess;
+  hipLaunchKernelGGL(stream_read_flat, dim3(FLAT_WGS), dim3(256), 0, s, reinterpret_cast<const uint4*>(buf), n16, sink);
   return hipGetLastError();
 }
 

@@ -41,8 +41,6 @@ template <int THREADS> struct fs_shape {
 };
 static constexpr int FS_PG = 2;             // pages a wave loads per iteration (8 KB in flight per wave)
 static constexpr int FS_MAX_SLICES = 1024;  // shares per row the merge kernel can index (one per thread)
-static int g_fs_threads = 1024;             // development knob: workgroup shape of the slice kernel
-extern "C" void as_debug_set_slice_threads(int t) { g_fs_threads = (t == 512) ? 512 : 1024; }
 
 static int device_cus() {
   static int cus = 0;
@@ -111,7 +109,7 @@ static select_plan plan_for(const as_params* p, int thr, int n_layers) {
 // of the 512-thread shape (two waves per SIMD).
 static int slice_threads_for(const as_params* p) {
   const int G = p->n_q_heads / p->n_kv_heads;
-  return (p->agg != AS_AGG_SUM && G > 16) ? 512 : g_fs_threads;
+  return (p->agg != AS_AGG_SUM && G > 16) ? 512 : 1024;
 }
 
 select_plan plan_select(const as_params* p, int n_layers) { return plan_for(p, slice_threads_for(p), n_layers); }
@@ -138,23 +136,18 @@ bool select_prefers_stages(const as_params* p) {
 // bytes of the candidate arrays (rows cut into several shares) and, behind them, of the per-share (max, sum)
 // pairs of the softmax-normalised aggregation
 static size_t cand_bytes(const as_params* p, const select_plan& pl, int n_layers) {
-  if (pl.nslices <= 1) return 0;
+  if (pl.nslices <= 1 || pl.nslices > FS_MAX_SLICES) return 0;   // one share per row, or no share plan at all
   const size_t rows = (size_t)p->batch * p->n_kv_heads * n_layers;
   return (rows * pl.nslices * ((size_t)pl.ccap * 8 + 4) + 15) / 16 * 16;
 }
 static size_t lse_bytes(const as_params* p, const select_plan& pl, int n_layers) {
-  if (p->agg != AS_AGG_SOFTMAX_SUM) return 0;
+  if (p->agg != AS_AGG_SOFTMAX_SUM || pl.nslices > FS_MAX_SLICES) return 0;
   return (size_t)p->batch * p->n_q_heads * n_layers * pl.nslices * sizeof(float2);
 }
 
 size_t select_workspace_bytes(const as_params* p, int n_layers) {
-  size_t best = 0;  // sized for either workgroup shape
-  for (int thr : {512, 1024}) {
-    const select_plan pl = plan_for(p, thr, n_layers);
-    const size_t b = cand_bytes(p, pl, n_layers) + lse_bytes(p, pl, n_layers);
-    if (b > best) best = b;
-  }
-  return best;
+  const select_plan pl = plan_select(p, n_layers);
+  return cand_bytes(p, pl, n_layers) + lse_bytes(p, pl, n_layers);
 }
 
 // MODE 0: scores are the max (or the pre-summed query's logit) over the group.  MODES 1 and 2 are the two passes
@@ -261,7 +254,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const int lp = ((lane / PG) * FS_WAVES + wave) * PG + (lane % PG);
     const int pi = pos / AS_PAGE + lp;
     const int32_t pg = pi < share_pages ? bt_row[real_page(pi)] : 0;
-    return pg < 0 ? 0 : (pg > last_page ? last_page : pg);   // a corrupt table must not leave the pool
+    return clamp_page(pg, last_page);   // a corrupt table must not leave the pool
   };
   int pos = 0;
   int32_t my_page = load_pages(0);
@@ -673,24 +666,17 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG, MODE_>), grid, dim3(THR_), 0, s, tab, p->batch,     \
                      p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices,      \
                      p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
+  // groups of up to 16 heads (one or two operand sets) run 1024-thread workgroups, larger ones the 512-thread shape
   if (p->agg == AS_AGG_SOFTMAX_SUM) {
     // two passes over K with the same grid: per-share (max, sum) pairs, then selection on the normalised scores
     if (nset == 8) { AS_SLICE_LAUNCH(8, 512, 1); AS_SLICE_LAUNCH(8, 512, 2); }
     else if (nset == 4) { AS_SLICE_LAUNCH(4, 512, 1); AS_SLICE_LAUNCH(4, 512, 2); }
-    else if (slice_threads_for(p) == 1024) {
-      if (nset == 2) { AS_SLICE_LAUNCH(2, 1024, 1); AS_SLICE_LAUNCH(2, 1024, 2); }
-      else { AS_SLICE_LAUNCH(1, 1024, 1); AS_SLICE_LAUNCH(1, 1024, 2); }
-    } else {
-      if (nset == 2) { AS_SLICE_LAUNCH(2, 512, 1); AS_SLICE_LAUNCH(2, 512, 2); }
-      else { AS_SLICE_LAUNCH(1, 512, 1); AS_SLICE_LAUNCH(1, 512, 2); }
-    }
-  } else if (nset > 2) {
-    if (nset == 4) AS_SLICE_LAUNCH(4, 512, 0); else AS_SLICE_LAUNCH(8, 512, 0);
-  } else if (slice_threads_for(p) == 1024) {
-    if (nset == 2) AS_SLICE_LAUNCH(2, 1024, 0); else AS_SLICE_LAUNCH(1, 1024, 0);
-  } else {
-    if (nset == 2) AS_SLICE_LAUNCH(2, 512, 0); else AS_SLICE_LAUNCH(1, 512, 0);
-  }
+    else if (nset == 2) { AS_SLICE_LAUNCH(2, 1024, 1); AS_SLICE_LAUNCH(2, 1024, 2); }
+    else { AS_SLICE_LAUNCH(1, 1024, 1); AS_SLICE_LAUNCH(1, 1024, 2); }
+  } else if (nset == 8) AS_SLICE_LAUNCH(8, 512, 0);
+  else if (nset == 4) AS_SLICE_LAUNCH(4, 512, 0);
+  else if (nset == 2) AS_SLICE_LAUNCH(2, 1024, 0);
+  else AS_SLICE_LAUNCH(1, 1024, 0);
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || pl.nslices == 1) return e;

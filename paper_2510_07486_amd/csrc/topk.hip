@@ -17,15 +17,16 @@ namespace asx {
 __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float* __restrict__ scores, int64_t stride,
                                                           const int32_t* __restrict__ ctx_lens,
                                                           int32_t* __restrict__ sel_idx,
-                                                          int32_t* __restrict__ sel_cnt, int Hkv, int C) {
+                                                          int32_t* __restrict__ sel_cnt, int Hkv, int C,
+                                                          int max_pages) {
   __shared__ uint32_t hist[TK_BINS];
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
 
   const int row = blockIdx.x;
   const int b = row / Hkv;
   const int tid = threadIdx.x;
-  int N = ctx_lens[b];
-  N = N < 0 ? 0 : ((int64_t)N > stride ? (int)stride : N);   // never past the score row
+  const int N = clamp_row(ctx_lens[b], max_pages, stride);   // never past the block table (what the scoring kernel
+                                                             // wrote) nor past the score row
   const float* s = scores + (int64_t)row * stride;
   int32_t* out = sel_idx + (int64_t)row * C;
   const int keep = N < C ? N : C;
@@ -48,7 +49,8 @@ template <int NPT>
 __global__ __launch_bounds__(TK_THREADS) void topk_regs_kernel(const float* __restrict__ scores, int64_t stride,
                                                                const int32_t* __restrict__ ctx_lens,
                                                                int32_t* __restrict__ sel_idx,
-                                                               int32_t* __restrict__ sel_cnt, int Hkv, int C) {
+                                                               int32_t* __restrict__ sel_cnt, int Hkv, int C,
+                                                               int max_pages) {
   constexpr int WORDS = NPT * TK_THREADS / 32;   // bitmap words, NPT per thread
   __shared__ uint32_t hist[TK_BINS];
   __shared__ uint32_t bitmap[WORDS];
@@ -57,8 +59,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_regs_kernel(const float* __re
   const int row = blockIdx.x;
   const int b = row / Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int N = ctx_lens[b];
-  N = N < 0 ? 0 : ((int64_t)N > stride ? (int)stride : N);
+  int N = clamp_row(ctx_lens[b], max_pages, stride);
   if (N > NPT * TK_THREADS) N = NPT * TK_THREADS;   // the host launches this kernel only when every row fits
   const float* s = scores + (int64_t)row * stride;
   int32_t* out = sel_idx + (int64_t)row * C;
@@ -122,20 +123,20 @@ __global__ __launch_bounds__(TK_THREADS) void topk_regs_kernel(const float* __re
 
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,
                        int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
-  const int rows = p->batch * p->n_kv_heads;
+  const int64_t rows = (int64_t)p->batch * p->n_kv_heads;   // <= 2^31 - 1 (checked with the parameters)
   if (rows == 0) return hipSuccess;
   // rows that fit 32 keys per thread are selected in registers; longer ones by the positional kernel
   const int64_t longest = (int64_t)p->max_pages_per_seq * AS_PAGE < stride ? (int64_t)p->max_pages_per_seq * AS_PAGE : stride;
 #define AS_TOPK_REGS(NPT_)                                                                                        \
-  hipLaunchKernelGGL(topk_regs_kernel<NPT_>, dim3(rows), dim3(TK_THREADS), 0, s, scores, stride, ctx_lens, sel_idx, \
-                     sel_cnt, p->n_kv_heads, p->budget)
+  hipLaunchKernelGGL(topk_regs_kernel<NPT_>, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, scores, stride, ctx_lens, \
+                     sel_idx, sel_cnt, p->n_kv_heads, p->budget, p->max_pages_per_seq)
   if (longest <= 4 * TK_THREADS) AS_TOPK_REGS(4);
   else if (longest <= 8 * TK_THREADS) AS_TOPK_REGS(8);
   else if (longest <= 16 * TK_THREADS) AS_TOPK_REGS(16);
   else if (longest <= 32 * TK_THREADS) AS_TOPK_REGS(32);
   else
-    hipLaunchKernelGGL(topk_kernel, dim3(rows), dim3(TK_THREADS), 0, s, scores, stride, ctx_lens, sel_idx, sel_cnt,
-                       p->n_kv_heads, p->budget);
+    hipLaunchKernelGGL(topk_kernel, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, scores, stride, ctx_lens, sel_idx,
+                       sel_cnt, p->n_kv_heads, p->budget, p->max_pages_per_seq);
 #undef AS_TOPK_REGS
   return hipGetLastError();
 }

@@ -11,25 +11,41 @@ from paper_2510_07486_amd import api
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    hdr = open(os.path.join(ROOT, "include", "asyncspade.h")).read()
+def declared_symbols(header="asyncspade.h"):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     return sorted(set(re.findall(r"\b(as_[a-z_]+)\s*\(", hdr)))
 
 
-def test_library_exports_every_declared_symbol():
+def exported_symbols():
+    """Every dynamic symbol the built library defines (nm -D)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", api.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    return sorted(ln.split()[-1] for ln in out.splitlines() if ln.strip())
+
+
+def test_library_exports_exactly_the_declared_symbols():
+    """Header and library agree in both directions: every declared entry point is exported, and nothing else is
+    (no internal C++ symbol, no kernel stub, no undeclared knob).  The method's calls live in asyncspade.h, the
+    development and measurement calls in asyncspade_debug.h."""
     L = api.lib()
     names = declared_symbols()
+    debug = declared_symbols("asyncspade_debug.h")
     assert set(api.EXPORTS) == set(names)
-    for n in names:
+    assert set(api.DEBUG_EXPORTS) == set(debug) and all(n.startswith("as_debug_") for n in debug)
+    for n in names + debug:
         assert getattr(L, n) is not None
+    assert exported_symbols() == sorted(names + debug)
 
 
 def test_workspace_bytes_and_param_validation():
     p = api.make_params(32, 32, 8, 16, 2048, 2048)
     n = api.as_workspace_bytes(p)
-    # q_hat + score rows + attention partials
-    assert n >= 32 * 32 * 128 * 4 + 32 * 8 * 32768 * 4 + 32 * 32 * 17 * 130 * 4
+    # q_hat + score rows + attention partials (at least two splits per row at this shape)
+    assert n >= 32 * 32 * 128 * 4 + 32 * 8 * 32768 * 4 + 32 * 32 * 2 * 130 * 4
+    # the attention calls need only the leading part of the layout
+    assert 32 * 32 * 2 * 130 * 4 <= api.as_workspace_bytes_attn(p) < n // 8
+    assert api.as_workspace_bytes_attn(api.make_params(1, 6, 4, 16, 64, 8)) == 0
     bad = api.make_params(1, 6, 4, 16, 64, 8)            # 6 % 4 != 0
     assert api.as_workspace_bytes(bad) == 0
     L = api.lib()
@@ -37,7 +53,10 @@ def test_workspace_bytes_and_param_validation():
     for kw, code in [(dict(n_q_heads=6, n_kv_heads=4), 1), (dict(ridge_eps=0.0), 1), (dict(window=0), 1),
                      (dict(budget=0), 1), (dict(head_dim=64), 2), (dict(page_size=32), 2), (dict(window=65), 2),
                      (dict(budget=65537), 2), (dict(n_q_heads=65, n_kv_heads=1), 2), (dict(agg=7), 1), (dict(agg=3), 1),
-                     (dict(predictor=2), 1)]:
+                     (dict(predictor=2), 1), (dict(batch=65536), 2), (dict(n_q_heads=65536, n_kv_heads=65536), 2),
+                     (dict(batch=65535, n_q_heads=65535, n_kv_heads=65535), 2),          # rows beyond 2^31 - 1
+                     (dict(n_q_heads=17 * 40000, n_kv_heads=40000), 2),                  # attention grid.y beyond 65535
+                     (dict(max_pages_per_seq=(1 << 25) // 16 + 1), 2)]:
         args = dict(batch=1, n_q_heads=8, n_kv_heads=2, window=4, budget=16, max_pages_per_seq=4)
         args.update(kw)
         q = api.make_params(**args)
@@ -72,6 +91,8 @@ def test_pack_workspace_and_share_plan():
     # a budget above half the candidate buffer forces buffer-sized shares: beyond 1024 of them per row there is no plan
     huge = api.make_params(1, 8, 2, 4, 5000, (1 << 25) // 16)
     assert api.select_plan(huge, 1)[1] > 1024
+    # ... and then no candidate arrays are sized from it: the workspace is the score rows plus small change
+    assert api.as_workspace_bytes(huge) < 2 * (1 << 25) * 4 + (8 << 20)
     # (single-layer calls then run the stand-alone stages; the softmax-normalised aggregation and packs, which
     # exist only in the fused kernels, are refused before anything touches the context or the device)
     huge_sm = api.make_params(1, 8, 2, 4, 5000, (1 << 25) // 16, agg=api.AS_AGG_SOFTMAX_SUM)

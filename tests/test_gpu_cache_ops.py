@@ -140,17 +140,16 @@ def test_gather_kv_bit_exact_and_dense_attention_over_the_compact_pool(kw):
     assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
 
 
-@pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("kw", [
     dict(batch=3, n_q_heads=8, n_kv_heads=2, ctx=2000, ctx_min=1),
     dict(batch=1, n_q_heads=32, n_kv_heads=8, ctx=16384),                            # workload c2 shape, full context
     dict(batch=5, n_q_heads=64, n_kv_heads=8, ctx=700, ctx_min=300),                 # group of 8
     dict(batch=2, n_q_heads=40, n_kv_heads=1, ctx=1500, ctx_min=700),                # MQA, three head blocks
 ])
-def test_dense_decode_attn_matches_oracle(kw, impl):
+def test_dense_decode_attn_matches_oracle(kw):
     """Full attention over the whole cache (the baseline of Appendix B) = the oracle's attention with an
-    empty selection and the dense tail starting at token 0; both kernels (matrix-core and vector-ALU)."""
-    note("dense", kw, impl)
+    empty selection and the dense tail starting at token 0."""
+    note("dense", kw)
     w = wl.Workload("da", window=4, budget=64, page_table="scatter", pool_slack=1.2, seed=23, **kw)
     cpu = wl.make_inputs(w)
     if w.batch > 1:
@@ -162,14 +161,10 @@ def test_dense_decode_attn_matches_oracle(kw, impl):
                                              torch.zeros((B, Hkv), dtype=torch.int32), f32(SCALE),
                                              torch.zeros((B,), dtype=torch.int32))
     p = params_for(cpu)
-    api.lib().as_debug_set_attn_impl(impl)
-    try:
-        ctx = api.Context(p)
-        out, lse = api.as_dense_decode_attn(ctx, p, api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens),
-                                            dev.q_real)
-        torch.cuda.synchronize()
-    finally:
-        api.lib().as_debug_set_attn_impl(0)
+    ctx = api.Context(p, workspace_bytes=api.as_workspace_bytes_attn(p))     # a ctx that only attends
+    out, lse = api.as_dense_decode_attn(ctx, p, api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens),
+                                        dev.q_real)
+    torch.cuda.synchronize()
     err = (out.cpu().float() - ref.float()).abs().max().item()
     note("  dense attn max abs err", err)
     assert err <= OUT_TOL
@@ -180,8 +175,10 @@ def test_dense_decode_attn_matches_oracle(kw, impl):
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 2), (6, 2)])
-def test_vector_alu_sparse_attention_kernel_matches_oracle(Hq, Hkv):
-    """The vector-ALU attention kernel kept behind the development switch, selection + own-token tail."""
+@pytest.mark.parametrize("splits", [0, 1, 3])
+def test_sparse_attention_with_tail_under_forced_split_counts(Hq, Hkv, splits):
+    """Selection + own-token tail, under the library's split rule and under forced split counts (the per-ctx
+    development knob): the result does not depend on how the token list is cut."""
     w = wl.Workload("va", 3, Hq, Hkv, 4, 300, 2000, ctx_min=100, page_table="scatter", pool_slack=1.2, seed=Hq)
     cpu = wl.make_inputs(w)
     dev = to_dev(cpu)
@@ -192,16 +189,22 @@ def test_vector_alu_sparse_attention_kernel_matches_oracle(Hq, Hkv):
     ref, ref_lse = oracle.sparse_decode_attn(cpu.k_pool, cpu.v_pool, cpu.block_table, cpu.ctx_lens, cpu.q_real, idx, cnt,
                                              f32(SCALE), lens_sel)
     p = params_for(cpu)
-    api.lib().as_debug_set_attn_impl(1)
-    try:
-        ctx = api.Context(p)
-        out, lse = api.as_sparse_decode_attn(ctx, p, api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens),
-                                             dev.q_real, idx.cuda(), cnt.cuda(), lens_sel.cuda())
-        torch.cuda.synchronize()
-    finally:
-        api.lib().as_debug_set_attn_impl(0)
+    ctx = api.Context(p, workspace_bytes=max(api.as_workspace_bytes_attn(p), api.attn_workspace_bytes_forced(p, splits)))
+    ctx.set_attn_splits(splits)
+    out, lse = api.as_sparse_decode_attn(ctx, p, api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens),
+                                         dev.q_real, idx.cuda(), cnt.cuda(), lens_sel.cuda())
+    torch.cuda.synchronize()
     assert (out.cpu().float() - ref.float()).abs().max().item() <= OUT_TOL
     assert (lse.cpu() - ref_lse).abs().max().item() <= 1e-3
+    if splits == 3:     # a forced count beyond what the workspace was sized for is refused, not overrun
+        small = api.Context(p, workspace_bytes=api.as_workspace_bytes_attn(p))
+        small.set_attn_splits(2)       # 300 tokens allow at most ceil(300 / 128) = 3 splits; the rule gives fewer rows
+        need = api.attn_workspace_bytes_forced(p, 2)
+        if need > small.workspace_bytes:
+            with pytest.raises(api.AsError) as e:
+                api.as_sparse_decode_attn(small, p, api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens),
+                                          dev.q_real, idx.cuda(), cnt.cuda(), lens_sel.cuda())
+            assert e.value.code == 3
 
 
 def test_decode_loop_append_attend_push_select():

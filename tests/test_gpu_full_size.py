@@ -1,6 +1,7 @@
 """Parity at the benchmark workloads' full sizes, in the launch configuration bench.py times: one layer of c3 / c4 / c5 is
-generated on the device, the HIP path runs on the whole batch, and sampled sequences are copied to the host and
-checked against the oracle one by one (selection sets with the tie band, q_hat and attention within 2e-2)."""
+generated on the device, the HIP path runs on the whole batch (selection on its own stream, attention on another,
+event hand-off), the layer is copied to the host and EVERY (sequence, KV head) row is checked against the oracle:
+selection sets with the tie band (swaps counted), q_hat and attention outputs within 2e-2, lse within 1e-3."""
 import numpy as np
 import pytest
 import torch
@@ -14,10 +15,9 @@ from helpers import compare_selection
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,budget,samples", [("c3", 2048, (0, 17, 31)), ("c4", 4096, (3, 15)),
-                                                   ("c5", 1024, (0, 21, 63)), ("c5", 4096, (5, 40))])
-def test_full_size_sampled_sequences(name, budget, samples):
-    print("full-size", name, budget, samples, flush=True)
+@pytest.mark.parametrize("name,budget", [("c3", 2048), ("c4", 4096), ("c5", 1024), ("c5", 4096)])
+def test_full_size_every_row_against_the_oracle(name, budget):
+    print("full-size", name, budget, flush=True)
     w = wl.scaled(wl.CONFIGS[name], budget=budget, layers=1)
     inp = wl.make_inputs(w, "cuda")
     eps = f32(1e-2)
@@ -35,30 +35,21 @@ def test_full_size_sampled_sequences(name, budget, samples):
     out, lse = api.as_sparse_decode_attn(ctx, p, kv, inp.q_real, sel_idx, sel_cnt, stream=s_att)
     q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur, stream=s_att)
     torch.cuda.synchronize()
-    # properties that hold for every row at any size
-    lens = inp.ctx_lens.cpu()
-    cnt = sel_cnt.cpu()
-    assert torch.equal(cnt, torch.clamp(lens, max=w.budget)[:, None].expand(-1, w.n_kv_heads).to(torch.int32))
-    idx = sel_idx.cpu()
-    for b in range(w.batch):
-        c = int(cnt[b, 0])
-        r = idx[b, :, :c]
-        assert (r >= 0).all() and (r < int(lens[b])).all() and (r[:, 1:] > r[:, :-1]).all()
-        assert (idx[b, :, c:] == -1).all()
-    assert torch.isfinite(out.float()).all()
-    swaps_total = 0
-    for b in samples:
-        one = wl.extract_sequence(inp, b)
-        rq, rs, ridx, rcnt = oracle.select_step(one.k_pool, one.block_table, one.ctx_lens, one.q_win, one.q_cur,
-                                                w.budget, eps)
-        assert (q_hat[b].cpu() - rq[0]).abs().max().item() <= 2e-2
-        swaps_total += compare_selection(sel_idx[b:b + 1], sel_cnt[b:b + 1], ridx, rcnt, rs, one.ctx_lens, w.budget)
-        ref, ref_lse = oracle.sparse_decode_attn(one.k_pool, one.v_pool, one.block_table, one.ctx_lens, one.q_real,
-                                                 sel_idx[b:b + 1].cpu(), sel_cnt[b:b + 1].cpu(), f32(SCALE))
-        err = (out[b].cpu().float() - ref[0].float()).abs().max().item()
-        assert err <= 2e-2, (b, err)
-        assert (lse[b].cpu() - ref_lse[0]).abs().max().item() <= 1e-3
-    print(f"  {name}: tie swaps {swaps_total} over {len(samples)} sampled sequences", flush=True)
+    print("  HIP path done; copying the layer to the host", flush=True)
+    k_cpu, v_cpu = inp.k_pool.cpu(), inp.v_pool.cpu()
+    bt, lens = inp.block_table.cpu(), inp.ctx_lens.cpu()
+    rq, rs, ridx, rcnt = oracle.select_step(k_cpu, bt, lens, inp.q_win.cpu(), inp.q_cur.cpu(), w.budget, eps)
+    print("  oracle selection done", flush=True)
+    assert (q_hat.cpu() - rq).abs().max().item() <= 2e-2
+    swaps = compare_selection(sel_idx, sel_cnt, ridx, rcnt, rs, lens, w.budget)      # every (sequence, KV head) row
+    ref, ref_lse = oracle.sparse_decode_attn(k_cpu, v_cpu, bt, lens, inp.q_real.cpu(), sel_idx.cpu(), sel_cnt.cpu(),
+                                             f32(SCALE))
+    err = (out.cpu().float() - ref.float()).abs().max().item()
+    lse_err = (lse.cpu() - ref_lse).abs().max().item()
+    print(f"  {name} budget {budget}: {w.batch * w.n_kv_heads} rows compared, tie swaps {swaps}, "
+          f"attention max abs err {err:.3e}, lse err {lse_err:.2e}", flush=True)
+    assert err <= 2e-2
+    assert lse_err <= 1e-3
     assert ctx.damaged_workspace_gap(p) == -1      # no kernel outgrew its region of the workspace at full size
 
 

@@ -122,7 +122,7 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
         assert (flat[:, keep:] == 9.0).all()
 
     assert fingerprint(*inputs) == before           # nothing wrote into the cache, the table or the queries
-    # the regions of the context workspace (q_hat, score rows, candidates, attention partials) are separated by
+    # the regions of the context workspace (attention partials, q_hat, score rows, candidates) are separated by
     # gaps that hold the pattern as_create wrote: a kernel that outgrew the size computed for its region shows here
     assert ctx.damaged_workspace_gap(p) == -1
     assert ctx_pack.damaged_workspace_gap(p, 2) == -1
@@ -154,8 +154,9 @@ def test_state_updates_touch_only_their_rows():
 
 
 def test_the_workspace_check_sees_a_write_into_a_gap():
-    """The check itself: after a call with one set of shapes, the gaps of a *different* layout (half the query
-    heads: its first gap lies where the call stored q_hat) no longer hold the fill pattern."""
+    """The check itself: after calls with one set of shapes, the gaps of a *different* layout (half the query
+    heads: its first gap lies where the dense attention call stored its split partials) no longer hold the fill
+    pattern."""
     w = wl.Workload("guard-check", 2, 8, 2, 4, 32, 400, page_table="identity", seed=31)
     dev = to_dev(wl.make_inputs(w))
     p = params_for(dev)
@@ -163,6 +164,7 @@ def test_the_workspace_check_sees_a_write_into_a_gap():
     assert ctx.damaged_workspace_gap(p) == -1                     # fresh workspace
     kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
     api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    api.as_dense_decode_attn(ctx, p, kv, dev.q_real)
     assert ctx.damaged_workspace_gap(p) == -1
     other = api.make_params(2, 4, 2, 4, 32, dev.max_pages)
     assert ctx.damaged_workspace_gap(other) == 0
@@ -178,7 +180,7 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
     B, Hq, Hkv, C = w.batch, w.n_q_heads, w.n_kv_heads, w.budget
     num_pages = clean.k_pool.shape[0]
 
-    def run(bt, lens, damage_selection, vector_alu=False):
+    def run(bt, lens, damage_selection):
         ctx = api.Context(p)
         kv = api.kv_view(clean.k_pool, clean.v_pool, bt, lens)
         sel = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
@@ -196,13 +198,9 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
             cnt[1, 1] = -4
             tail[1] = -100
         out, lse = Guarded((B, Hq, 128), torch.bfloat16, 3.0), Guarded((B, Hq), torch.float32, 3.0)
-        api.lib().as_debug_set_attn_impl(1 if vector_alu else 0)
-        try:
-            api.as_sparse_decode_attn(ctx, p, kv, clean.q_real, idx, cnt, tail, out.t, lse.t)
-            dense = Guarded((B, Hq, 128), torch.bfloat16, 3.0)
-            api.as_dense_decode_attn(ctx, p, kv, clean.q_real, dense.t, want_lse=False)
-        finally:
-            api.lib().as_debug_set_attn_impl(0)
+        api.as_sparse_decode_attn(ctx, p, kv, clean.q_real, idx, cnt, tail, out.t, lse.t)
+        dense = Guarded((B, Hq, 128), torch.bfloat16, 3.0)
+        api.as_dense_decode_attn(ctx, p, kv, clean.q_real, dense.t, want_lse=False)
         cp = api.compact_pages(p)
         k_out = Guarded((B * cp, Hkv, 16, 128), torch.bfloat16, 9.0)
         v_out = Guarded((B * cp, Hkv, 16, 128), torch.bfloat16, 9.0)
@@ -225,20 +223,18 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
         return dict(sel=sel[0].t, cnt=sel[1].t, sel2=sel2[0].t, out=out.t, lse=lse.t, dense=dense.t, k_out=k_out.t,
                     inter=inter.t)
 
-    ref = {impl: run(clean.block_table, clean.ctx_lens, damage_selection=False, vector_alu=impl)
-           for impl in (False, True)}           # the two attention kernels round differently
+    ref = run(clean.block_table, clean.ctx_lens, damage_selection=False)
     bt = clean.block_table.clone()
     bt[1, 0::3] = -7                                   # negative page ids
     bt[1, 1::3] = num_pages + 12345                    # page ids beyond the pool
     for bad_len in (-3, 16 * bt.shape[1] + 999):       # a negative length, a length beyond the block table
         lens = clean.ctx_lens.clone()
         lens[1] = bad_len
-        for vector_alu in (False, True):
-            print("corrupt", bad_len, vector_alu, flush=True)
-            got = run(bt, lens, damage_selection=True, vector_alu=vector_alu)
-            for name in ("sel", "cnt", "sel2", "out", "lse", "dense", "inter"):
-                for b in (0, 2):
-                    assert torch.equal(got[name][b], ref[vector_alu][name][b]), (name, b)
-            cp = api.compact_pages(p)
+        print("corrupt", bad_len, flush=True)
+        got = run(bt, lens, damage_selection=True)
+        for name in ("sel", "cnt", "sel2", "out", "lse", "dense", "inter"):
             for b in (0, 2):
-                assert torch.equal(got["k_out"][b * cp:(b + 1) * cp], ref[vector_alu]["k_out"][b * cp:(b + 1) * cp])
+                assert torch.equal(got[name][b], ref[name][b]), (name, b)
+        cp = api.compact_pages(p)
+        for b in (0, 2):
+            assert torch.equal(got["k_out"][b * cp:(b + 1) * cp], ref["k_out"][b * cp:(b + 1) * cp])
