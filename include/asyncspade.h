@@ -63,7 +63,8 @@ typedef enum {
   AS_ERR_INVALID_ARG = 1,
   AS_ERR_UNSUPPORTED = 2,
   AS_ERR_WORKSPACE = 3,
-  AS_ERR_HIP = 4
+  AS_ERR_HIP = 4,
+  AS_ERR_STATIC_SCRATCH = 5 /* as_select_step_static: the parameters need more scratch than the static array holds */
 } as_status;
 
 /* How the per-query-head logits of a GQA group become one score per KV head (the paper leaves it open):
@@ -195,6 +196,28 @@ AS_API as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view
  */
 AS_API as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win,
                          const void* q_cur, int32_t* sel_idx, int32_t* sel_cnt, void* stream);
+
+/*
+ * as_select_step for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It needs no ctx.  The same kernels run with q_hat, the score rows and
+ * the per-share candidates in a static device array of AS_STATIC_SCRATCH_BYTES that is part of the library
+ * image (every GPU the library runs on holds that much until the process ends); the call makes no
+ * allocation and frees nothing.  Results are identical, bit for bit, to as_select_step.
+ *   - runs on the CURRENT device; inputs and outputs are the caller's, as in as_select_step
+ *   - scratch need: q_hat (batch * n_q_heads * 512 B) plus the one region the shape's route uses, the
+ *     per-share candidates (rows cut into several shares: 8 B per candidate) or the score rows (few-row shapes
+ *     that run the stand-alone stages: 4 B per token); as_workspace_bytes(p) - as_workspace_bytes_attn(p) is
+ *     an upper bound.  Parameters that need more than AS_STATIC_SCRATCH_BYTES are refused with
+ *     AS_ERR_STATIC_SCRATCH before anything is launched
+ *   - the array's device address is looked up once per device, on the first call there or in any earlier
+ *     as_create on that device: make one of the two happen before a stream capture begins
+ *   - all calls on one GPU share the one array (nothing in it needs clearing between calls: every word a kernel
+ *     reads was written earlier in the same call): calls that overlap in time on one GPU, on whatever streams,
+ *     race and give unspecified results
+ */
+#define AS_STATIC_SCRATCH_BYTES (48u << 20)
+AS_API as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
+                                       int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
 /*
  * Depth-wise packed selection (Sec. 4.3, "Depth-wise Parallelism on Cache Rank": several

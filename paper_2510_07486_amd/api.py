@@ -20,7 +20,8 @@ _lib = None
 AS_AGG_MAX, AS_AGG_SUM, AS_AGG_SOFTMAX_SUM = 0, 1, 2
 AS_PRED_PER_WINDOW, AS_PRED_SINGLE_SOLVE = 0, 1
 EXPORTS = ["as_workspace_bytes", "as_workspace_bytes_attn", "as_create", "as_destroy", "as_status_str", "as_predict_query", "as_score_keys",
-           "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_workspace_bytes_pack",
+           "as_topk_select", "as_score_topk", "as_sparse_decode_attn", "as_select_step", "as_select_step_static",
+           "as_workspace_bytes_pack",
            "as_select_step_pack", "as_kv_append", "as_window_push", "as_gather_kv", "as_overlap_ratio",
            "as_dense_decode_attn"]
 # development / measurement entry points (include/asyncspade_debug.h)
@@ -28,6 +29,7 @@ DEBUG_EXPORTS = ["as_debug_select_plan", "as_debug_workspace_gaps", "as_debug_se
                  "as_debug_set_attn_splits", "as_debug_attn_workspace_bytes", "as_debug_stream_read_paged",
                  "as_debug_stream_read_flat", "as_debug_stream_read_flat_sink_words"]
 AS_MAX_PACK = 16
+AS_STATIC_SCRATCH_BYTES = 48 << 20
 
 
 class AsParams(C.Structure):
@@ -87,6 +89,8 @@ def lib():
         L.as_score_topk.argtypes = [vp, PP, KP, vp, vp, vp, vp]
         L.as_select_step.restype = C.c_int
         L.as_select_step.argtypes = [vp, PP, KP, vp, vp, vp, vp, vp]
+        L.as_select_step_static.restype = C.c_int
+        L.as_select_step_static.argtypes = [PP, KP, vp, vp, vp, vp, vp]
         L.as_workspace_bytes_pack.restype = C.c_size_t
         L.as_workspace_bytes_pack.argtypes = [PP, C.c_int32]
         L.as_select_step_pack.restype = C.c_int
@@ -300,6 +304,14 @@ def as_select_step(ctx: Context, p: AsParams, kv: AsKvView, q_win, q_cur, sel_id
         sel_cnt = torch.empty((p.batch, p.n_kv_heads), dtype=torch.int32, device=q_win.device)
     _check(lib().as_select_step(ctx.handle, C.byref(p), C.byref(kv), _ptr(q_win), _ptr(q_cur), _ptr(sel_idx),
                                 _ptr(sel_cnt), _stream(stream)), "as_select_step")
+    return sel_idx, sel_cnt
+
+
+def as_select_step_static(p: AsParams, kv: AsKvView, q_win, q_cur, sel_idx, sel_cnt, stream=None):
+    """as_select_step without a ctx and without any allocation: scratch lives in the library's static device array.
+    Outputs are the caller's (no tensor is created here)."""
+    _check(lib().as_select_step_static(C.byref(p), C.byref(kv), _ptr(q_win), _ptr(q_cur), _ptr(sel_idx), _ptr(sel_cnt),
+                                       _stream(stream)), "as_select_step_static")
     return sel_idx, sel_cnt
 
 

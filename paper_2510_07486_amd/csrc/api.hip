@@ -1,8 +1,14 @@
 // C ABI of the KV-selection hot path: argument validation, workspace carving, launches.
 // No device allocation outside as_create / as_destroy and no host synchronisation.
+#include <mutex>
 #include <new>
 
 #include "common.hpp"
+
+// Scratch of as_select_step_static: device memory that belongs to the library image, not to a ctx.  Every GPU the
+// library is loaded on holds its own copy at its own address.  In host code this name is only a handle for
+// hipGetSymbolAddress (see static_scratch below); it is never passed to a kernel, a copy or a fill.
+static __device__ __align__(256) unsigned char scratch[AS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -72,11 +78,11 @@ inline as_status hip_status(hipError_t e) { return e == hipSuccess ? AS_OK : AS_
 // the fused kernels: when the fused kernels have no share plan for the shape, when the plan could not prune
 // anything, or when the development knob says so.  The softmax-normalised aggregation exists only in the fused
 // kernels.
-bool use_stages(const as_ctx* ctx, const as_params* p) {
+bool use_stages(int select_mode, const as_params* p) {
   if (p->agg == AS_AGG_SOFTMAX_SUM) return false;
   if (!asx::select_plan_ok(p, 1)) return true;      // more shares per row than the merge kernel indexes
-  if (ctx->select_mode == 2) return false;
-  return ctx->select_mode == 1 || asx::select_prefers_stages(p);
+  if (select_mode == 2) return false;
+  return select_mode == 1 || asx::select_prefers_stages(p);
 }
 
 hipError_t score_then_topk(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
@@ -84,6 +90,48 @@ hipError_t score_then_topk(const as_params* p, const as_kv_view* kv, const float
   const hipError_t e = asx::launch_score(p, kv, q_hat, scores, stride, s);
   if (e != hipSuccess) return e;
   return asx::launch_topk(p, scores, stride, kv->ctx_lens, sel_idx, sel_cnt, s);
+}
+
+
+as_status check_select_step(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
+                            const int32_t* sel_idx, const int32_t* sel_cnt) {
+  as_status st = check_params(p);
+  if (st != AS_OK) return st;
+  if ((st = check_kv(kv, false)) != AS_OK) return st;
+  if (!q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
+  if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
+  return AS_OK;
+}
+
+// One layer-step of selection with its scratch regions given explicitly (parts of the ctx workspace, or of the
+// static scratch array): q_hat always, then the score rows (stand-alone stages) or the candidate region (fused
+// kernels), whichever the route needs.
+as_status select_step_on(float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, const as_params* p,
+                         const as_kv_view* kv, const void* q_win, const void* q_cur, int32_t* sel_idx,
+                         int32_t* sel_cnt, hipStream_t s) {
+  hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
+                                     q_hat, s);
+  if (e != hipSuccess) return AS_ERR_HIP;
+  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, cand, sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, sel_idx, sel_cnt, s));
+}
+
+// The device address of `scratch` that kernels, copies and fills may use: resolved once per device, with that
+// device current, and kept here.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[MAX_DEVICES] = {};
+
+// `device` must be the current device.  nullptr if the address cannot be resolved.
+char* static_scratch(int device) {
+  if (device < 0 || device >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[device] = static_cast<char*>(ptr);
+  }
+  return g_scratch_ptr[device];
 }
 
 }  // namespace
@@ -106,6 +154,7 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return AS_ERR_HIP;
   if (hipSetDevice(device) != hipSuccess) return AS_ERR_HIP;
+  (void)static_scratch(device);   // set-up of as_select_step_static on this device (its own call repeats it if needed)
   as_ctx* c = new (std::nothrow) as_ctx();
   if (!c) return AS_ERR_HIP;
   c->device = device;
@@ -143,6 +192,7 @@ const char* as_status_str(as_status s) {
     case AS_ERR_UNSUPPORTED: return "unsupported configuration";
     case AS_ERR_WORKSPACE: return "ctx workspace too small";
     case AS_ERR_HIP: return "HIP runtime error";
+    case AS_ERR_STATIC_SCRATCH: return "parameters need more than the static scratch array holds";
   }
   return "unknown status";
 }
@@ -211,7 +261,7 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
   if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
-  const bool stages = use_stages(ctx, p);
+  const bool stages = use_stages(ctx->select_mode, p);
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
@@ -223,23 +273,36 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
 
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
                          int32_t* sel_idx, int32_t* sel_cnt, void* stream) {
-  as_status st = check_params(p);
+  as_status st = check_select_step(p, kv, q_win, q_cur, sel_idx, sel_cnt);
   if (st != AS_OK) return st;
-  if ((st = check_kv(kv, false)) != AS_OK) return st;
-  if (!ctx || !q_win || !q_cur || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
-  if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
-  const bool stages = use_stages(ctx, p);
+  if (!ctx) return AS_ERR_INVALID_ARG;
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
-  float* q_hat = reinterpret_cast<float*>(ws + l.q_hat);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
-                                     q_hat, s);
-  if (e != hipSuccess) return AS_ERR_HIP;
-  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
-  return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
-                                    sel_cnt, s));
+  return select_step_on(reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
+                        ws + l.cand, use_stages(ctx->select_mode, p), p, kv, q_win, q_cur, sel_idx, sel_cnt,
+                        static_cast<hipStream_t>(stream));
+}
+
+as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
+                                int32_t* sel_idx, int32_t* sel_cnt, void* stream) {
+  as_status st = check_select_step(p, kv, q_win, q_cur, sel_idx, sel_cnt);
+  if (st != AS_OK) return st;
+  // q_hat, a gap, then the one region the route of this shape uses: score rows or candidates
+  const bool stages = use_stages(0, p);
+  const int64_t score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
+  const size_t q_bytes = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
+  const size_t region = stages ? (size_t)p->batch * p->n_kv_heads * (size_t)score_stride * sizeof(float)
+                               : asx::select_workspace_bytes(p, 1);
+  const size_t region_off = q_bytes + WS_GAP;
+  if (region_off + region > (size_t)AS_STATIC_SCRATCH_BYTES) return AS_ERR_STATIC_SCRATCH;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return AS_ERR_HIP;
+  char* base = static_scratch(device);    // this GPU's copy of the array (its address is resolved once per device)
+  if (!base) return AS_ERR_HIP;
+  return select_step_on(reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + region_off), score_stride,
+                        base + region_off, stages, p, kv, q_win, q_cur, sel_idx, sel_cnt,
+                        static_cast<hipStream_t>(stream));
 }
 
 size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers) {
