@@ -7,29 +7,51 @@ namespace asx {
 
 static constexpr int AT_SPLIT = AS_ATTN_CHUNK;  // smallest workgroup split, tokens (bounds the number of partials)
 
-// Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head).  Measured
-// (32/8 and 64/8 heads, budgets 1024-4096): what counts is that all workgroups are resident at
-// once (three fit a compute unit: at most 768; a second, partly filled round costs 5-10 %) and that the four
-// wavefronts of a workgroup get the same number of 32-token steps; 512 workgroups of 1024 tokens beat 1536 of 256-341
-// by 6-9 %.  So: the largest split count that keeps the grid within one round, preferably one that divides the
-// list into multiples of 128 tokens; never below AT_SPLIT tokens per split.
-static int attn_splits_for(const as_params* p, int64_t list_len, int forced) {
+// Split geometry for a logical token list of at most `list_len` tokens per (sequence, KV head): how many
+// workgroups share a row and how many wavefronts (4 or 8) a workgroup has.  Measured (32/8 and 64/8 heads,
+// budgets 1024-4096): what counts is that all wavefronts are resident at once, about eight per compute unit
+// (2048 in all; a second, partly filled round costs 5-10 %), and that every wavefront gets the same number of
+// 32-token steps.  Rows that one workgroup can take whole are not split at all: the kernel then finishes them
+// itself and neither partials nor the merge launch exist.  So: eight-wavefront workgroups when a whole number of
+// them per row gives one workgroup per compute unit or fewer, else four-wavefront ones; the split count is the
+// largest that keeps the grid within one round, preferably one that divides the list into equal whole steps per
+// wavefront; never below AT_SPLIT tokens per split.
+struct attn_geom { int nsplit, waves; };
+static attn_geom attn_geometry(const as_params* p, int64_t list_len, int forced) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (list_len < 1) list_len = 1;
   int64_t pairs = (int64_t)p->batch * p->n_kv_heads * ((G + 15) / 16);
   if (pairs < 1) pairs = 1;
-  int64_t nsel = 768 / pairs;
   const int64_t max_sel = (list_len + AT_SPLIT - 1) / AT_SPLIT;
-  if (nsel > max_sel) nsel = max_sel;
-  if (nsel < 1) nsel = 1;
-  const int64_t units = list_len / 128;           // a split of whole units gives every wavefront the same steps
-  for (int64_t d = nsel; d >= 1 && d * pairs >= 384; --d)
-    if (units > 0 && units % d == 0 && list_len % 128 == 0) {
-      nsel = d;
-      break;
-    }
-  if (forced > 0) nsel = forced < max_sel ? forced : max_sel;
-  return (int)nsel;
+  attn_geom g;
+  // eight wavefronts per workgroup, one workgroup per compute unit: rows x splits <= 256 with >= 256 tokens per wavefront-set
+  for (int waves : {8, 4}) {
+    const int64_t slots = waves == 8 ? 256 : 768;            // workgroups resident at once
+    const int64_t step_unit = 32 * waves;                    // tokens of one step of every wavefront
+    int64_t nsel = slots / pairs;
+    if (nsel > max_sel) nsel = max_sel;
+    if (nsel < 1) nsel = 1;
+    const int64_t units = list_len / step_unit;
+    bool even = false;
+    for (int64_t d = nsel; d >= 1 && d * pairs >= slots / 2; --d)
+      if (units > 0 && units % d == 0 && list_len % step_unit == 0) {
+        nsel = d;
+        even = true;
+        break;
+      }
+    g.nsplit = (int)nsel;
+    g.waves = waves;
+    // the eight-wavefront shape is taken when it fills at least seven eighths of the compute units evenly
+    if (waves == 8 && even && nsel * pairs >= 224 && pairs <= 256) break;
+  }
+  if (forced > 0) {
+    g.nsplit = (int)(forced < max_sel ? forced : max_sel);
+    g.waves = 4;
+  }
+  return g;
+}
+static int attn_splits_for(const as_params* p, int64_t list_len, int forced) {
+  return attn_geometry(p, list_len, forced).nsplit;
 }
 
 // partial outputs and partial (m, l) pairs, for the sparse call (list = budget) and the dense one
@@ -41,9 +63,11 @@ size_t attn_workspace_bytes(const as_params* p, int forced_splits) {
   return heads * (size_t)(ns > nd ? ns : nd) * (AS_HEAD_DIM + 2) * sizeof(float);
 }
 
-// merges the split partials of one (sequence, query head).  A separate launch on purpose: a
-// "last workgroup merges" scheme needs device-scope fences, which write back and invalidate
-// the whole per-XCD L2 on this chip and cost several times the kernel itself.
+// merges the split partials of one (sequence, query head).  A separate launch on purpose.  "Last workgroup of a
+// row merges" was built twice and measured: with device-scope fences it is several times slower (they write back
+// and invalidate the whole per-XCD L2); without fences (write-through stores, a completion wait, a barrier, one
+// device-scope atomic, device-scope loads) it is correct but its serial chain of round trips at the end of the
+// kernel costs what this launch costs (batch 16, 64/8 heads, budget 4096: 52.8 against 52.6 us).
 __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* __restrict__ part_o,
                                                                    const float* __restrict__ part_ml,
                                                                    uint16_t* __restrict__ out,
@@ -109,7 +133,7 @@ __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* 
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            int nsplit, int list_len, hipStream_t s);
+                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, hipStream_t s);
 
 // sel_idx == nullptr: dense attention over [0, ctx_lens[b]) (the token list is only the "tail", from 0)
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
@@ -119,11 +143,13 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   if (heads == 0) return hipSuccess;
   const bool dense = sel_idx == nullptr;
   const int64_t list_len = dense ? (int64_t)p->max_pages_per_seq * AS_PAGE : (int64_t)p->budget;
-  const int nsplit = attn_splits_for(p, list_len, forced_splits);
+  const attn_geom gm = attn_geometry(p, list_len, forced_splits);
+  const int nsplit = gm.nsplit;
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
-  hipError_t e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, nsplit, (int)list_len, s);
-  if (e != hipSuccess) return e;
+  hipError_t e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, out, lse, nsplit,
+                                  gm.waves, (int)list_len, s);
+  if (e != hipSuccess || nsplit == 1) return e;      // unsplit rows are finished by the attention kernel itself
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)heads), dim3(AS_HEAD_DIM), 0, s, part_o, part_ml, out, lse,
                      nsplit);
   return hipGetLastError();

@@ -12,9 +12,11 @@
 // transposing LDS read that hands a lane four tokens of one dim.  The S^T accumulator layout
 // (lane = head, 4 tokens per tile and lane group) IS the A-operand layout of P for the PV
 // product, so probabilities go from registers straight back into the matrix core.  Each
-// wavefront keeps its own online-softmax state (no barrier in the loop); the four waves of a
-// workgroup merge once at the end and write one partial (m, l, o) per head and split, which
-// attn_combine_kernel (attn.hip) reduces.
+// wavefront keeps its own online-softmax state (no barrier in the loop); the waves of a workgroup
+// (four or eight, chosen by the host so that about eight wavefronts per compute unit each get the
+// same number of steps) merge once at the end.  A row that is not split across workgroups is
+// finished there (normalised, rounded to bf16, lse written); otherwise the workgroup writes one
+// partial (m, l, o) per head and split, which attn_combine_kernel (attn.hip) reduces.
 #include "common.hpp"
 #include "score_common.hpp"
 
@@ -34,14 +36,23 @@ __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
-__global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
+// WAVES = 4: 37 KB of LDS, three workgroups fit a compute unit.  WAVES = 8: the LDS request is padded beyond half
+// of a compute unit's 160 KB, so that the dispatcher can never put two of these on one compute unit and none on
+// another (the host launches about one per compute unit).
+template <int WAVES> struct am_shape {
+  static constexpr int LDS = WAVES * AM_WAVE_LDS < WAVES * 16 * AS_HEAD_DIM * 4 ? WAVES * 16 * AS_HEAD_DIM * 4 : WAVES * AM_WAVE_LDS;
+  static constexpr int LDS_PADDED = (WAVES == 8 && LDS < 84 * 1024) ? 84 * 1024 : LDS;
+};
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kernel(
     const uint16_t* __restrict__ k_pool, const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
-    float* __restrict__ part_ml, int Hq, int Hkv, int G, int C, int max_pages, float sm_scale, int nsplit,
-    int list_len, int32_t last_page) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * AM_WAVE_LDS];
-  __shared__ float m_sh[4][16], l_sh[4][16];
+    float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ lse, int Hq, int Hkv, int G, int C,
+    int max_pages, float sm_scale, int nsplit, int list_len, int32_t last_page) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[am_shape<WAVES>::LDS_PADDED];
+  __shared__ float m_sh[WAVES][16], l_sh[WAVES][16], l_fin[16];
 
   // a workgroup serves up to 16 heads of a group: larger groups (MQA) take several head blocks per KV head
   const int hblocks = (G + 15) / 16;
@@ -72,13 +83,17 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
   const int L = cnt + (N - tail0);
   const int t_end = (split == nsplit - 1) ? L : (t_next < L ? t_next : L);
   const int64_t pbase = ((int64_t)b * Hq + (int64_t)j * G + g0) * nsplit + split;  // + g * nsplit per head
+  const bool direct = nsplit == 1;                                            // the whole row is this workgroup's
+  const int64_t obase = (int64_t)b * Hq + (int64_t)j * G + g0;                // + g per head
   if (t_begin >= t_end) {                                                     // nothing here: mark empty
-    if (tid < Gb) {
+    if (direct) {
+      for (int i = tid; i < Gb * AS_HEAD_DIM; i += WAVES * 64) out[obase * AS_HEAD_DIM + i] = 0;
+      if (lse && tid < Gb) lse[obase + tid] = -INFINITY;
+    } else if (tid < Gb) {
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 0] = -INFINITY;
       part_ml[(pbase + (int64_t)tid * nsplit) * 2 + 1] = 0.f;
     }
-    return;
-  }
+  } else {
   const int nsteps = (t_end - t_begin + AM_STEP - 1) / AM_STEP;
 
   // Q^T as the B operand of S^T = K Q^T: lane (head t, k group grp), step m holds the 8 dims of
@@ -113,11 +128,11 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
 
   uint32_t my_pk = (w < nsteps) ? page_of(w, raw_first) : 0u;
 #pragma unroll 1
-  for (int step = w; step < nsteps; step += 4) {
+  for (int step = w; step < nsteps; step += WAVES) {
     // next step's index is requested now, its page id after this step's rows are on their way
-    const bool more = step + 4 < nsteps;
+    const bool more = step + WAVES < nsteps;
     int raw_next = 0;
-    if (more) raw_next = fetch_index(step + 4);
+    if (more) raw_next = fetch_index(step + WAVES);
     // ---- gather the 32 K and V rows of the step (8 loads of 4 rows each) ----
     uint4 kr[8], vr[8];
 #pragma unroll
@@ -128,7 +143,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
       vr[it] = am_ld16_nt(v_pool + off);
     }
     uint32_t pk_next = 0;
-    if (more) pk_next = page_of(step + 4, raw_next);
+    if (more) pk_next = page_of(step + WAVES, raw_next);
     // ---- S^T = K Q^T for the two tiles (K goes through one 16-token image, tile after tile): lane (head t, grp) gets tokens tile*16 + 4*grp + i ----
     float s[8];
 #pragma unroll
@@ -210,7 +225,7 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
     my_pk = pk_next;
   }
 
-  // ---- merge the four waves: common max per head, rescale, sum ----
+  // ---- merge the waves: common max per head, rescale, sum ----
   if (grp == 0) {
     m_sh[w][t] = m_run;
     l_sh[w][t] = l_run;
@@ -218,11 +233,11 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
   __syncthreads();                      // also: every wave is done with its LDS images
   float M = -INFINITY, Ls = 0.f;
 #pragma unroll
-  for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, m_sh[ww][t]);
+  for (int ww = 0; ww < WAVES; ++ww) M = fmaxf(M, m_sh[ww][t]);
 #pragma unroll
-  for (int ww = 0; ww < 4; ++ww) Ls += (m_sh[ww][t] == -INFINITY) ? 0.f : l_sh[ww][t] * __expf(m_sh[ww][t] - M);
+  for (int ww = 0; ww < WAVES; ++ww) Ls += (m_sh[ww][t] == -INFINITY) ? 0.f : l_sh[ww][t] * __expf(m_sh[ww][t] - M);
   const float wgt = (m_run == -INFINITY) ? 0.f : __expf(m_run - M);   // this wave's factor for head t
-  float* red = reinterpret_cast<float*>(lds_raw);                      // [4 waves][16 heads][128] fp32 = 32 KB
+  float* red = reinterpret_cast<float*>(lds_raw);                      // [WAVES][16 heads][128] fp32
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float f = __shfl(wgt, 4 * grp + i);
@@ -230,29 +245,45 @@ __global__ __launch_bounds__(256, 3) void attn_mfma_kernel(
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) red[(w * 16 + head) * AS_HEAD_DIM + nt * 16 + t] = o_acc[nt][i] * f;
   }
+  if (w == 0 && grp == 0) l_fin[t] = Ls;   // the merged normaliser of head t
   __syncthreads();
-  for (int i = tid; i < Gb * AS_HEAD_DIM; i += 256) {
+  for (int i = tid; i < Gb * AS_HEAD_DIM; i += WAVES * 64) {
     const int g = i / AS_HEAD_DIM, d = i % AS_HEAD_DIM;
-    const float v = red[(0 * 16 + g) * AS_HEAD_DIM + d] + red[(1 * 16 + g) * AS_HEAD_DIM + d] +
-                    red[(2 * 16 + g) * AS_HEAD_DIM + d] + red[(3 * 16 + g) * AS_HEAD_DIM + d];
-    part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
+    float v = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < WAVES; ++ww) v += red[(ww * 16 + g) * AS_HEAD_DIM + d];
+    if (direct) {
+      const float lg = l_fin[g];
+      out[(obase + g) * AS_HEAD_DIM + d] = (uint16_t)f32_to_bf16_rne(lg > 0.f ? v / lg : 0.f);
+    } else {
+      part_o[(pbase + (int64_t)g * nsplit) * AS_HEAD_DIM + d] = v;
+    }
   }
   if (w == 0 && grp == 0 && t < Gb) {
-    part_ml[(pbase + (int64_t)t * nsplit) * 2 + 0] = M;
-    part_ml[(pbase + (int64_t)t * nsplit) * 2 + 1] = Ls;
+    if (direct) {
+      if (lse) lse[obase + t] = (Ls > 0.f) ? M + logf(Ls) : -INFINITY;
+    } else {
+      part_ml[(pbase + (int64_t)t * nsplit) * 2 + 0] = M;
+      part_ml[(pbase + (int64_t)t * nsplit) * 2 + 1] = Ls;
+    }
   }
+  }   // this split had tokens
+
 }
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            int nsplit, int list_len, hipStream_t s) {
+                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
   dim3 grid(nsplit, p->n_kv_heads * ((G + 15) / 16), p->batch);
-  hipLaunchKernelGGL(attn_mfma_kernel, grid, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(kv->k_pool),
-                     reinterpret_cast<const uint16_t*>(kv->v_pool), kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt,
-                     sel_ctx_lens, part_o, part_ml, p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0,
-                     p->max_pages_per_seq,
-                     p->sm_scale, nsplit, list_len, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0));
+#define AS_ATTN_LAUNCH(WAVES_)                                                                                        \
+  hipLaunchKernelGGL(attn_mfma_kernel<WAVES_>, grid, dim3(WAVES_ * 64), 0, s,                                         \
+                     reinterpret_cast<const uint16_t*>(kv->k_pool), reinterpret_cast<const uint16_t*>(kv->v_pool),    \
+                     kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, out, lse,     \
+                     p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0, p->max_pages_per_seq, p->sm_scale,      \
+                     nsplit, list_len, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0))
+  if (waves == 8) AS_ATTN_LAUNCH(8); else AS_ATTN_LAUNCH(4);
+#undef AS_ATTN_LAUNCH
   return hipGetLastError();
 }
 
