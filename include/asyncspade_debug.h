@@ -37,6 +37,13 @@ AS_API as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode);
 AS_API as_status as_debug_set_attn_splits(as_ctx* ctx, int32_t splits);
 AS_API size_t as_debug_attn_workspace_bytes(const as_params* p, int32_t splits);
 
+/* Workgroup timeline of THIS ctx: while buf is set, every workgroup w (linear index, x fastest) of the fused
+ * selection kernel and of the attention kernel writes the device's 100 MHz wall clock at its entry to buf[2 * w]
+ * and at its exit to buf[2 * w + 1] (workgroups at and beyond `capacity` write nothing).  The buffer is device
+ * memory of the caller's, 2 * capacity int64; each launch overwrites the last one's marks.  capacity = 0 switches
+ * the marks off (the default). */
+AS_API as_status as_debug_set_timeline(as_ctx* ctx, int64_t* buf, int32_t capacity);
+
 /* Calibration kernels.  as_debug_stream_read_paged walks the K pages of every (sequence, KV head) exactly like
  * the scoring kernels (block table, coalesced non-temporal 128-bit loads) and does no arithmetic beyond an XOR
  * fold; words_per_token != 0 writes one 4-byte word per token into sink[b][j][n] (known read and write sizes,

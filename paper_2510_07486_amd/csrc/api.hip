@@ -108,11 +108,11 @@ as_status check_select_step(const as_params* p, const as_kv_view* kv, const void
 // kernels), whichever the route needs.
 as_status select_step_on(float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, const as_params* p,
                          const as_kv_view* kv, const void* q_win, const void* q_cur, int32_t* sel_idx,
-                         int32_t* sel_cnt, hipStream_t s) {
+                         int32_t* sel_cnt, asx::wg_timeline tl, hipStream_t s) {
   hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
                                      q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
-  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, cand, sel_idx, sel_cnt, s));
+  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, cand, sel_idx, sel_cnt, tl, s));
   return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, sel_idx, sel_cnt, s));
 }
 
@@ -162,6 +162,8 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->ws_bytes = workspace_bytes;
   c->select_mode = 0;
   c->attn_splits = 0;
+  c->timeline = nullptr;
+  c->timeline_cap = 0;
   if (workspace_bytes > 0) {
     if (hipMalloc(&c->ws, workspace_bytes) != hipSuccess) {
       delete c;
@@ -238,7 +240,8 @@ as_status as_sparse_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_vie
   if (!ctx->ws || ctx->ws_bytes < l.attn_end) return AS_ERR_WORKSPACE;   // the attention region leads the layout
   return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), sel_idx, sel_cnt, sel_ctx_lens,
                                      static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
-                                     ctx->attn_splits, static_cast<hipStream_t>(stream)));
+                                     ctx->attn_splits, asx::wg_timeline{ctx->timeline, ctx->timeline_cap},
+                                     static_cast<hipStream_t>(stream)));
 }
 
 as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q, void* out,
@@ -251,7 +254,8 @@ as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_kv_view
   if (!ctx->ws || ctx->ws_bytes < l.attn_end) return AS_ERR_WORKSPACE;
   return hip_status(asx::launch_attn(p, kv, static_cast<const uint16_t*>(q), nullptr, nullptr, nullptr,
                                      static_cast<uint16_t*>(out), lse, static_cast<char*>(ctx->ws) + l.attn,
-                                     ctx->attn_splits, static_cast<hipStream_t>(stream)));
+                                     ctx->attn_splits, asx::wg_timeline{ctx->timeline, ctx->timeline_cap},
+                                     static_cast<hipStream_t>(stream)));
 }
 
 as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat, int32_t* sel_idx,
@@ -266,7 +270,9 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt, s));
+  if (!stages)
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt,
+                                               asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
   return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
                                     sel_cnt, s));
 }
@@ -281,7 +287,7 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   char* ws = static_cast<char*>(ctx->ws);
   return select_step_on(reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
                         ws + l.cand, use_stages(ctx->select_mode, p), p, kv, q_win, q_cur, sel_idx, sel_cnt,
-                        static_cast<hipStream_t>(stream));
+                        asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
 }
 
 as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
@@ -301,7 +307,7 @@ as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const 
   char* base = static_scratch(device);    // this GPU's copy of the array (its address is resolved once per device)
   if (!base) return AS_ERR_HIP;
   return select_step_on(reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + region_off), score_stride,
-                        base + region_off, stages, p, kv, q_win, q_cur, sel_idx, sel_cnt,
+                        base + region_off, stages, p, kv, q_win, q_cur, sel_idx, sel_cnt, asx::wg_timeline{nullptr, 0},
                         static_cast<hipStream_t>(stream));
 }
 
@@ -326,6 +332,7 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
   char* ws = static_cast<char*>(ctx->ws);
   asx::pred_tab pt = {};
   asx::sel_tab stab = {};
+  stab.timeline = asx::wg_timeline{ctx->timeline, ctx->timeline_cap};
   for (int l = 0; l < n_layers; ++l) {
     float* q_hat = reinterpret_cast<float*>(ws + lay.q_hat + lay.q_hat_layer * l);
     pt.q_win[l] = static_cast<const uint16_t*>(layers[l].q_win);
@@ -422,6 +429,13 @@ as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_lay
 as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode) {
   if (!ctx || mode < 0 || mode > 2) return AS_ERR_INVALID_ARG;
   ctx->select_mode = mode;
+  return AS_OK;
+}
+
+as_status as_debug_set_timeline(as_ctx* ctx, int64_t* buf, int32_t capacity) {
+  if (!ctx || capacity < 0 || (capacity > 0 && !buf)) return AS_ERR_INVALID_ARG;
+  ctx->timeline = capacity > 0 ? reinterpret_cast<long long*>(buf) : nullptr;
+  ctx->timeline_cap = capacity;
   return AS_OK;
 }
 

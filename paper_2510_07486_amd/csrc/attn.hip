@@ -133,12 +133,13 @@ __global__ __launch_bounds__(AS_HEAD_DIM) void attn_combine_kernel(const float* 
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, hipStream_t s);
+                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, wg_timeline tl,
+                            hipStream_t s);
 
 // sel_idx == nullptr: dense attention over [0, ctx_lens[b]) (the token list is only the "tail", from 0)
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
-                       int forced_splits, hipStream_t s) {
+                       int forced_splits, wg_timeline tl, hipStream_t s) {
   const int64_t heads = (int64_t)p->batch * p->n_q_heads;
   if (heads == 0) return hipSuccess;
   const bool dense = sel_idx == nullptr;
@@ -148,7 +149,7 @@ hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t*
   float* part_o = reinterpret_cast<float*>(ws);
   float* part_ml = part_o + heads * nsplit * AS_HEAD_DIM;
   hipError_t e = launch_attn_mfma(p, kv, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, out, lse, nsplit,
-                                  gm.waves, (int)list_len, s);
+                                  gm.waves, (int)list_len, tl, s);
   if (e != hipSuccess || nsplit == 1) return e;      // unsplit rows are finished by the attention kernel itself
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)heads), dim3(AS_HEAD_DIM), 0, s, part_o, part_ml, out, lse,
                      nsplit);

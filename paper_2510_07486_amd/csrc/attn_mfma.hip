@@ -50,7 +50,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
     const int32_t* __restrict__ ctx_lens, const uint16_t* __restrict__ q, const int32_t* __restrict__ sel_idx,
     const int32_t* __restrict__ sel_cnt, const int32_t* __restrict__ sel_ctx_lens, float* __restrict__ part_o,
     float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ lse, int Hq, int Hkv, int G, int C,
-    int max_pages, float sm_scale, int nsplit, int list_len, int32_t last_page) {
+    int max_pages, float sm_scale, int nsplit, int list_len, int32_t last_page, wg_timeline tl) {
+  timeline_mark(tl, 0);
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[am_shape<WAVES>::LDS_PADDED];
   __shared__ float m_sh[WAVES][16], l_sh[WAVES][16], l_fin[16];
 
@@ -273,7 +274,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
 
 hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                             const int32_t* sel_cnt, const int32_t* sel_ctx_lens, float* part_o, float* part_ml,
-                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, hipStream_t s) {
+                            uint16_t* out, float* lse, int nsplit, int waves, int list_len, wg_timeline tl,
+                            hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
   dim3 grid(nsplit, p->n_kv_heads * ((G + 15) / 16), p->batch);
 #define AS_ATTN_LAUNCH(WAVES_)                                                                                        \
@@ -281,7 +283,7 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
                      reinterpret_cast<const uint16_t*>(kv->k_pool), reinterpret_cast<const uint16_t*>(kv->v_pool),    \
                      kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, out, lse,     \
                      p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0, p->max_pages_per_seq, p->sm_scale,      \
-                     nsplit, list_len, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0))
+                     nsplit, list_len, (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0), tl)
   if (waves == 8) AS_ATTN_LAUNCH(8); else AS_ATTN_LAUNCH(4);
 #undef AS_ATTN_LAUNCH
   return hipGetLastError();

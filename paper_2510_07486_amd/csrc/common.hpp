@@ -22,9 +22,23 @@ struct as_ctx {
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
                         1: always the separate kernels via HBM scores, 2: always fused */
   int attn_splits;   /* > 0: forced number of attention splits per (sequence, KV head) */
+  long long* timeline;   /* development: device buffer that receives wall_clock64 at entry and exit of every */
+  int timeline_cap;      /* workgroup of the selection and attention kernels (pairs), and its capacity in pairs */
 };
 
 namespace asx {
+
+// development hook: where workgroups leave their entry / exit clock (buf == nullptr: nowhere)
+struct wg_timeline {
+  long long* buf;
+  int cap;
+};
+__device__ __forceinline__ void timeline_mark(const wg_timeline& tl, int which) {
+  if (tl.buf && threadIdx.x == 0) {
+    const int wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (wg < tl.cap) tl.buf[2 * wg + which] = wall_clock64();
+  }
+}
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t lo16) { return __uint_as_float(lo16 << 16); }
 // low / high bf16 of a packed dword -> fp32
@@ -59,6 +73,7 @@ struct sel_tab {
   int32_t* sel_idx[AS_PACK_MAX];
   int32_t* sel_cnt[AS_PACK_MAX];
   int32_t last_page[AS_PACK_MAX];   // num_pages - 1 of the layer's pool (page ids are clamped to it)
+  wg_timeline timeline;             // development hook of the slice kernel
 };
 
 // ---- launchers (host) -------------------------------------------------------------
@@ -83,13 +98,13 @@ bool select_prefers_stages(const as_params* p);
 size_t select_workspace_bytes(const as_params* p, int n_layers);
 hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s);
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
-                               int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
+                               int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl, hipStream_t s);
 // partial buffers live in the ctx workspace
 // forced_splits > 0 overrides the split rule (development knob of a ctx)
 size_t attn_workspace_bytes(const as_params* p, int forced_splits);
 hipError_t launch_attn(const as_params* p, const as_kv_view* kv, const uint16_t* q, const int32_t* sel_idx,
                        const int32_t* sel_cnt, const int32_t* sel_ctx_lens, uint16_t* out, float* lse, void* ws,
-                       int forced_splits, hipStream_t s);
+                       int forced_splits, wg_timeline tl, hipStream_t s);
 
 // cache-side bookkeeping (cache_ops.hip)
 hipError_t launch_kv_append(const as_params* p, uint16_t* k_pool, uint16_t* v_pool, const int32_t* block_table,

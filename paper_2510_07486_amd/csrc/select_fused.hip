@@ -37,7 +37,8 @@ template <int THREADS> struct fs_shape {
   static constexpr int RCAP = THREADS * 4;                // largest budget served by pruning (a prune frees >= CAP / 2)
   static constexpr int B0 = 11;                           // bits of the first radix pass
   static constexpr int BINS = 1 << B0;
-  static constexpr int SHARE_CAP = THREADS * 32;          // tokens per share (balance of ragged batches)
+  static constexpr int SHARE_CAP = THREADS * (THREADS == 1024 ? 64 : 32);   // tokens per share: the bitmap that orders
+                                                          // a share's selection has one bit per token (8 KB / 2 KB)
 };
 static constexpr int FS_PG = 2;             // pages a wave loads per iteration (8 KB in flight per wave)
 static constexpr int FS_MAX_SLICES = 1024;  // shares per row the merge kernel can index (one per thread)
@@ -65,7 +66,7 @@ static select_plan plan_for(const as_params* p, int thr, int n_layers) {
   select_plan pl;
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
   const int64_t max_ctx = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  const int ssub = thr * 8, rcap = thr * 4, share_cap = thr * 32;
+  const int ssub = thr * 8, rcap = thr * 4, share_cap = thr == 1024 ? fs_shape<1024>::SHARE_CAP : fs_shape<512>::SHARE_CAP;
   const int64_t slots = (int64_t)device_cus() * (thr == 1024 ? 1 : 2);
   const double T_SHARED = 9.5e-3 * 256.0 / (double)device_cus() * (thr == 1024 ? 1.0 : 2.0);
   const double T_ALONE = 7.2e-3 * (thr == 1024 ? 1.0 : 2.0);
@@ -162,7 +163,8 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   using shape = fs_shape<FS_THREADS>;
   constexpr int FS_WAVES = shape::WAVES, CAP = shape::CAP, NPT = CAP / FS_THREADS;
   constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS, BM_WORDS = shape::SHARE_CAP / 32;
-  static_assert(BM_WORDS <= FS_THREADS && BM_WORDS <= FS_BINS, "one bitmap word per thread; prefixes alias hist");
+  constexpr int BM_WPT = (BM_WORDS + FS_THREADS - 1) / FS_THREADS;   // consecutive bitmap words a thread scans
+  static_assert(BM_WORDS <= FS_BINS, "the prefixes of the bitmap words alias hist");
   __shared__ __attribute__((aligned(16))) uint32_t c_key[CAP];   // candidate buffer: keys ...
   __shared__ __attribute__((aligned(16))) int32_t c_tok[CAP];    // ... and their token indices
   __shared__ uint4 stage[FS_WAVES][256];  // per-wave page images while streaming; ordered output at the end
@@ -175,6 +177,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
   // sequences (the share) must vary slowest, or the workgroups that do have work pile up on half
   // of the compute units.
+  timeline_mark(tab.timeline, 0);
   const int j = blockIdx.x, sh = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t = lane & 15, grp = lane >> 4;
@@ -214,6 +217,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   const bool final_out = (nshares == 1);
   if (MODE == 1 && n_share == 0) {
     if (tid < G) lse_part[(crow * nshares + sh) * G + tid] = make_float2(-INFINITY, 0.f);
+    timeline_mark(tab.timeline, 1);
     return;
   }
   if (n_share == 0) {
@@ -223,6 +227,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     } else if (tid == 0) {
       cand_cnt[crow * nshares + sh] = 0;
     }
+    timeline_mark(tab.timeline, 1);
     return;
   }
 
@@ -470,6 +475,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       }
       lse_part[(crow * nshares + sh) * G + tid] = make_float2(m, l);
     }
+    timeline_mark(tab.timeline, 1);
     return;
   }
 
@@ -491,19 +497,31 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     }
     if (keep < cnt) mark_best<FS_THREADS, FS_B0, NPT>(key, tok, have, keep, hist, xch, sel);
     // order by token through a bitmap of the share: rank of a token = set bits below it
-    if (tid < BM_WORDS) bitmap[tid] = 0;
+    for (int wd = tid; wd < BM_WORDS; wd += FS_THREADS) bitmap[wd] = 0;
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < NPT; ++e)
       if (sel[e]) atomicOr(&bitmap[(tok[e] - tok0) >> 5], 1u << ((tok[e] - tok0) & 31));
     __syncthreads();
-    const uint32_t pc = tid < BM_WORDS ? (uint32_t)__popc(bitmap[tid]) : 0u;
+    uint32_t pcw[BM_WPT], pc = 0;
+#pragma unroll
+    for (int k = 0; k < BM_WPT; ++k) {
+      const int wd = tid * BM_WPT + k;
+      pcw[k] = wd < BM_WORDS ? (uint32_t)__popc(bitmap[wd]) : 0u;
+      pc += pcw[k];
+    }
     const uint32_t inc = wave_incl_scan(pc);
     if (lane == 63) xch[wave] = inc;
     __syncthreads();
     uint32_t woff[1];
     seg_wave_offsets<FS_WAVES, 1>(xch, wave, woff);
-    if (tid < BM_WORDS) hist[tid] = woff[0] + inc - pc;   // set bits in the words below this one
+    uint32_t below = woff[0] + inc - pc;                  // set bits in the words below this thread's first one
+#pragma unroll
+    for (int k = 0; k < BM_WPT; ++k) {
+      const int wd = tid * BM_WPT + k;
+      if (wd < BM_WORDS) hist[wd] = below;
+      below += pcw[k];
+    }
     __syncthreads();
     uint32_t* o_key = reinterpret_cast<uint32_t*>(&stage[0][0]);   // [CAP] + [CAP] words fit: the page images are dead
     int32_t* o_tok = reinterpret_cast<int32_t*>(o_key + CAP);
@@ -529,6 +547,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
     }
   }
+  timeline_mark(tab.timeline, 1);
 }
 
 // Reduces a row's per-slice candidates (ascending token order within and across slices) to
@@ -692,8 +711,9 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
 }
 
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
-                               int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+                               int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl, hipStream_t s) {
   sel_tab tab = {};
+  tab.timeline = tl;
   tab.k_pool[0] = reinterpret_cast<const uint16_t*>(kv->k_pool);
   tab.block_table[0] = kv->block_table;
   tab.ctx_lens[0] = kv->ctx_lens;

@@ -41,10 +41,12 @@ def test_library_exports_exactly_the_declared_symbols():
 def test_workspace_bytes_and_param_validation():
     p = api.make_params(32, 32, 8, 16, 2048, 2048)
     n = api.as_workspace_bytes(p)
-    # q_hat + score rows + attention partials (at least two splits per row at this shape)
-    assert n >= 32 * 32 * 128 * 4 + 32 * 8 * 32768 * 4 + 32 * 32 * 2 * 130 * 4
+    # q_hat + score rows + attention partials (one set per head: rows of this shape are not split)
+    assert n >= 32 * 32 * 128 * 4 + 32 * 8 * 32768 * 4 + 32 * 32 * 130 * 4
     # the attention calls need only the leading part of the layout
-    assert 32 * 32 * 2 * 130 * 4 <= api.as_workspace_bytes_attn(p) < n // 8
+    assert 32 * 32 * 130 * 4 <= api.as_workspace_bytes_attn(p) < n // 8
+    # a forced split count (development knob) asks for that many partial sets
+    assert api.attn_workspace_bytes_forced(p, 4) >= 32 * 32 * 4 * 130 * 4
     assert api.as_workspace_bytes_attn(api.make_params(1, 6, 4, 16, 64, 8)) == 0
     bad = api.make_params(1, 6, 4, 16, 64, 8)            # 6 % 4 != 0
     assert api.as_workspace_bytes(bad) == 0
@@ -135,7 +137,7 @@ def test_share_plan_invariants_over_random_shapes():
         share, shares, cand = api.select_plan(p, layers)
         max_ctx = pages * 16
         wide = g > 16 and agg != 1                     # MQA-sized groups run the 512-thread shape
-        buf, cap = (4096, 16384) if wide else (8192, 32768)
+        buf, cap = (4096, 16384) if wide else (8192, 65536)
         assert share * shares >= max_ctx and (shares - 1) * share < max(max_ctx, 1) or shares == 1
         assert 256 <= share <= cap and share % 64 == 0
         if budget > buf // 2:

@@ -54,7 +54,7 @@ def test_static_scratch_refuses_what_does_not_fit():
     L = api.lib()
     one = C.c_void_p(1)
     kv = api.AsKvView(1, 1, 1, 1, 1)
-    big = api.make_params(128, 32, 8, 16, 4096, 4096)          # candidates of 1024 rows x 2 shares x 4096 x 8 B = 64 MiB
+    big = api.make_params(128, 32, 8, 16, 4096, 8192)          # candidates of 1024 rows x 2 shares x 4096 x 8 B = 64 MiB
     share, shares, cand = api.select_plan(big, 1)
     assert shares > 1 and 1024 * shares * cand * 8 > api.AS_STATIC_SCRATCH_BYTES
     assert L.as_select_step_static(C.byref(big), C.byref(kv), one, one, one, one, None) == 5
