@@ -49,10 +49,13 @@ def parse():
     ap.add_argument("--graph", action="store_true", help="time the overlapped schedule as HIP graph replays (two graphs, "
                     "one per selection buffer parity) instead of eager launches")
     ap.add_argument("--pack", type=int, default=1, help="layers per packed selection launch (as_select_step_pack)")
-    ap.add_argument("--probe", default="", choices=["", "traffic", "attn-splits"],
+    ap.add_argument("--probe", default="", choices=["", "traffic", "attn-splits", "predictor", "timeline"],
                     help="instead of the benchmark: 'traffic' launches the calibration kernels and every kernel of the "
                          "path a few times on one layer (the program rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs on); "
-                         "'attn-splits' sweeps the forced attention split count (--splits)")
+                         "'attn-splits' sweeps the forced attention split count (--splits); 'predictor' times as_select_step "
+                         "(--pack > 1: as_select_step_pack) with the predictor as its own launch and inside the selection "
+                         "kernel's prologue; 'timeline' prints when the workgroups of the selection and attention kernels "
+                         "start and end")
     ap.add_argument("--splits", default="0,1,2,3,4,6,8,12,16", help="split counts of --probe attn-splits (0 = the rule)")
     ap.add_argument("--reps", type=int, default=3, help="launches per kernel of --probe traffic")
     return ap.parse_args()
@@ -140,6 +143,97 @@ def probe_attn_splits(a, torch, api, wl):
         print(f"  {label:36s} {us:7.1f} us  {rows * 512 / us / 1e3:7.0f} GB/s", flush=True)
 
 
+def probe_predictor(a, torch, api, wl):
+    """as_select_step (or a packed launch of --pack layers) per layer, predictor as a launch of its own (the library's
+    default) against the predictor in the prologue of the fused selection kernel (per-ctx development mode), on
+    rotating copies of one layer; the two forms must select the same tokens."""
+    import numpy as np
+    w = wl.CONFIGS[a.workload]
+    dev = torch.device("cuda:0")
+    lens_cpu = wl.draw_ctx_lens(w)
+    bt_cpu, num_pages = wl.make_page_table(w, lens_cpu)
+    pack = max(1, a.pack)
+    L = max(3, pack)
+    ks = [wl.make_kv(w, num_pages, dev, l)[0] for l in range(L)]
+    bt, cl = bt_cpu.to(dev), lens_cpu.to(dev)
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1])
+    ctx = api.Context(p, pack=pack)
+    qs = [wl.make_queries(w, dev, l) for l in range(L)]
+    kvs = [api.kv_view(k, None, bt, cl) for k in ks]
+    idx = [torch.empty((w.batch, w.n_kv_heads, w.budget), dtype=torch.int32, device=dev) for _ in range(L)]
+    cnt = [torch.empty((w.batch, w.n_kv_heads), dtype=torch.int32, device=dev) for _ in range(L)]
+    if pack > 1:
+        arr = (api.AsLayerIo * pack)(*[api.layer_io(kvs[l], qs[l][0], qs[l][1], idx[l], cnt[l]) for l in range(pack)])
+        call = lambda i: api.as_select_step_pack(ctx, p, arr)
+    else:
+        call = lambda i: api.as_select_step(ctx, p, kvs[i % L], qs[i % L][0], qs[i % L][1], idx[i % L], cnt[i % L])
+    times, kept = {0: [], 1: []}, {}
+    for mode in (1, 0, 1, 0):
+        ctx.set_predict_mode(mode)
+        for i in range(4):
+            call(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(30):
+            call(i)
+        e1.record()
+        torch.cuda.synchronize()
+        times[mode].append(e0.elapsed_time(e1) / 30 * 1e3 / pack)
+        kept[mode] = [(idx[l].clone(), cnt[l].clone()) for l in range(L)]
+    same = all(torch.equal(x[0], y[0]) and torch.equal(x[1], y[1]) for x, y in zip(kept[0], kept[1]))
+    fused_route = api.select_plan(p, pack)
+    print(json.dumps({"probe": "predictor", "workload": a.workload, "layers_per_launch": pack,
+                      "own_launch_us_per_layer": round(float(np.mean(times[0])), 1),
+                      "in_selection_prologue_us_per_layer": round(float(np.mean(times[1])), 1),
+                      "identical_selections": same, "share_plan": list(fused_route)}))
+
+
+def probe_timeline(a, torch, api, wl):
+    """Entry and exit clock of every workgroup of one as_score_topk launch and one as_sparse_decode_attn launch on a
+    layer of the workload (per-ctx development hook, 100 MHz device clock): span, average number of busy compute
+    units, and how many workgroups run at each twentieth of the span."""
+    import numpy as np
+    w = wl.CONFIGS[a.workload]
+    if a.budget:
+        w = wl.scaled(w, budget=a.budget)
+    dev = torch.device("cuda:0")
+    inp = wl.make_inputs(w, dev)
+    other = wl.make_kv(w, inp.num_pages, dev, 1)             # a second copy, so that the marked launch reads cold rows
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, inp.max_pages)
+    ctx = api.Context(p)
+    kv = api.kv_view(inp.k_pool, inp.v_pool, inp.block_table, inp.ctx_lens)
+    kv2 = api.kv_view(other[0], other[1], inp.block_table, inp.ctx_lens)
+    q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur)
+    tb = torch.zeros((8192, 2), dtype=torch.int64, device=dev)
+    out = {"probe": "timeline", "workload": a.workload, "budget": w.budget, "share_plan": list(api.select_plan(p))}
+    for name, fn in (("as_score_topk", lambda k: api.as_score_topk(ctx, p, k, q_hat)),
+                     ("as_sparse_decode_attn", None)):
+        if fn is None:
+            idx, cnt = api.as_score_topk(ctx, p, kv, q_hat)
+            fn = lambda k: api.as_sparse_decode_attn(ctx, p, k, inp.q_real, idx, cnt, want_lse=False)
+        for _ in range(2):
+            fn(kv2)
+        torch.cuda.synchronize()
+        tb.zero_()
+        ctx.set_timeline(tb)
+        fn(kv)
+        torch.cuda.synchronize()
+        ctx.set_timeline(None)
+        t = tb.cpu().numpy().astype(np.float64)
+        t = t[t[:, 1] > 0]
+        t = (t - t[:, 0].min()) / 100.0
+        span = float(t[:, 1].max())
+        busy = float((t[:, 1] - t[:, 0]).sum())
+        out[name] = {"workgroups": int(len(t)), "span_us": round(span, 1),
+                     "mean_workgroup_us": round(busy / len(t), 1), "mean_running_workgroups": round(busy / span, 1),
+                     "last_start_us": round(float(t[:, 0].max()), 1),
+                     "end_us_p0_p10_p50_p90_p100": [round(float(x), 1) for x in np.percentile(t[:, 1], [0, 10, 50, 90, 100])],
+                     "running_at_each_20th_of_span": [int(((t[:, 0] <= x) & (t[:, 1] > x)).sum())
+                                                      for x in np.linspace(0, span, 21)]}
+    print(json.dumps(out))
+
+
 def csrc_sha16():
     """Fingerprint of the kernel sources the library is built from: stored byte counts (profiles/traffic.json) are
     reported only while it matches."""
@@ -203,7 +297,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
     if a.probe:
-        {"traffic": probe_traffic, "attn-splits": probe_attn_splits}[a.probe](a, torch, api, wl)
+        {"traffic": probe_traffic, "attn-splits": probe_attn_splits, "predictor": probe_predictor,
+         "timeline": probe_timeline}[a.probe](a, torch, api, wl)
         return
 
     w = wl.CONFIGS[a.workload]

@@ -31,6 +31,13 @@ AS_API as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_
  * (where a share plan exists). */
 AS_API as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode);
 
+/* Where the predictor of as_select_step / as_select_step_pack runs for THIS ctx: 0 = as a launch of its own (the
+ * default: measured faster on every benchmark workload), 1 = in the prologue of the fused selection kernel wherever
+ * that kernel can (windows of up to 16 queries, groups of up to 16 heads, max or sum aggregation, fused route):
+ * up to eight wavefronts of each workgroup predict one head each before the workgroup starts to stream.  Results
+ * are identical, bit for bit. */
+AS_API as_status as_debug_set_predict_mode(as_ctx* ctx, int32_t mode);
+
 /* Forces the number of attention splits per (sequence, KV head) for THIS ctx (0 = the library's rule).  A forced
  * count that needs more partial buffers than the ctx workspace holds makes the attention calls return
  * AS_ERR_WORKSPACE; as_debug_attn_workspace_bytes gives the bytes the attention region needs under a forced count. */

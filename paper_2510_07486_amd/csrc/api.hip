@@ -104,15 +104,21 @@ as_status check_select_step(const as_params* p, const as_kv_view* kv, const void
 }
 
 // One layer-step of selection with its scratch regions given explicitly (parts of the ctx workspace, or of the
-// static scratch array): q_hat always, then the score rows (stand-alone stages) or the candidate region (fused
-// kernels), whichever the route needs.
-as_status select_step_on(float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, const as_params* p,
-                         const as_kv_view* kv, const void* q_win, const void* q_cur, int32_t* sel_idx,
-                         int32_t* sel_cnt, asx::wg_timeline tl, hipStream_t s) {
-  hipError_t e = asx::launch_predict(p, static_cast<const uint16_t*>(q_win), static_cast<const uint16_t*>(q_cur),
-                                     q_hat, s);
+// static scratch array): q_hat, then the score rows (stand-alone stages) or the candidate region (fused
+// kernels), whichever the route needs.  The predictor is a launch of its own (measured faster in every workload);
+// with predict_mode 1 and a shape whose fused selection kernel can run the predictor in its own prologue, no
+// separate predictor launch is made and q_hat is not used at all.
+as_status select_step_on(float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, int predict_mode,
+                         const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
+                         int32_t* sel_idx, int32_t* sel_cnt, asx::wg_timeline tl, hipStream_t s) {
+  const uint16_t* qw = static_cast<const uint16_t*>(q_win);
+  const uint16_t* qc = static_cast<const uint16_t*>(q_cur);
+  if (!stages && predict_mode == 1 && asx::select_can_predict(p))
+    return hip_status(asx::launch_select_fused(p, kv, nullptr, qw, qc, cand, sel_idx, sel_cnt, tl, s));
+  hipError_t e = asx::launch_predict(p, qw, qc, q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
-  if (!stages) return hip_status(asx::launch_select_fused(p, kv, q_hat, cand, sel_idx, sel_cnt, tl, s));
+  if (!stages)
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, cand, sel_idx, sel_cnt, tl, s));
   return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, sel_idx, sel_cnt, s));
 }
 
@@ -162,6 +168,7 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->ws_bytes = workspace_bytes;
   c->select_mode = 0;
   c->attn_splits = 0;
+  c->predict_mode = 0;
   c->timeline = nullptr;
   c->timeline_cap = 0;
   if (workspace_bytes > 0) {
@@ -271,7 +278,7 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   char* ws = static_cast<char*>(ctx->ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!stages)
-    return hip_status(asx::launch_select_fused(p, kv, q_hat, ws + l.cand, sel_idx, sel_cnt,
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, ws + l.cand, sel_idx, sel_cnt,
                                                asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
   return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
                                     sel_cnt, s));
@@ -286,8 +293,8 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
   return select_step_on(reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
-                        ws + l.cand, use_stages(ctx->select_mode, p), p, kv, q_win, q_cur, sel_idx, sel_cnt,
-                        asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
+                        ws + l.cand, use_stages(ctx->select_mode, p), ctx->predict_mode, p, kv, q_win, q_cur, sel_idx,
+                        sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
 }
 
 as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
@@ -307,8 +314,8 @@ as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const 
   char* base = static_scratch(device);    // this GPU's copy of the array (its address is resolved once per device)
   if (!base) return AS_ERR_HIP;
   return select_step_on(reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + region_off), score_stride,
-                        base + region_off, stages, p, kv, q_win, q_cur, sel_idx, sel_cnt, asx::wg_timeline{nullptr, 0},
-                        static_cast<hipStream_t>(stream));
+                        base + region_off, stages, 0, p, kv, q_win, q_cur, sel_idx, sel_cnt,
+                        asx::wg_timeline{nullptr, 0}, static_cast<hipStream_t>(stream));
 }
 
 size_t as_workspace_bytes_pack(const as_params* p, int32_t n_layers) {
@@ -347,9 +354,17 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     stab.last_page[l] = (int32_t)(layers[l].kv.num_pages - 1);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
-  if (e != hipSuccess) return AS_ERR_HIP;
-  return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand, s));
+  const bool fuse = ctx->predict_mode == 1 && asx::select_can_predict(p);   // predictor in the selection kernel's prologue
+  if (fuse) {
+    for (int l = 0; l < n_layers; ++l) {
+      stab.q_win[l] = pt.q_win[l];
+      stab.q_cur[l] = pt.q_cur[l];
+    }
+  } else {
+    hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
+    if (e != hipSuccess) return AS_ERR_HIP;
+  }
+  return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand, fuse, s));
 }
 
 as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
@@ -429,6 +444,12 @@ as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_lay
 as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode) {
   if (!ctx || mode < 0 || mode > 2) return AS_ERR_INVALID_ARG;
   ctx->select_mode = mode;
+  return AS_OK;
+}
+
+as_status as_debug_set_predict_mode(as_ctx* ctx, int32_t mode) {
+  if (!ctx || mode < 0 || mode > 1) return AS_ERR_INVALID_ARG;
+  ctx->predict_mode = mode;
   return AS_OK;
 }
 

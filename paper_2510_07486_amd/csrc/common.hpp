@@ -22,6 +22,8 @@ struct as_ctx {
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
                         1: always the separate kernels via HBM scores, 2: always fused */
   int attn_splits;   /* > 0: forced number of attention splits per (sequence, KV head) */
+  int predict_mode;  /* 0: the predictor is a launch of its own, 1: it runs in the prologue of the fused selection
+                        kernel where that kernel can */
   long long* timeline;   /* development: device buffer that receives wall_clock64 at entry and exit of every */
   int timeline_cap;      /* workgroup of the selection and attention kernels (pairs), and its capacity in pairs */
 };
@@ -33,10 +35,16 @@ struct wg_timeline {
   long long* buf;
   int cap;
 };
-__device__ __forceinline__ void timeline_mark(const wg_timeline& tl, int which) {
+// The entry clock is only read (it stays in scalar registers); both marks are stored at the exit.  A store at the
+// very start of a kernel was measured to cost the selection kernel a quarter more vector registers.
+__device__ __forceinline__ long long timeline_begin(const wg_timeline& tl) { return tl.buf ? wall_clock64() : 0; }
+__device__ __forceinline__ void timeline_end(const wg_timeline& tl, long long t_in) {
   if (tl.buf && threadIdx.x == 0) {
     const int wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    if (wg < tl.cap) tl.buf[2 * wg + which] = wall_clock64();
+    if (wg < tl.cap) {
+      tl.buf[2 * wg] = t_in;
+      tl.buf[2 * wg + 1] = wall_clock64();
+    }
   }
 }
 
@@ -74,6 +82,11 @@ struct sel_tab {
   int32_t* sel_cnt[AS_PACK_MAX];
   int32_t last_page[AS_PACK_MAX];   // num_pages - 1 of the layer's pool (page ids are clamped to it)
   wg_timeline timeline;             // development hook of the slice kernel
+  // predictor in the kernel's prologue (q_hat[] is then unused): the query window and the predictor's parameters
+  const uint16_t* q_win[AS_PACK_MAX];
+  const uint16_t* q_cur[AS_PACK_MAX];
+  double pred_eps, pred_beta;
+  int32_t pred_window, pred_single;
 };
 
 // ---- launchers (host) -------------------------------------------------------------
@@ -96,9 +109,16 @@ select_plan plan_select(const as_params* p, int n_layers);
 bool select_plan_ok(const as_params* p, int n_layers);
 bool select_prefers_stages(const as_params* p);
 size_t select_workspace_bytes(const as_params* p, int n_layers);
-hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s);
-hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
-                               int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl, hipStream_t s);
+// whether the slice kernel of this shape can run the predictor in its prologue (windows of up to 16 queries,
+// groups of up to 16 heads, max / sum aggregation)
+bool select_can_predict(const as_params* p);
+// fuse_predict: tab carries q_win / q_cur instead of q_hat (only where select_can_predict)
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, bool fuse_predict,
+                              hipStream_t s);
+// q_win != nullptr: the predictor runs in the kernel's prologue and q_hat is not read
+hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, const uint16_t* q_win,
+                               const uint16_t* q_cur, void* ws, int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl,
+                               hipStream_t s);
 // partial buffers live in the ctx workspace
 // forced_splits > 0 overrides the split rule (development knob of a ctx)
 size_t attn_workspace_bytes(const as_params* p, int forced_splits);

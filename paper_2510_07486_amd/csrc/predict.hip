@@ -10,6 +10,7 @@
 //   q_hat = sum_i a_i S_i,  a_i = (1/W) sum_{k>=i} w^{(k)}_i,  S = (Q_t, Q_{t-1}, ..., Q_{t-W+1}).
 // Latency-bound and tiny (about 50 kflop per head at W = 16): one dependent chain per head.
 #include "common.hpp"
+#include "predict_common.hpp"
 
 namespace asx {
 
@@ -134,146 +135,17 @@ __global__ __launch_bounds__(64) void predict_kernel(const pred_tab tab, int hea
   }
 }
 
-// Window sizes known at compile time (the paper profiles W = 16), W <= 16.  Same algorithm, laid out for one
-// wavefront:
-//  * the Gram matrix of the W predecessors is one chain of 32 fp64 matrix-core instructions
-//    (v_mfma_f64_16x16x4: G += X_s X_s^T over 32 slices of four dims; lane l supplies X[l % 16][4s + l / 16] as
-//    both operands); the result lands with lane (r = l % 16, q = l / 16) holding G[r][q + 4v], v = 0..3, i.e.
-//    every row spread over four lanes, which is the distribution the factorisation below works in;
-//  * G + eps I = L D L^T (unit lower L, no square roots) by right-looking elimination on the full symmetric
-//    trailing block: per step one reciprocal, the pivot row and column fetched with cross-lane reads, at most four
-//    multiply-adds per lane.  The right-hand side b rides along, so z = L^-1 b and y = D^-1 z come out of the
-//    same loop.  Leading blocks of L and D factor the leading blocks of G: one factorisation serves every window size;
-//  * lane k-1 then back-substitutes L_k^T omega = y_{1:k} on its own, the W(W+1)/2 softmax exponentials are
-//    spread over the 64 lanes.
+// Window sizes known at compile time (the paper profiles W = 16), W <= 16: one wavefront per workgroup runs
+// predict_wave (predict_common.hpp).
 template <int W>
 __global__ __launch_bounds__(64) void predict_kernel_w(const pred_tab tab, int heads_per_layer, double eps,
                                                        double beta, int single) {
-  static_assert(W >= 1 && W <= 16, "one 16 x 16 matrix-core tile holds the Gram matrix");
-  typedef double f64x4 __attribute__((ext_vector_type(4)));
-  constexpr int RW = AS_HEAD_DIM + 4;  // row stride of the staged window: lanes (r, q) read banks 4r + q
-  __shared__ float Rf[(W + 1) * RW];   // row i < W = Q_{t-1-i}, row W = Q_t
-  __shared__ double Ls[W][W + 1];      // L below the diagonal
-  __shared__ double Om[W][W + 1];      // row k-1: beta*omega^{(k)} - max, then exp of it
-  __shared__ double yv[W], zinv[W], av[W];
-
-  const int lane = threadIdx.x;
-  const int r = lane & 15, q = lane >> 4;
+  __shared__ predict_lds<W> S;
   const int layer = blockIdx.x / heads_per_layer;
   const int64_t bh = blockIdx.x - layer * heads_per_layer;
-  float* __restrict__ q_hat = tab.q_hat[layer];
   const uint32_t* win = reinterpret_cast<const uint32_t*>(tab.q_win[layer] + bh * (int64_t)W * AS_HEAD_DIM);
   const uint32_t* cur = reinterpret_cast<const uint32_t*>(tab.q_cur[layer] + bh * (int64_t)AS_HEAD_DIM);
-#pragma unroll
-  for (int i = 0; i < W; ++i) {
-    const uint32_t w2 = win[(int64_t)(W - 1 - i) * (AS_HEAD_DIM / 2) + lane];
-    Rf[i * RW + 2 * lane] = bf16lo(w2);
-    Rf[i * RW + 2 * lane + 1] = bf16hi(w2);
-  }
-  {
-    const uint32_t w2 = cur[lane];
-    Rf[W * RW + 2 * lane] = bf16lo(w2);
-    Rf[W * RW + 2 * lane + 1] = bf16hi(w2);
-  }
-  __syncthreads();
-
-  // Gram matrix on the matrix cores; the rhs b_r = <Q_{t-1-r}, Q_t> from the same operand values
-  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-  double b = 0.0;
-  {
-    const float* xr = Rf + (r < W ? r : 0) * RW + q;
-    const float* tr = Rf + W * RW + q;
-#pragma unroll 8
-    for (int s4 = 0; s4 < AS_HEAD_DIM; s4 += 4) {
-      const double x = r < W ? (double)xr[s4] : 0.0;
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, x, acc, 0, 0, 0);
-      b += x * (double)tr[s4];
-    }
-    b += __shfl_xor(b, 16);
-    b += __shfl_xor(b, 32);
-  }
-  double a[4];   // a[v] = (G + eps I)[r][q + 4v]
-#pragma unroll
-  for (int v = 0; v < 4; ++v) a[v] = acc[v] + (q + 4 * v == r ? eps : 0.0);
-
-  // L D L^T with the rhs carried along
-  auto from_lane = [](double x, int src) -> double {   // src uniform
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src);
-    return __hiloint2double(hi, lo);
-  };
-#pragma unroll
-  for (int j = 0; j < W; ++j) {
-    const int jq = j & 3, jv = j >> 2;                       // column j sits in lanes q = jq, register jv
-    const double inv = 1.0 / from_lane(a[jv], j + 16 * jq);  // pivot D_j
-    const double zj = from_lane(b, j);
-    const double cr = __shfl(a[jv], r + 16 * jq);            // (G)[r][j] after the earlier steps
-    const double lr = r > j ? cr * inv : 0.0;                // L[r][j]
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-      if (4 * v + 3 > j) {                                   // some lane's column q + 4v lies right of j
-        const double rj = __shfl(a[v], j + 16 * q);          // row j, this lane's column
-        if (q + 4 * v > j) a[v] -= lr * rj;
-      }
-    b -= lr * zj;
-    if (q == 0 && r > j && r < W) Ls[r][j] = lr;
-    if (lane == 0) yv[j] = zj * inv;
-  }
-  __syncthreads();
-
-  // lane kk: L_k^T omega = y_{1:k} for k = kk+1, weights stay zero above kk (single-solve mode: every lane
-  // solves the full system; only its kk+1 newest entries enter the softmax below)
-  const int kk = lane;
-  double om[W];
-#pragma unroll
-  for (int i = 0; i < W; ++i) om[i] = 0.0;
-#pragma unroll
-  for (int i = W - 1; i >= 0; --i) {
-    double s = yv[i];
-#pragma unroll
-    for (int m = i + 1; m < W; ++m) s -= Ls[m][i] * om[m];
-    om[i] = (single || i <= kk) ? s : 0.0;
-  }
-  if (kk < W) {
-    double mx = beta * om[0];
-#pragma unroll
-    for (int i = 1; i < W; ++i)
-      if (i <= kk) mx = fmax(mx, beta * om[i]);
-#pragma unroll
-    for (int i = 0; i < W; ++i) Om[kk][i] = beta * om[i] - mx;
-  }
-  __syncthreads();
-  // exponentials of the W(W+1)/2 (k, i) pairs, spread over the lanes
-  for (int p = lane; p < W * (W + 1) / 2; p += 64) {
-    int k = (int)((sqrtf(8.0f * (float)p + 1.0f) - 1.0f) * 0.5f);
-    while (k * (k + 1) / 2 > p) --k;
-    while ((k + 1) * (k + 2) / 2 <= p) ++k;
-    const int i = p - k * (k + 1) / 2;
-    Om[k][i] = exp(Om[k][i]);
-  }
-  __syncthreads();
-  if (kk < W) {
-    double z = 0.0;
-#pragma unroll
-    for (int i = 0; i < W; ++i)
-      if (i <= kk) z += Om[kk][i];
-    zinv[kk] = 1.0 / z;
-  }
-  __syncthreads();
-  if (kk < W) {
-    double sum = 0.0;
-#pragma unroll
-    for (int k2 = 0; k2 < W; ++k2)
-      if (k2 >= kk) sum += Om[k2][kk] * zinv[k2];
-    av[kk] = sum / (double)W;
-  }
-  __syncthreads();
-  for (int d = lane; d < AS_HEAD_DIM; d += 64) {
-    double o = av[0] * (double)Rf[W * RW + d];
-#pragma unroll
-    for (int i = 1; i < W; ++i) o += av[i] * (double)Rf[(i - 1) * RW + d];
-    q_hat[bh * AS_HEAD_DIM + d] = (float)o;
-  }
+  predict_wave<W, false>(win, cur, W, eps, beta, single, S, tab.q_hat[layer] + bh * AS_HEAD_DIM);
 }
 
 hipError_t launch_predict_pack(const as_params* p, int n_layers, const pred_tab& tab, hipStream_t s) {

@@ -26,6 +26,7 @@
 // use shares that fit the buffer whole.  The first sub-slice of a long share has a pseudo-random
 // shorter length so that the prune phases of different compute units do not coincide.
 #include "common.hpp"
+#include "predict_common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
 
@@ -155,7 +156,10 @@ size_t select_workspace_bytes(const as_params* p, int n_layers) {
 // of the softmax-normalised aggregation s[n] = sum_g exp(scale * l[g][n] - LSE_g): pass 1 streams the share and
 // leaves one (max, sum) pair per head in lse_part, pass 2 merges the pairs of all shares of its row into LSE_g
 // and then selects exactly like mode 0 with s[n] as the score.
-template <int NSET, int FS_THREADS, int PG, int MODE>
+// PRED: the query predictor (Sec. 4.2) runs in the prologue: up to eight wavefronts at a time each predict one head
+// of the group from its window (predict_wave, fp64; their scratch borrows the page images and the candidate
+// buffer, which are idle until the stream starts) and leave q_hat in LDS, where the MFMA operand is built from.
+template <int NSET, int FS_THREADS, int PG, int MODE, bool PRED>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const sel_tab tab, int B, int Hq, int Hkv, int G, int agg, int max_pages, int share_len, int nshares, int C,
     int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt,
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
   // sequences (the share) must vary slowest, or the workgroups that do have work pile up on half
   // of the compute units.
-  timeline_mark(tab.timeline, 0);
+  const long long t_in = timeline_begin(tab.timeline);
   const int j = blockIdx.x, sh = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t = lane & 15, grp = lane >> 4;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   const bool final_out = (nshares == 1);
   if (MODE == 1 && n_share == 0) {
     if (tid < G) lse_part[(crow * nshares + sh) * G + tid] = make_float2(-INFINITY, 0.f);
-    timeline_mark(tab.timeline, 1);
+    timeline_end(tab.timeline, t_in);
     return;
   }
   if (n_share == 0) {
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     } else if (tid == 0) {
       cand_cnt[crow * nshares + sh] = 0;
     }
-    timeline_mark(tab.timeline, 1);
+    timeline_end(tab.timeline, t_in);
     return;
   }
 
@@ -265,7 +269,31 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   int32_t my_page = load_pages(0);
 
   bf16x8 aq[NSET][4];
-  build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
+  if constexpr (PRED) {
+    static_assert(MODE == 0 && NSET <= 2 && FS_THREADS == 1024, "hist holds q_hat of up to 16 heads; eight scratch areas");
+    static_assert(sizeof(predict_lds<16>) <= 16384, "four areas in the page images, two each in the candidate arrays");
+    float* qh_sh = reinterpret_cast<float*>(hist);   // [G][128]; hist is next written by a prune, behind a barrier
+    unsigned char* area = wave < 4 ? reinterpret_cast<unsigned char*>(&stage[0][0]) + wave * 16384
+                          : wave < 6 ? reinterpret_cast<unsigned char*>(c_key) + (wave - 4) * 16384
+                                     : reinterpret_cast<unsigned char*>(c_tok) + (wave - 6) * 16384;
+    const int W = tab.pred_window;
+#pragma unroll 1
+    for (int h0 = 0; h0 < G; h0 += 8) {
+      const int h = h0 + wave;
+      if (wave < 8 && h < G) {
+        const int64_t bh = (int64_t)b * Hq + (int64_t)j * G + h;
+        predict_wave<16, true>(reinterpret_cast<const uint32_t*>(tab.q_win[layer] + bh * W * AS_HEAD_DIM),
+                               reinterpret_cast<const uint32_t*>(tab.q_cur[layer] + bh * AS_HEAD_DIM), W, tab.pred_eps,
+                               tab.pred_beta, tab.pred_single, *reinterpret_cast<predict_lds<16>*>(area),
+                               qh_sh + h * AS_HEAD_DIM);
+      }
+    }
+    __syncthreads();
+    build_q_operand<NSET>(qh_sh, 0, 0, 0, G, agg, lane, aq);   // the group's rows start at qh_sh
+    __syncthreads();   // the scratch areas become page images and candidates again
+  } else {
+    build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
+  }
 
   // softmax modes: the lane's accumulators of operand set s belong to heads s*8 + 2*grp and s*8 + 2*grp + 1
   float hm[NSET][2], hl[NSET][2];   // pass 1: running (max, sum of exp) of this lane's token column; pass 2: hm = LSE
@@ -475,7 +503,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       }
       lse_part[(crow * nshares + sh) * G + tid] = make_float2(m, l);
     }
-    timeline_mark(tab.timeline, 1);
+    timeline_end(tab.timeline, t_in);
     return;
   }
 
@@ -547,7 +575,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
     }
   }
-  timeline_mark(tab.timeline, 1);
+  timeline_end(tab.timeline, t_in);
 }
 
 // Reduces a row's per-slice candidates (ascending token order within and across slices) to
@@ -664,10 +692,22 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
   if (tid == 0) sel_cnt[row] = keep;
 }
 
-hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, hipStream_t s) {
+bool select_can_predict(const as_params* p) {
+  const int G = p->n_q_heads / p->n_kv_heads;
+  return p->window <= 16 && p->agg != AS_AGG_SOFTMAX_SUM && (p->agg == AS_AGG_SUM || G <= 16);
+}
+
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab_in, void* ws, bool fuse_predict,
+                              hipStream_t s) {
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
   if (rows == 0) return hipSuccess;
   if ((int64_t)p->batch * n_layers > 65535) return hipErrorInvalidValue;   // grid.y
+  if (fuse_predict && !select_can_predict(p)) return hipErrorInvalidValue;
+  sel_tab tab = tab_in;
+  tab.pred_window = p->window;
+  tab.pred_single = p->predictor == AS_PRED_SINGLE_SOLVE ? 1 : 0;
+  tab.pred_eps = (double)p->ridge_eps;
+  tab.pred_beta = (double)p->softmax_beta;
   const select_plan pl = plan_select(p, n_layers);
   const int G = p->n_q_heads / p->n_kv_heads;
   uint32_t* cand_key = nullptr;
@@ -681,21 +721,21 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   dim3 grid(p->n_kv_heads, p->batch * n_layers, pl.nslices);
   const int nset = (p->agg == AS_AGG_SUM || G <= 8) ? 1 : G <= 16 ? 2 : G <= 32 ? 4 : 8;
   float2* lse_part = reinterpret_cast<float2*>(static_cast<char*>(ws) + cand_bytes(p, pl, n_layers));
-#define AS_SLICE_LAUNCH(NSET_, THR_, MODE_)                                                                       \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG, MODE_>), grid, dim3(THR_), 0, s, tab, p->batch,     \
-                     p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len, pl.nslices,      \
-                     p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
+#define AS_SLICE_LAUNCH(NSET_, THR_, MODE_, PRED_)                                                                \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG, MODE_, PRED_>), grid, dim3(THR_), 0, s, tab,        \
+                     p->batch, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len,        \
+                     pl.nslices, p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
   // groups of up to 16 heads (one or two operand sets) run 1024-thread workgroups, larger ones the 512-thread shape
   if (p->agg == AS_AGG_SOFTMAX_SUM) {
     // two passes over K with the same grid: per-share (max, sum) pairs, then selection on the normalised scores
-    if (nset == 8) { AS_SLICE_LAUNCH(8, 512, 1); AS_SLICE_LAUNCH(8, 512, 2); }
-    else if (nset == 4) { AS_SLICE_LAUNCH(4, 512, 1); AS_SLICE_LAUNCH(4, 512, 2); }
-    else if (nset == 2) { AS_SLICE_LAUNCH(2, 1024, 1); AS_SLICE_LAUNCH(2, 1024, 2); }
-    else { AS_SLICE_LAUNCH(1, 1024, 1); AS_SLICE_LAUNCH(1, 1024, 2); }
-  } else if (nset == 8) AS_SLICE_LAUNCH(8, 512, 0);
-  else if (nset == 4) AS_SLICE_LAUNCH(4, 512, 0);
-  else if (nset == 2) AS_SLICE_LAUNCH(2, 1024, 0);
-  else AS_SLICE_LAUNCH(1, 1024, 0);
+    if (nset == 8) { AS_SLICE_LAUNCH(8, 512, 1, false); AS_SLICE_LAUNCH(8, 512, 2, false); }
+    else if (nset == 4) { AS_SLICE_LAUNCH(4, 512, 1, false); AS_SLICE_LAUNCH(4, 512, 2, false); }
+    else if (nset == 2) { AS_SLICE_LAUNCH(2, 1024, 1, false); AS_SLICE_LAUNCH(2, 1024, 2, false); }
+    else { AS_SLICE_LAUNCH(1, 1024, 1, false); AS_SLICE_LAUNCH(1, 1024, 2, false); }
+  } else if (nset == 8) AS_SLICE_LAUNCH(8, 512, 0, false);
+  else if (nset == 4) AS_SLICE_LAUNCH(4, 512, 0, false);
+  else if (nset == 2) { if (fuse_predict) AS_SLICE_LAUNCH(2, 1024, 0, true); else AS_SLICE_LAUNCH(2, 1024, 0, false); }
+  else { if (fuse_predict) AS_SLICE_LAUNCH(1, 1024, 0, true); else AS_SLICE_LAUNCH(1, 1024, 0, false); }
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || pl.nslices == 1) return e;
@@ -710,10 +750,13 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   return hipGetLastError();
 }
 
-hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, void* ws,
-                               int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl, hipStream_t s) {
+hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, const uint16_t* q_win,
+                               const uint16_t* q_cur, void* ws, int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl,
+                               hipStream_t s) {
   sel_tab tab = {};
   tab.timeline = tl;
+  tab.q_win[0] = q_win;
+  tab.q_cur[0] = q_cur;
   tab.k_pool[0] = reinterpret_cast<const uint16_t*>(kv->k_pool);
   tab.block_table[0] = kv->block_table;
   tab.ctx_lens[0] = kv->ctx_lens;
@@ -721,7 +764,7 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
   tab.sel_idx[0] = sel_idx;
   tab.sel_cnt[0] = sel_cnt;
   tab.last_page[0] = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
-  return launch_select_pack(p, 1, tab, ws, s);
+  return launch_select_pack(p, 1, tab, ws, q_win != nullptr, s);
 }
 
 }  // namespace asx
