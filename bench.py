@@ -49,13 +49,17 @@ def parse():
     ap.add_argument("--graph", action="store_true", help="time the overlapped schedule as HIP graph replays (two graphs, "
                     "one per selection buffer parity) instead of eager launches")
     ap.add_argument("--pack", type=int, default=1, help="layers per packed selection launch (as_select_step_pack)")
-    ap.add_argument("--probe", default="", choices=["", "traffic", "attn-splits", "predictor", "timeline"],
+    ap.add_argument("--probe", default="", choices=["", "traffic", "attn-splits", "predictor", "timeline", "gather-compact"],
                     help="instead of the benchmark: 'traffic' launches the calibration kernels and every kernel of the "
                          "path a few times on one layer (the program rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs on); "
                          "'attn-splits' sweeps the forced attention split count (--splits); 'predictor' times as_select_step "
                          "(--pack > 1: as_select_step_pack) with the predictor as its own launch and inside the selection "
                          "kernel's prologue; 'timeline' prints when the workgroups of the selection and attention kernels "
-                         "start and end")
+                         "start and end; 'gather-compact' times the KV re-organisation and dense attention over the compact "
+                         "pool against in-kernel index gathers")
+    ap.add_argument("--write-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
+                    help="no GPU work: turns the counter_collection.csv files of the two rocprofv3 --pmc runs of "
+                         "'--probe traffic' (FETCH_SIZE, then WRITE_SIZE) into profiles/traffic.json for --workload")
     ap.add_argument("--splits", default="0,1,2,3,4,6,8,12,16", help="split counts of --probe attn-splits (0 = the rule)")
     ap.add_argument("--reps", type=int, default=3, help="launches per kernel of --probe traffic")
     return ap.parse_args()
@@ -234,6 +238,85 @@ def probe_timeline(a, torch, api, wl):
     print(json.dumps(out))
 
 
+def probe_gather_compact(a, torch, api, wl):
+    """KV re-organisation (as_gather_kv) + dense attention over the compact pool against sparse attention with
+    in-kernel index gathers, and full attention over the whole cache; three resident layers cycled."""
+    w = wl.CONFIGS[a.workload]
+    dev = torch.device("cuda:0")
+    lens_cpu = wl.draw_ctx_lens(w)
+    bt_cpu, num_pages = wl.make_page_table(w, lens_cpu)
+    L = 3
+    layers = [wl.make_kv(w, num_pages, dev, l) for l in range(L)]
+    qw, qc, qr = wl.make_queries(w, dev, 0)
+    bt, cl = bt_cpu.to(dev), lens_cpu.to(dev)
+    p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, bt.shape[1])
+    ctx = api.Context(p)
+    kvs = [api.kv_view(k, v, bt, cl) for k, v in layers]
+    sels = [api.as_select_step(ctx, p, kv, qw, qc) for kv in kvs]
+    pc = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, 16, api.compact_pages(p))
+    ctxc = api.Context(pc)
+    comp = [api.as_gather_kv(ctx, p, kvs[l], *sels[l]) for l in range(L)]
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+
+    def timeit(fn, n=30):
+        for i in range(5):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+
+    t_g = timeit(lambda i: api.as_gather_kv(ctx, p, kvs[i % L], sels[i % L][0], sels[i % L][1], *comp[i % L]))
+    t_s = timeit(lambda i: api.as_sparse_decode_attn(ctx, p, kvs[i % L], qr, sels[i % L][0], sels[i % L][1], out=out,
+                                                     want_lse=False))
+    kvc = [api.kv_view(*c) for c in comp]
+    t_d = timeit(lambda i: api.as_dense_decode_attn(ctxc, pc, kvc[i % L], qr, out=out, want_lse=False))
+    t_f = timeit(lambda i: api.as_dense_decode_attn(ctx, p, kvs[i % L], qr, out=out, want_lse=False), n=10)
+    x = api.as_sparse_decode_attn(ctx, p, kvs[0], qr, sels[0][0], sels[0][1])[0]
+    y = api.as_dense_decode_attn(ctxc, pc, kvc[0], qr)[0]
+    rows = int(torch.clamp(lens_cpu, max=w.budget).sum()) * w.n_kv_heads
+    print(json.dumps({"probe": "gather-compact", "workload": a.workload, "gather_kv_us": round(t_g, 1),
+                      "gather_kv_gbs_read_plus_write": round(2 * rows * 512 / t_g / 1e3),
+                      "sparse_attn_index_gathers_us": round(t_s, 1), "dense_attn_over_compact_pool_us": round(t_d, 1),
+                      "full_attn_us": round(t_f, 1), "full_attn_gbs": round(int(lens_cpu.sum()) * w.n_kv_heads * 512 / t_f / 1e3),
+                      "outputs_bit_identical": bool(torch.equal(x, y))}))
+
+
+def write_traffic(a):
+    """profiles/traffic.json from the two --pmc runs of `--probe traffic`: per kernel, FETCH_SIZE and WRITE_SIZE (KiB
+    per dispatch, averaged) scaled by what the same counter reads for the calibration kernel of known size."""
+    import collections
+    import csv
+    from paper_2510_07486_amd import workloads as wl
+    w = wl.CONFIGS[a.workload]
+    tokens = int(wl.draw_ctx_lens(w).sum())
+    known = {"fetch": tokens * w.n_kv_heads * 256 / 1024, "write": tokens * w.n_kv_heads * 4 / 1024}   # KiB
+    res = {}
+    for nm, path in zip(("fetch", "write"), a.write_traffic):
+        agg = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            if "asx" in r["Kernel_Name"]:
+                agg[r["Kernel_Name"].split("(")[0].replace("void ", "")].append(float(r["Counter_Value"]))
+        res[nm] = {k: sum(v) / len(v) for k, v in agg.items()}
+    cal = "asx::stream_read_paged<true>"
+    scale = {nm: known[nm] / res[nm][cal] for nm in ("fetch", "write")}
+    per = {k: {"fetch_kib_raw": round(res["fetch"][k], 1), "write_kib_raw": round(res["write"].get(k, 0.0), 1),
+               "bytes": int((res["fetch"][k] * scale["fetch"] + res["write"].get(k, 0.0) * scale["write"]) * 1024)}
+           for k in res["fetch"]}
+    sel = sum(v["bytes"] for k, v in per.items() if "select_slice_kernel" in k or "select_merge_kernel" in k)
+    tf = os.path.join(ROOT, "profiles", "traffic.json")
+    allw = json.load(open(tf)) if os.path.exists(tf) else {}
+    allw[a.workload] = {"score_keys_hbm_bytes_per_launch": sel, "per_kernel": per, "fetch_scale": scale["fetch"],
+                        "write_scale": scale["write"], "csrc_sha16": csrc_sha16(),
+                        "source": f"profiles/traffic_{a.workload}_pmc.md"}
+    json.dump(allw, open(tf, "w"), indent=1)
+    print(json.dumps(allw[a.workload], indent=1))
+
+
 def csrc_sha16():
     """Fingerprint of the kernel sources the library is built from: stored byte counts (profiles/traffic.json) are
     reported only while it matches."""
@@ -282,6 +365,9 @@ def selection_parity(gidx, gcnt, ridx, rcnt, scores, lens):
 
 def main():
     a = parse()
+    if a.write_traffic:
+        write_traffic(a)
+        return
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; nothing is split across GPUs, so --gpus must be 1 "
               f"(got {a.gpus}).", file=sys.stderr)
@@ -298,7 +384,7 @@ def main():
     torch.cuda.set_device(0)
     if a.probe:
         {"traffic": probe_traffic, "attn-splits": probe_attn_splits, "predictor": probe_predictor,
-         "timeline": probe_timeline}[a.probe](a, torch, api, wl)
+         "timeline": probe_timeline, "gather-compact": probe_gather_compact}[a.probe](a, torch, api, wl)
         return
 
     w = wl.CONFIGS[a.workload]

@@ -36,9 +36,10 @@ __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
-// WAVES = 4: 37 KB of LDS, three workgroups fit a compute unit; WAVES = 8: 73 KB, two fit.  When the grid has fewer
-// workgroups than that, the launch pads the LDS request (see launch_attn_mfma) so that no compute unit gets more
-// than its even share: the dispatcher otherwise puts three on one compute unit and one on another.
+// WAVES = 4: 37 KB of LDS, three workgroups fit a compute unit; WAVES = 8: 73 KB, two fit.  (Padding the LDS
+// request so that a compute unit cannot take more than its even share of a grid was measured: nothing gained
+// alone, and beside the selection kernel, whose workgroups own a compute unit each, attention then waits for
+// whole compute units instead of packing into the free ones: batch 16, 64/8 heads, 216 -> 253 us per layer-step.)
 template <int WAVES> struct am_shape {
   static constexpr int LDS = WAVES * AM_WAVE_LDS < WAVES * 16 * AS_HEAD_DIM * 4 ? WAVES * 16 * AS_HEAD_DIM * 4 : WAVES * AM_WAVE_LDS;
 };
@@ -277,33 +278,8 @@ hipError_t launch_attn_mfma(const as_params* p, const as_kv_view* kv, const uint
                             hipStream_t s) {
   const int G = p->n_q_heads / p->n_kv_heads;
   dim3 grid(nsplit, p->n_kv_heads * ((G + 15) / 16), p->batch);
-  // even share of workgroups per compute unit; the LDS request is padded with unused dynamic LDS until no more than
-  // that many fit (160 KB per compute unit)
-  int cus = 256, dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-    cus = 256;
-  const int64_t wgs = (int64_t)grid.x * grid.y * grid.z;
-  const int64_t share = (wgs + cus - 1) / cus;
-  const int used = (waves == 8 ? am_shape<8>::LDS : am_shape<4>::LDS) + 1024;   // + the small arrays and rounding
-  constexpr int CU_LDS = 160 * 1024;
-  int pad = 0;
-  if (share >= 1 && share <= 3) {
-    const int request = CU_LDS / (int)(share + 1) + 256;     // share + 1 of these do not fit a compute unit ...
-    if (request * share <= CU_LDS && request > used) pad = request - used;   // ... share of them do
-  }
-  if (pad > 0) {   // dynamic LDS beyond the default limit has to be allowed once per kernel
-    static int allowed[2] = {0, 0};
-    int& a = allowed[waves == 8 ? 1 : 0];
-    if (pad > a) {
-      const void* fn = waves == 8 ? reinterpret_cast<const void*>(attn_mfma_kernel<8>)
-                                  : reinterpret_cast<const void*>(attn_mfma_kernel<4>);
-      const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-      if (e != hipSuccess) return e;
-      a = 64 * 1024;
-    }
-  }
 #define AS_ATTN_LAUNCH(WAVES_)                                                                                        \
-  hipLaunchKernelGGL(attn_mfma_kernel<WAVES_>, grid, dim3(WAVES_ * 64), (size_t)pad, s,                               \
+  hipLaunchKernelGGL(attn_mfma_kernel<WAVES_>, grid, dim3(WAVES_ * 64), 0, s,                                         \
                      reinterpret_cast<const uint16_t*>(kv->k_pool), reinterpret_cast<const uint16_t*>(kv->v_pool),    \
                      kv->block_table, kv->ctx_lens, q, sel_idx, sel_cnt, sel_ctx_lens, part_o, part_ml, out, lse,     \
                      p->n_q_heads, p->n_kv_heads, G, sel_idx ? p->budget : 0, p->max_pages_per_seq, p->sm_scale,      \

@@ -42,6 +42,8 @@ template <int THREADS> struct fs_shape {
                                                           // a share's selection has one bit per token (8 KB / 2 KB)
 };
 static constexpr int FS_PG = 2;             // pages a wave loads per iteration (8 KB in flight per wave)
+static constexpr int FS_PG4 = 4;            // ... of the four-operand-set instance: its 512-thread workgroups leave a compute
+                                            // unit with 8 wavefronts instead of 16, so each keeps twice the bytes in flight
 static constexpr int FS_MAX_SLICES = 1024;  // shares per row the merge kernel can index (one per thread)
 
 static int device_cus() {
@@ -722,7 +724,7 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   const int nset = (p->agg == AS_AGG_SUM || G <= 8) ? 1 : G <= 16 ? 2 : G <= 32 ? 4 : 8;
   float2* lse_part = reinterpret_cast<float2*>(static_cast<char*>(ws) + cand_bytes(p, pl, n_layers));
 #define AS_SLICE_LAUNCH(NSET_, THR_, MODE_, PRED_)                                                                \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, FS_PG, MODE_, PRED_>), grid, dim3(THR_), 0, s, tab,        \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, (NSET_ == 4 ? FS_PG4 : FS_PG), MODE_, PRED_>), grid, dim3(THR_), 0, s, tab, \
                      p->batch, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len,        \
                      pl.nslices, p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
   // groups of up to 16 heads (one or two operand sets) run 1024-thread workgroups, larger ones the 512-thread shape
