@@ -62,6 +62,8 @@ def parse():
                          "'--probe traffic' (FETCH_SIZE, then WRITE_SIZE) into profiles/traffic.json for --workload")
     ap.add_argument("--splits", default="0,1,2,3,4,6,8,12,16", help="split counts of --probe attn-splits (0 = the rule)")
     ap.add_argument("--reps", type=int, default=3, help="launches per kernel of --probe traffic")
+    ap.add_argument("--force-fused", action="store_true", help="--probe timeline: run the fused selection kernels even where "
+                    "the library would pick the stand-alone stages (few-row shapes)")
     return ap.parse_args()
 
 
@@ -201,16 +203,23 @@ def probe_timeline(a, torch, api, wl):
     w = wl.CONFIGS[a.workload]
     if a.budget:
         w = wl.scaled(w, budget=a.budget)
+    if a.batch:
+        w = wl.scaled(w, batch=a.batch)
+    if a.ctx:
+        w = wl.scaled(w, ctx=a.ctx)
     dev = torch.device("cuda:0")
     inp = wl.make_inputs(w, dev)
     other = wl.make_kv(w, inp.num_pages, dev, 1)             # a second copy, so that the marked launch reads cold rows
     p = api.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.window, w.budget, inp.max_pages)
     ctx = api.Context(p)
+    if a.force_fused:
+        ctx.set_select_mode(2)
     kv = api.kv_view(inp.k_pool, inp.v_pool, inp.block_table, inp.ctx_lens)
     kv2 = api.kv_view(other[0], other[1], inp.block_table, inp.ctx_lens)
     q_hat = api.as_predict_query(ctx, p, inp.q_win, inp.q_cur)
     tb = torch.zeros((8192, 2), dtype=torch.int64, device=dev)
-    out = {"probe": "timeline", "workload": a.workload, "budget": w.budget, "share_plan": list(api.select_plan(p))}
+    out = {"probe": "timeline", "workload": a.workload, "batch": w.batch, "context": w.ctx, "budget": w.budget,
+           "share_plan": list(api.select_plan(p))}
     for name, fn in (("as_score_topk", lambda k: api.as_score_topk(ctx, p, k, q_hat)),
                      ("as_sparse_decode_attn", None)):
         if fn is None:
@@ -226,6 +235,9 @@ def probe_timeline(a, torch, api, wl):
         ctx.set_timeline(None)
         t = tb.cpu().numpy().astype(np.float64)
         t = t[t[:, 1] > 0]
+        if len(t) == 0:                                      # this shape runs kernels that carry no marks
+            out[name] = None
+            continue
         t = (t - t[:, 0].min()) / 100.0
         span = float(t[:, 1].max())
         busy = float((t[:, 1] - t[:, 0]).sum())
