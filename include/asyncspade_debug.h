@@ -31,6 +31,11 @@ AS_API as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_
  * (where a share plan exists). */
 AS_API as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode);
 
+/* How rows that the fused selection cuts into several shares are merged for THIS ctx: 0 = inside the selection kernel
+ * by the last workgroup of the row to finish, wherever the row's candidates fit that kernel's LDS buffer (the
+ * default), 1 = always by a second launch.  Results are identical, bit for bit. */
+AS_API as_status as_debug_set_merge_mode(as_ctx* ctx, int32_t mode);
+
 /* Where the predictor of as_select_step / as_select_step_pack runs for THIS ctx: 0 = as a launch of its own (the
  * default: measured faster on every benchmark workload), 1 = in the prologue of the fused selection kernel wherever
  * that kernel can (windows of up to 16 queries, groups of up to 16 heads, max or sum aggregation, fused route):

@@ -26,7 +26,7 @@ EXPORTS = ["as_workspace_bytes", "as_workspace_bytes_attn", "as_create", "as_des
            "as_dense_decode_attn"]
 # development / measurement entry points (include/asyncspade_debug.h)
 DEBUG_EXPORTS = ["as_debug_select_plan", "as_debug_workspace_gaps", "as_debug_set_select_mode",
-                 "as_debug_set_attn_splits", "as_debug_set_timeline", "as_debug_set_predict_mode", "as_debug_attn_workspace_bytes", "as_debug_stream_read_paged",
+                 "as_debug_set_attn_splits", "as_debug_set_timeline", "as_debug_set_predict_mode", "as_debug_set_merge_mode", "as_debug_attn_workspace_bytes", "as_debug_stream_read_paged",
                  "as_debug_stream_read_flat", "as_debug_stream_read_flat_sink_words"]
 AS_MAX_PACK = 16
 AS_STATIC_SCRATCH_BYTES = 48 << 20
@@ -111,6 +111,8 @@ def lib():
         L.as_debug_set_select_mode.argtypes = [vp, C.c_int32]
         L.as_debug_set_attn_splits.restype = C.c_int
         L.as_debug_set_attn_splits.argtypes = [vp, C.c_int32]
+        L.as_debug_set_merge_mode.restype = C.c_int
+        L.as_debug_set_merge_mode.argtypes = [vp, C.c_int32]
         L.as_debug_set_predict_mode.restype = C.c_int
         L.as_debug_set_predict_mode.argtypes = [vp, C.c_int32]
         L.as_debug_set_timeline.restype = C.c_int
@@ -219,6 +221,10 @@ class Context:
         with attn_workspace_bytes_forced for the largest count used."""
         _check(lib().as_debug_set_attn_splits(self.handle, n), "as_debug_set_attn_splits")
 
+
+    def set_merge_mode(self, m: int):
+        """0 = multi-share rows are merged inside the selection kernel where possible (default), 1 = by a second launch."""
+        _check(lib().as_debug_set_merge_mode(self.handle, m), "as_debug_set_merge_mode")
 
     def set_predict_mode(self, m: int):
         """0 = the predictor is a launch of its own (default), 1 = in the prologue of the fused selection kernel where possible."""

@@ -16,9 +16,13 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 constexpr size_t WS_GAP = 256;          // never written by a kernel: separates the regions of the workspace
 constexpr unsigned char WS_FILL = 0xA5;  // what as_create fills the workspace with
+// The workspace begins with the arrival counters of the selection kernel (rows cut into shares: the last workgroup
+// of a row merges it): zero when as_create returns and zero again after every launch that used them, whatever the
+// parameters of the call were.
+constexpr size_t WS_COUNTER_BYTES = AS_SEL_COUNTERS * sizeof(int32_t);
 
 struct ws_layout {
-  size_t attn, q_hat, q_hat_layer, scores, cand, total;
+  size_t counters, attn, q_hat, q_hat_layer, scores, cand, total;
   size_t attn_end;   // what the attention calls need: the attention region and the gap behind it
   size_t gap[4];     // offsets of the gaps behind the attention partials, q_hat, the score rows, the candidates
   int64_t score_stride;
@@ -30,7 +34,8 @@ struct ws_layout {
 ws_layout layout_of(const as_params* p, int n_layers = 1, int attn_splits = 0) {
   ws_layout l;
   l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
-  l.attn = 0;
+  l.counters = 0;                                            // same place and size under every layout
+  l.attn = WS_COUNTER_BYTES + WS_GAP;
   l.gap[0] = l.attn + align_up(asx::attn_workspace_bytes(p, attn_splits));
   l.attn_end = l.gap[0] + WS_GAP;
   l.q_hat = l.attn_end;
@@ -108,17 +113,17 @@ as_status check_select_step(const as_params* p, const as_kv_view* kv, const void
 // kernels), whichever the route needs.  The predictor is a launch of its own (measured faster in every workload);
 // with predict_mode 1 and a shape whose fused selection kernel can run the predictor in its own prologue, no
 // separate predictor launch is made and q_hat is not used at all.
-as_status select_step_on(float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, int predict_mode,
+as_status select_step_on(int32_t* arrivals, float* q_hat, float* scores, int64_t score_stride, char* cand, bool stages, int predict_mode,
                          const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
                          int32_t* sel_idx, int32_t* sel_cnt, asx::wg_timeline tl, hipStream_t s) {
   const uint16_t* qw = static_cast<const uint16_t*>(q_win);
   const uint16_t* qc = static_cast<const uint16_t*>(q_cur);
   if (!stages && predict_mode == 1 && asx::select_can_predict(p))
-    return hip_status(asx::launch_select_fused(p, kv, nullptr, qw, qc, cand, sel_idx, sel_cnt, tl, s));
+    return hip_status(asx::launch_select_fused(p, kv, nullptr, qw, qc, cand, arrivals, sel_idx, sel_cnt, tl, s));
   hipError_t e = asx::launch_predict(p, qw, qc, q_hat, s);
   if (e != hipSuccess) return AS_ERR_HIP;
   if (!stages)
-    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, cand, sel_idx, sel_cnt, tl, s));
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, cand, arrivals, sel_idx, sel_cnt, tl, s));
   return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, sel_idx, sel_cnt, s));
 }
 
@@ -169,6 +174,7 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
   c->select_mode = 0;
   c->attn_splits = 0;
   c->predict_mode = 0;
+  c->merge_mode = 0;
   c->timeline = nullptr;
   c->timeline_cap = 0;
   if (workspace_bytes > 0) {
@@ -176,7 +182,8 @@ as_status as_create(as_ctx** out, int device, size_t workspace_bytes) {
       delete c;
       return AS_ERR_HIP;
     }
-    if (hipMemset(c->ws, WS_FILL, workspace_bytes) != hipSuccess) {   // the gaps between regions keep this pattern
+    if (hipMemset(c->ws, WS_FILL, workspace_bytes) != hipSuccess ||   // the gaps between regions keep this pattern
+        hipMemset(c->ws, 0, workspace_bytes < WS_COUNTER_BYTES ? workspace_bytes : WS_COUNTER_BYTES) != hipSuccess) {
       (void)hipFree(c->ws);
       delete c;
       return AS_ERR_HIP;
@@ -278,8 +285,9 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   char* ws = static_cast<char*>(ctx->ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!stages)
-    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, ws + l.cand, sel_idx, sel_cnt,
-                                               asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
+    return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, ws + l.cand,
+                                               ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+                                               sel_idx, sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
   return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
                                     sel_cnt, s));
 }
@@ -292,7 +300,8 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
-  return select_step_on(reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
+  return select_step_on(ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+                        reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
                         ws + l.cand, use_stages(ctx->select_mode, p), ctx->predict_mode, p, kv, q_win, q_cur, sel_idx,
                         sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
 }
@@ -307,13 +316,16 @@ as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const 
   const size_t q_bytes = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
   const size_t region = stages ? (size_t)p->batch * p->n_kv_heads * (size_t)score_stride * sizeof(float)
                                : asx::select_workspace_bytes(p, 1);
-  const size_t region_off = q_bytes + WS_GAP;
+  // the array starts with the arrival counters (zero at load time like the whole array, zero again after every call)
+  const size_t q_off = WS_COUNTER_BYTES + WS_GAP;
+  const size_t region_off = q_off + q_bytes + WS_GAP;
   if (region_off + region > (size_t)AS_STATIC_SCRATCH_BYTES) return AS_ERR_STATIC_SCRATCH;
   int device = 0;
   if (hipGetDevice(&device) != hipSuccess) return AS_ERR_HIP;
   char* base = static_scratch(device);    // this GPU's copy of the array (its address is resolved once per device)
   if (!base) return AS_ERR_HIP;
-  return select_step_on(reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + region_off), score_stride,
+  return select_step_on(reinterpret_cast<int32_t*>(base), reinterpret_cast<float*>(base + q_off),
+                        reinterpret_cast<float*>(base + region_off), score_stride,
                         base + region_off, stages, 0, p, kv, q_win, q_cur, sel_idx, sel_cnt,
                         asx::wg_timeline{nullptr, 0}, static_cast<hipStream_t>(stream));
 }
@@ -364,7 +376,9 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
     if (e != hipSuccess) return AS_ERR_HIP;
   }
-  return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand, fuse, s));
+  return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand,
+                                            ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + lay.counters) : nullptr,
+                                            fuse, s));
 }
 
 as_status as_kv_append(as_ctx* ctx, const as_params* p, void* k_pool, void* v_pool, const int32_t* block_table,
@@ -444,6 +458,12 @@ as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_lay
 as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode) {
   if (!ctx || mode < 0 || mode > 2) return AS_ERR_INVALID_ARG;
   ctx->select_mode = mode;
+  return AS_OK;
+}
+
+as_status as_debug_set_merge_mode(as_ctx* ctx, int32_t mode) {
+  if (!ctx || mode < 0 || mode > 1) return AS_ERR_INVALID_ARG;
+  ctx->merge_mode = mode;
   return AS_OK;
 }
 

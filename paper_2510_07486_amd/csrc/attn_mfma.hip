@@ -42,6 +42,9 @@ __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
 // whole compute units instead of packing into the free ones: batch 16, 64/8 heads, 216 -> 253 us per layer-step.)
 template <int WAVES> struct am_shape {
   static constexpr int LDS = WAVES * AM_WAVE_LDS < WAVES * 16 * AS_HEAD_DIM * 4 ? WAVES * 16 * AS_HEAD_DIM * 4 : WAVES * AM_WAVE_LDS;
+  // Block-table rows of up to this many pages are copied into LDS at the start of the kernel, in the same round trip as
+  // the first token indices: the chain index -> page id -> row address then has two dependent global loads, not three.
+  static constexpr int BT_CAP = WAVES == 8 ? 4096 : 2048;   // 16 KB / 8 KB (three four-wavefront workgroups still fit a compute unit)
 };
 
 template <int WAVES>
@@ -54,6 +57,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
   const long long t_in = timeline_begin(tl);
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[am_shape<WAVES>::LDS];
   __shared__ float m_sh[WAVES][16], l_sh[WAVES][16], l_fin[16];
+  __shared__ __attribute__((aligned(16))) int32_t bt_sh[am_shape<WAVES>::BT_CAP];
 
   // a workgroup serves up to 16 heads of a group: larger groups (MQA) take several head blocks per KV head
   const int hblocks = (G + 15) / 16;
@@ -75,6 +79,11 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
     return (ti < C) ? idx_row[ti] : 0;
   };
   const int raw_first = fetch_index(w);       // speculative: validated once the lengths are known
+  const bool bt_in_lds = max_pages <= am_shape<WAVES>::BT_CAP;   // uniform
+  if (bt_in_lds) {                            // the whole table row of the sequence (it is max_pages entries long)
+    const int32_t* src = block_table + (int64_t)b * max_pages;
+    for (int i = tid; i < max_pages; i += WAVES * 64) bt_sh[i] = src[i];
+  }
 
   const int N = clamp_ctx(ctx_lens[b], max_pages);
   int cnt = sel_cnt ? sel_cnt[b * Hkv + j] : 0;   // no selection arrays: dense attention over [0, N)
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
     int n = 0;
     if (ti < t_end) n = (ti < cnt) ? raw : tail0 + (ti - cnt);
     n = clamp_token(n, N);                                              // keeps a bad index inside the sequence
-    int32_t pg = bt_row[n >> 4];
+    int32_t pg = bt_in_lds ? bt_sh[n >> 4] : bt_row[n >> 4];
     pg = clamp_page(pg, last_page);                                     // a corrupt table must not leave the pool
     return ((uint32_t)pg << 4) | (uint32_t)(n & 15);
   };
@@ -127,6 +136,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
   for (int nt = 0; nt < 8; ++nt) o_acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f; // softmax state of head t (replicated in the 4 lane groups)
 
+  if (bt_in_lds) __syncthreads();       // the table row has landed (uniform branch; every wave of a workgroup with tokens is here)
   uint32_t my_pk = (w < nsteps) ? page_of(w, raw_first) : 0u;
 #pragma unroll 1
   for (int step = w; step < nsteps; step += WAVES) {

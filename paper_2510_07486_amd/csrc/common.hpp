@@ -14,6 +14,7 @@
 #define AS_MAX_BUDGET 65536
 #define AS_ATTN_CHUNK 128 /* tokens per attention split */
 #define AS_PACK_MAX AS_MAX_PACK /* layers one packed selection launch can cover */
+#define AS_SEL_COUNTERS 16384 /* arrival counters of the selection kernel (one per row of a launch), at the head of the scratch */
 
 struct as_ctx {
   int device;
@@ -22,6 +23,8 @@ struct as_ctx {
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
                         1: always the separate kernels via HBM scores, 2: always fused */
   int attn_splits;   /* > 0: forced number of attention splits per (sequence, KV head) */
+  int merge_mode;    /* 0: rows cut into shares are merged inside the selection kernel where its LDS holds the row's
+                        candidates, 1: always by a second launch */
   int predict_mode;  /* 0: the predictor is a launch of its own, 1: it runs in the prologue of the fused selection
                         kernel where that kernel can */
   long long* timeline;   /* development: device buffer that receives wall_clock64 at entry and exit of every */
@@ -113,12 +116,13 @@ size_t select_workspace_bytes(const as_params* p, int n_layers);
 // groups of up to 16 heads, max / sum aggregation)
 bool select_can_predict(const as_params* p);
 // fuse_predict: tab carries q_win / q_cur instead of q_hat (only where select_can_predict)
-hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, bool fuse_predict,
-                              hipStream_t s);
+// arrivals: AS_SEL_COUNTERS counters that are zero before the launch (and zero again after it), or nullptr
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab, void* ws, int32_t* arrivals,
+                              bool fuse_predict, hipStream_t s);
 // q_win != nullptr: the predictor runs in the kernel's prologue and q_hat is not read
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, const uint16_t* q_win,
-                               const uint16_t* q_cur, void* ws, int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl,
-                               hipStream_t s);
+                               const uint16_t* q_cur, void* ws, int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt,
+                               wg_timeline tl, hipStream_t s);
 // partial buffers live in the ctx workspace
 // forced_splits > 0 overrides the split rule (development knob of a ctx)
 size_t attn_workspace_bytes(const as_params* p, int forced_splits);

@@ -154,6 +154,118 @@ size_t select_workspace_bytes(const as_params* p, int n_layers) {
   return cand_bytes(p, pl, n_layers) + lse_bytes(p, pl, n_layers);
 }
 
+// ---- rows cut into several shares, merged inside the slice kernel ---------------------------------
+// The last workgroup of a row to finish merges the row's per-share candidates itself (merge_row_lds below)
+// instead of a second launch doing it.  No fence with a cache write-back is involved and nobody waits for
+// anybody: candidates are stored with device-scope stores (written through to memory), every wavefront waits
+// for its own stores to complete, the workgroup meets at a barrier and then counts itself in with one
+// device-scope atomic add on the row's arrival counter; the workgroup that completes the count reads the
+// candidates back with device-scope loads (buffer loads carrying the device-scope bit, several in flight),
+// every other workgroup simply ends.  The counter is reset by the workgroup that completes it, so counters
+// are zero between launches.
+__device__ __forceinline__ void st_dev(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(int32_t* p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_dev(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, byte_off, 0, 16 /* device scope */);
+}
+
+// Top-C of one row from its shares' candidates (token order within and across shares), at most 8 * THREADS of
+// them in all: the candidates are compacted into LDS, marked in registers (mark_best) and compacted in order.
+//   row_key / row_idx: [nslices][ccap] candidates of the row; row_cnt: [nslices]
+//   lkey / lidx: 8 * THREADS words of LDS each; cnt_sh / pre_sh: nslices words each; hist: 2^B0 words
+template <int THREADS, int B0>
+__device__ __forceinline__ void merge_row_lds(const uint32_t* row_key, const int32_t* row_idx, const int32_t* row_cnt,
+                                              int nslices, int ccap, int C, int32_t* __restrict__ out_idx,
+                                              int32_t* __restrict__ out_cnt, uint32_t* lkey, int32_t* lidx,
+                                              int32_t* cnt_sh, int32_t* pre_sh, uint32_t* hist, uint32_t* xch) {
+  constexpr int NPT = 8, WAVES = THREADS / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row_key), 0, 0x7fffffff, 0x00020000);
+  const __amdgpu_buffer_rsrc_t ri = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(row_idx), 0, 0x7fffffff, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(row_cnt), 0, 0x7fffffff, 0x00020000);
+  // counts and their exclusive prefix over shares: thread s owns share s, THREADS shares per round
+  uint32_t run = 0;
+  for (int s0 = 0; s0 < nslices; s0 += THREADS) {
+    const int sl = s0 + tid;
+    const uint32_t mine = sl < nslices ? ld_dev(rc, (uint32_t)sl * 4u) : 0u;
+    const uint32_t inc = wave_incl_scan(mine);
+    __syncthreads();
+    if (lane == 63) xch[wave] = inc;
+    __syncthreads();
+    uint32_t woff[1];
+    const uint32_t tot = seg_wave_offsets<WAVES, 1>(xch, wave, woff);
+    if (sl < nslices) {
+      cnt_sh[sl] = (int32_t)mine;
+      pre_sh[sl] = (int32_t)(run + woff[0] + inc - mine);
+    }
+    run += tot;
+  }
+  __syncthreads();
+  const int total = (int)run;                 // <= nslices * ccap <= NPT * THREADS (host check)
+  const int keep = total < C ? total : C;
+  const int nvirt = nslices * ccap;
+  if (keep > 0) {
+#pragma unroll 1
+    for (int base = 0; base < nvirt; base += NPT * THREADS) {
+      uint32_t k[NPT];
+      int32_t ix[NPT];
+      int pos[NPT];
+#pragma unroll
+      for (int u = 0; u < NPT; ++u) {   // every load issued before the first is used; empty slots re-read candidate 0
+        const int v = base + u * THREADS + tid;
+        const int sl = v < nvirt ? v / ccap : 0;
+        const int i = v - sl * ccap;
+        const bool ok = v < nvirt && i < cnt_sh[sl];
+        pos[u] = ok ? pre_sh[sl] + i : -1;
+        k[u] = ld_dev(rk, (uint32_t)(ok ? v : 0) * 4u);
+        ix[u] = (int32_t)ld_dev(ri, (uint32_t)(ok ? v : 0) * 4u);
+      }
+#pragma unroll
+      for (int u = 0; u < NPT; ++u)
+        if (pos[u] >= 0) {
+          lkey[pos[u]] = k[u];
+          lidx[pos[u]] = ix[u];
+        }
+    }
+    __syncthreads();
+    uint32_t key[NPT];
+    int32_t tok[NPT];
+    bool have[NPT], sel[NPT];
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) {
+      const int i = tid * NPT + e;              // < NPT * THREADS
+      have[e] = i < total;
+      const uint32_t k = lkey[i];
+      const int32_t tk = lidx[i];
+      key[e] = have[e] ? k : 0u;
+      tok[e] = have[e] ? tk : 0;
+      sel[e] = have[e];
+    }
+    if (keep < total) mark_best<THREADS, B0, NPT>(key, tok, have, keep, hist, xch, sel);
+    uint32_t c = 0;
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) c += sel[e] ? 1u : 0u;
+    const uint32_t sinc = wave_incl_scan(c);
+    __syncthreads();                 // every thread has its candidates in registers: lidx becomes the output stage
+    if (lane == 63) xch[wave] = sinc;
+    __syncthreads();
+    uint32_t soff[1];
+    seg_wave_offsets<WAVES, 1>(xch, wave, soff);
+    uint32_t at = soff[0] + sinc - c;
+#pragma unroll
+    for (int e = 0; e < NPT; ++e)
+      if (sel[e]) lidx[at++] = tok[e];
+    __syncthreads();
+    for (int i = tid; i < keep; i += THREADS) out_idx[i] = lidx[i];
+  }
+  for (int i = keep + tid; i < C; i += THREADS) out_idx[i] = -1;
+  if (tid == 0) *out_cnt = keep;
+}
+
 // MODE 0: scores are the max (or the pre-summed query's logit) over the group.  MODES 1 and 2 are the two passes
 // of the softmax-normalised aggregation s[n] = sum_g exp(scale * l[g][n] - LSE_g): pass 1 streams the share and
 // leaves one (max, sum) pair per head in lse_part, pass 2 merges the pairs of all shares of its row into LSE_g
@@ -165,7 +277,7 @@ template <int NSET, int FS_THREADS, int PG, int MODE, bool PRED>
 __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     const sel_tab tab, int B, int Hq, int Hkv, int G, int agg, int max_pages, int share_len, int nshares, int C,
     int ccap, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_idx, int32_t* __restrict__ cand_cnt,
-    float sm_scale, float2* __restrict__ lse_part) {
+    float sm_scale, float2* __restrict__ lse_part, int32_t* __restrict__ arrivals) {
   using shape = fs_shape<FS_THREADS>;
   constexpr int FS_WAVES = shape::WAVES, CAP = shape::CAP, NPT = CAP / FS_THREADS;
   constexpr int FS_B0 = shape::B0, FS_BINS = shape::BINS, BM_WORDS = shape::SHARE_CAP / 32;
@@ -178,6 +290,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   __shared__ uint32_t bitmap[BM_WORDS];   // one bit per token of the share: orders the selected tokens
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
   __shared__ uint32_t c_cnt;              // candidates in the buffer
+  __shared__ int last_sh;                 // this workgroup completed its row's arrival count
 
   // Grid = (KV head, layer * B + batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
   // and, inside an XCD, over its shader arrays: any index whose upper values are empty for short
@@ -211,7 +324,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       if (rank == slot) xch[0] = (uint32_t)u;
     }
     __syncthreads();
-    b = (int)xch[0];
+    b = __builtin_amdgcn_readfirstlane((int)xch[0]);   // uniform: keeps the row's addresses in scalar registers
   }
   __syncthreads();
   const int64_t row = (int64_t)b * Hkv + j;                      // row of this layer's outputs
@@ -221,6 +334,26 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   int n_share = N - tok0;
   n_share = n_share < 0 ? 0 : (n_share > share_len ? share_len : n_share);
   const bool final_out = (nshares == 1);
+  // rows with several shares and an arrival counter: called by every workgroup of the row once its candidates (and
+  // their count) are stored; the one that completes the count merges the row
+  auto arrive_and_merge = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's device-scope stores have completed
+    __syncthreads();
+    if (tid == 0) {
+      int32_t* ctr = arrivals + crow;
+      const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int last = old == nshares - 1;
+      if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      last_sh = last;
+    }
+    __syncthreads();
+    if (!last_sh) return;
+    static_assert(BM_WORDS >= 512, "share counts and their prefixes live in the bitmap words");
+    merge_row_lds<FS_THREADS, FS_B0>(cand_key + crow * nshares * (int64_t)ccap, cand_idx + crow * nshares * (int64_t)ccap,
+                                     cand_cnt + crow * nshares, nshares, ccap, C, sel_idx + row * C, sel_cnt + row,
+                                     c_key, c_tok, reinterpret_cast<int32_t*>(bitmap),
+                                     reinterpret_cast<int32_t*>(bitmap) + BM_WORDS / 2, hist, xch);
+  };
   if (MODE == 1 && n_share == 0) {
     if (tid < G) lse_part[(crow * nshares + sh) * G + tid] = make_float2(-INFINITY, 0.f);
     timeline_end(tab.timeline, t_in);
@@ -230,6 +363,9 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
     if (final_out) {
       for (int i = tid; i < C; i += FS_THREADS) sel_idx[row * C + i] = -1;
       if (tid == 0) sel_cnt[row] = 0;
+    } else if (arrivals) {
+      if (tid == 0) st_dev(&cand_cnt[crow * nshares + sh], 0);
+      arrive_and_merge();
     } else if (tid == 0) {
       cand_cnt[crow * nshares + sh] = 0;
     }
@@ -570,13 +706,22 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       if (tid == 0) sel_cnt[row] = keep;
     } else {
       const int64_t cbase = (crow * nshares + sh) * (int64_t)ccap;
-      for (int i = tid; i < keep; i += FS_THREADS) {
-        cand_key[cbase + i] = o_key[i];
-        cand_idx[cbase + i] = o_tok[i];
+      if (arrivals) {
+        for (int i = tid; i < keep; i += FS_THREADS) {
+          st_dev(&cand_key[cbase + i], o_key[i]);
+          st_dev(&cand_idx[cbase + i], o_tok[i]);
+        }
+        if (tid == 0) st_dev(&cand_cnt[crow * nshares + sh], keep);
+      } else {
+        for (int i = tid; i < keep; i += FS_THREADS) {
+          cand_key[cbase + i] = o_key[i];
+          cand_idx[cbase + i] = o_tok[i];
+        }
+        if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
       }
-      if (tid == 0) cand_cnt[crow * nshares + sh] = keep;
     }
   }
+  if (!final_out && arrivals) arrive_and_merge();
   timeline_end(tab.timeline, t_in);
 }
 
@@ -699,8 +844,8 @@ bool select_can_predict(const as_params* p) {
   return p->window <= 16 && p->agg != AS_AGG_SOFTMAX_SUM && (p->agg == AS_AGG_SUM || G <= 16);
 }
 
-hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab_in, void* ws, bool fuse_predict,
-                              hipStream_t s) {
+hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab_in, void* ws, int32_t* arrivals,
+                              bool fuse_predict, hipStream_t s) {
   const int64_t rows = (int64_t)p->batch * p->n_kv_heads * n_layers;
   if (rows == 0) return hipSuccess;
   if ((int64_t)p->batch * n_layers > 65535) return hipErrorInvalidValue;   // grid.y
@@ -722,11 +867,19 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   }
   dim3 grid(p->n_kv_heads, p->batch * n_layers, pl.nslices);
   const int nset = (p->agg == AS_AGG_SUM || G <= 8) ? 1 : G <= 16 ? 2 : G <= 32 ? 4 : 8;
+  // Rows cut into several shares are merged by the last workgroup of the row inside the slice kernel when there
+  // is an arrival counter per row and the row's candidates fit the kernel's LDS candidate buffer; else by a
+  // second launch.
+  const int thr = nset > 2 ? 512 : 1024;
+  const bool merge_in_kernel = arrivals != nullptr && pl.nslices > 1 && rows <= AS_SEL_COUNTERS &&
+                               (int64_t)pl.nslices * pl.ccap <= 8 * thr && pl.nslices <= thr / 4 &&
+                               (int64_t)rows * pl.nslices * pl.ccap * 8 < 0x7fffffffLL;
+  int32_t* arr = merge_in_kernel ? arrivals : nullptr;
   float2* lse_part = reinterpret_cast<float2*>(static_cast<char*>(ws) + cand_bytes(p, pl, n_layers));
 #define AS_SLICE_LAUNCH(NSET_, THR_, MODE_, PRED_)                                                                \
   hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, (NSET_ == 4 ? FS_PG4 : FS_PG), MODE_, PRED_>), grid, dim3(THR_), 0, s, tab, \
                      p->batch, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len,        \
-                     pl.nslices, p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part)
+                     pl.nslices, p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part, arr)
   // groups of up to 16 heads (one or two operand sets) run 1024-thread workgroups, larger ones the 512-thread shape
   if (p->agg == AS_AGG_SOFTMAX_SUM) {
     // two passes over K with the same grid: per-share (max, sum) pairs, then selection on the normalised scores
@@ -740,7 +893,7 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   else { if (fuse_predict) AS_SLICE_LAUNCH(1, 1024, 0, true); else AS_SLICE_LAUNCH(1, 1024, 0, false); }
 #undef AS_SLICE_LAUNCH
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || pl.nslices == 1) return e;
+  if (e != hipSuccess || pl.nslices == 1 || merge_in_kernel) return e;
   const int64_t most = (int64_t)pl.nslices * pl.ccap;   // candidates a row can have
 #define AS_MERGE_LAUNCH(NPT_)                                                                                   \
   hipLaunchKernelGGL(select_merge_kernel<NPT_>, dim3((unsigned)rows), dim3(TK_THREADS), 0, s, tab,              \
@@ -753,8 +906,8 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
 }
 
 hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const float* q_hat, const uint16_t* q_win,
-                               const uint16_t* q_cur, void* ws, int32_t* sel_idx, int32_t* sel_cnt, wg_timeline tl,
-                               hipStream_t s) {
+                               const uint16_t* q_cur, void* ws, int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt,
+                               wg_timeline tl, hipStream_t s) {
   sel_tab tab = {};
   tab.timeline = tl;
   tab.q_win[0] = q_win;
@@ -766,7 +919,7 @@ hipError_t launch_select_fused(const as_params* p, const as_kv_view* kv, const f
   tab.sel_idx[0] = sel_idx;
   tab.sel_cnt[0] = sel_cnt;
   tab.last_page[0] = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
-  return launch_select_pack(p, 1, tab, ws, q_win != nullptr, s);
+  return launch_select_pack(p, 1, tab, ws, arrivals, q_win != nullptr, s);
 }
 
 }  // namespace asx
