@@ -211,9 +211,10 @@ AS_API as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_vie
  *     AS_ERR_STATIC_SCRATCH before anything is launched
  *   - the array's device address is looked up once per device, on the first call there or in any earlier
  *     as_create on that device: make one of the two happen before a stream capture begins
- *   - all calls on one GPU share the one array (nothing in it needs clearing between calls: every word a kernel
- *     reads was written earlier in the same call): calls that overlap in time on one GPU, on whatever streams,
- *     race and give unspecified results
+ *   - all calls on one GPU share the one array.  Nothing in it needs clearing between calls: apart from the
+ *     arrival counters at its head, every word a kernel reads was written earlier in the same call, and the
+ *     counters (zero when the library is loaded) are put back to zero by the kernel that used them.  Calls that
+ *     overlap in time on one GPU, on whatever streams, race and give unspecified results
  */
 #define AS_STATIC_SCRATCH_BYTES (48u << 20)
 AS_API as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,

@@ -253,8 +253,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 1) void attn_mfma_kern
   for (int i = 0; i < 4; ++i) {
     const float f = __shfl(wgt, 4 * grp + i);
     const int head = 4 * grp + i;
+    if (head < Gb) {                     // rows of the zero-padded heads are never read
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) red[(w * 16 + head) * AS_HEAD_DIM + nt * 16 + t] = o_acc[nt][i] * f;
+      for (int nt = 0; nt < 8; ++nt) red[(w * 16 + head) * AS_HEAD_DIM + nt * 16 + t] = o_acc[nt][i] * f;
+    }
   }
   if (w == 0 && grp == 0) l_fin[t] = Ls;   // the merged normaliser of head t
   __syncthreads();
