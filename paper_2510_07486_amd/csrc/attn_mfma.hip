@@ -36,6 +36,11 @@ __device__ __forceinline__ uint4 am_ld16_nt(const void* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+// Measured and not kept: a second register set per wavefront, so that the rows of the next step are requested before
+// the current one is computed (252 registers, two steps = 32 KB in flight per wavefront).  Batch 32, 32/8 heads,
+// budget 2048: 51.2 us against 49.1 us.  While all workgroups run the kernel already moves 6.3 TB/s (the rate of
+// full attention over long contexts); what is left is the spread between the fastest and the slowest compute unit
+// at the end (38.7 / 42.6 / 48.0 us for the first, median and last workgroup), which more loads in flight do not shorten.
 // WAVES = 4: 37 KB of LDS, three workgroups fit a compute unit; WAVES = 8: 73 KB, two fit.  (Padding the LDS
 // request so that a compute unit cannot take more than its even share of a grid was measured: nothing gained
 // alone, and beside the selection kernel, whose workgroups own a compute unit each, attention then waits for

@@ -17,9 +17,10 @@ __device__ __forceinline__ int cmap(int grp, int m) { return grp * 4 + m; }
 
 // Builds the A operand (rows = hi/lo parts of the group's queries) for this lane.
 //   row r = lane & 15:  head slot 2*(r>>2) + (r&1), part (r>>1)&1  (0 = hi, 1 = lo)
+//   operand set s (of NSET, counted from s_base) holds head slots (s_base + s) * 8 .. + 7, wrapped modulo G
 template <int NSET>
 __device__ __forceinline__ void build_q_operand(const float* __restrict__ q_hat, int b, int j, int Hq, int G,
-                                                int agg, int lane, bf16x8 (&aq)[NSET][4]) {
+                                                int agg, int lane, bf16x8 (&aq)[NSET][4], int s_base = 0) {
   const int r = lane & 15, grp = lane >> 4;
   const int slot = 2 * (r >> 2) + (r & 1);
   const int part = (r >> 1) & 1;
@@ -40,7 +41,7 @@ __device__ __forceinline__ void build_q_operand(const float* __restrict__ q_hat,
           for (int e = 0; e < 8; ++e) v[m][e] += qb[g * AS_HEAD_DIM + cmap(grp, m) * 8 + e];
       }
     } else {
-      const int g = (s * 8 + slot) % G;
+      const int g = ((s_base + s) * 8 + slot) % G;
 #pragma unroll
       for (int m = 0; m < 4; ++m)
 #pragma unroll

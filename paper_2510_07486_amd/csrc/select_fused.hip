@@ -290,6 +290,13 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   __shared__ uint32_t bitmap[BM_WORDS];   // one bit per token of the share: orders the selected tokens
   __shared__ __attribute__((aligned(16))) uint32_t xch[TK_XCH];
   __shared__ uint32_t c_cnt;              // candidates in the buffer
+  // Groups of 33-64 heads (eight operand sets), plain selection: the sets stay in LDS and a wavefront holds one half
+  // (four sets, 64 registers) at a time; the pages of an iteration are kept in registers and scored against one
+  // half, the other half is loaded, the same pages are scored again, and the next iteration starts with the half
+  // that is already loaded: one half-load (16 KB per wavefront) per PG pages, and room for PG = 4 pages in flight.
+  constexpr bool HALF = NSET == 8 && MODE == 0;
+  constexpr int NREG = HALF ? 4 : NSET;   // operand sets held in registers
+  __shared__ uint4 aq_lds[HALF ? 8 * 4 * 64 : 1];
   __shared__ int last_sh;                 // this workgroup completed its row's arrival count
 
   // Grid = (KV head, layer * B + batch slot, share).  Consecutive workgroup ids go round-robin over the 8 XCDs
@@ -406,8 +413,19 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   int pos = 0;
   int32_t my_page = load_pages(0);
 
-  bf16x8 aq[NSET][4];
-  if constexpr (PRED) {
+  bf16x8 aq[NREG][4];
+  if constexpr (HALF) {
+    static_assert(FS_WAVES == 8, "wavefront w builds operand set w");
+    bf16x8 one[1][4];
+    build_q_operand<1>(q_hat, b, j, Hq, G, agg, lane, one, wave);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) aq_lds[(wave * 4 + m) * 64 + lane] = __builtin_bit_cast(uint4, one[0][m]);
+    __syncthreads();
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+      for (int m = 0; m < 4; ++m) aq[s2][m] = __builtin_bit_cast(bf16x8, aq_lds[(s2 * 4 + m) * 64 + lane]);
+  } else if constexpr (PRED) {
     static_assert(MODE == 0 && NSET <= 2 && FS_THREADS == 1024, "hist holds q_hat of up to 16 heads; eight scratch areas");
     static_assert(sizeof(predict_lds<16>) <= 16384, "four areas in the page images, two each in the candidate arrays");
     float* qh_sh = reinterpret_cast<float*>(hist);   // [G][128]; hist is next written by a prune, behind a barrier
@@ -427,11 +445,12 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
       }
     }
     __syncthreads();
-    build_q_operand<NSET>(qh_sh, 0, 0, 0, G, agg, lane, aq);   // the group's rows start at qh_sh
+    build_q_operand<NREG>(qh_sh, 0, 0, 0, G, agg, lane, aq);   // the group's rows start at qh_sh
     __syncthreads();   // the scratch areas become page images and candidates again
   } else {
-    build_q_operand<NSET>(q_hat, b, j, Hq, G, agg, lane, aq);
+    build_q_operand<NREG>(q_hat, b, j, Hq, G, agg, lane, aq);
   }
+  int cur_half = 0;   // HALF: which half of the operand sets aq holds
 
   // softmax modes: the lane's accumulators of operand set s belong to heads s*8 + 2*grp and s*8 + 2*grp + 1
   float hm[NSET][2], hl[NSET][2];   // pass 1: running (max, sum of exp) of this lane's token column; pass 2: hm = LSE
@@ -491,6 +510,48 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
         for (int i = 0; i < 4; ++i) kb[pg][i] = ld16<true>(base + i * 64 + lane);
       }
       float res[PG];
+      if constexpr (HALF) {
+        uint4 kkh[PG][4];
+        float vpart[PG];
+#pragma unroll
+        for (int pg = 0; pg < PG; ++pg) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st[lds_slot(4 * i + grp, t)] = kb[pg][i];
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int m = 0; m < 4; ++m) kkh[pg][m] = st[lds_slot(t, cmap(grp, m))];
+          __builtin_amdgcn_wave_barrier();
+          float v = -INFINITY;
+#pragma unroll
+          for (int s2 = 0; s2 < 4; ++s2) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[s2][m], __builtin_bit_cast(bf16x8, kkh[pg][m]), acc, 0, 0, 0);
+            v = fmaxf(v, fold_rows(acc));
+          }
+          vpart[pg] = v;
+        }
+        cur_half ^= 1;
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+          for (int m = 0; m < 4; ++m)
+            aq[s2][m] = __builtin_bit_cast(bf16x8, aq_lds[((cur_half * 4 + s2) * 4 + m) * 64 + lane]);
+#pragma unroll
+        for (int pg = 0; pg < PG; ++pg) {
+          float v = vpart[pg];
+#pragma unroll
+          for (int s2 = 0; s2 < 4; ++s2) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[s2][m], __builtin_bit_cast(bf16x8, kkh[pg][m]), acc, 0, 0, 0);
+            v = fmaxf(v, fold_rows(acc));
+          }
+          res[pg] = group_max(v);
+        }
+      } else {
 #pragma unroll
       for (int pg = 0; pg < PG; ++pg) {
 #pragma unroll
@@ -537,6 +598,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
           res[pg] = 0.f;
         }
       }
+      }   // !HALF
       if (MODE == 1) continue;   // pass 1 keeps no candidates
       float outv = res[0];
 #pragma unroll
@@ -877,7 +939,7 @@ hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& t
   int32_t* arr = merge_in_kernel ? arrivals : nullptr;
   float2* lse_part = reinterpret_cast<float2*>(static_cast<char*>(ws) + cand_bytes(p, pl, n_layers));
 #define AS_SLICE_LAUNCH(NSET_, THR_, MODE_, PRED_)                                                                \
-  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, (NSET_ == 4 ? FS_PG4 : FS_PG), MODE_, PRED_>), grid, dim3(THR_), 0, s, tab, \
+  hipLaunchKernelGGL((select_slice_kernel<NSET_, THR_, (NSET_ == 4 || (NSET_ == 8 && MODE_ == 0) ? FS_PG4 : FS_PG), MODE_, PRED_>), grid, dim3(THR_), 0, s, tab, \
                      p->batch, p->n_q_heads, p->n_kv_heads, G, p->agg, p->max_pages_per_seq, pl.slice_len,        \
                      pl.nslices, p->budget, pl.ccap, cand_key, cand_idx, cand_cnt, p->sm_scale, lse_part, arr)
   // groups of up to 16 heads (one or two operand sets) run 1024-thread workgroups, larger ones the 512-thread shape
