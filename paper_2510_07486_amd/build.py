@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasyncspade.so")
 OBJ = os.path.join(HERE, "_build")
 DEMO = os.path.join(HERE, "abi_demo")
-SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip",
+SOURCES = ["api.hip", "predict.hip", "score.hip", "topk.hip", "select_rows.hip", "select_fused.hip", "attn.hip", "attn_mfma.hip",
            "cache_ops.hip"]
 
 

@@ -90,8 +90,12 @@ bool use_stages(int select_mode, const as_params* p) {
   return select_mode == 1 || asx::select_prefers_stages(p);
 }
 
+// arrivals != nullptr and a shape the one-launch form serves: scoring and the per-row top-k share a grid
+// (select_rows.hip); otherwise the two stand-alone kernels, one after the other.  Same scores, same selection.
 hipError_t score_then_topk(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
-                           int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+                           int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
+  if (arrivals && asx::select_rows_ok(p))
+    return asx::launch_select_rows(p, kv, q_hat, scores, stride, arrivals, sel_idx, sel_cnt, s);
   const hipError_t e = asx::launch_score(p, kv, q_hat, scores, stride, s);
   if (e != hipSuccess) return e;
   return asx::launch_topk(p, scores, stride, kv->ctx_lens, sel_idx, sel_cnt, s);
@@ -124,7 +128,7 @@ as_status select_step_on(int32_t* arrivals, float* q_hat, float* scores, int64_t
   if (e != hipSuccess) return AS_ERR_HIP;
   if (!stages)
     return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, cand, arrivals, sel_idx, sel_cnt, tl, s));
-  return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, sel_idx, sel_cnt, s));
+  return hip_status(score_then_topk(p, kv, q_hat, scores, score_stride, arrivals, sel_idx, sel_cnt, s));
 }
 
 // The device address of `scratch` that kernels, copies and fills may use: resolved once per device, with that
@@ -288,8 +292,10 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
     return hip_status(asx::launch_select_fused(p, kv, q_hat, nullptr, nullptr, ws + l.cand,
                                                ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
                                                sel_idx, sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
-  return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride, sel_idx,
-                                    sel_cnt, s));
+  return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
+                                    ctx->merge_mode == 0 && ctx->select_mode != 1
+                                        ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+                                    sel_idx, sel_cnt, s));
 }
 
 as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const void* q_win, const void* q_cur,
@@ -300,9 +306,11 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
-  return select_step_on(ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+  const bool stages = use_stages(ctx->select_mode, p);
+  const bool one_launch = ctx->merge_mode == 0 && !(stages && ctx->select_mode == 1);
+  return select_step_on(one_launch ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
                         reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
-                        ws + l.cand, use_stages(ctx->select_mode, p), ctx->predict_mode, p, kv, q_win, q_cur, sel_idx,
+                        ws + l.cand, stages, ctx->predict_mode, p, kv, q_win, q_cur, sel_idx,
                         sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
 }
 

@@ -29,6 +29,7 @@
 #include "predict_common.hpp"
 #include "score_common.hpp"
 #include "topk_common.hpp"
+#include "devscope.hpp"
 
 namespace asx {
 
@@ -156,23 +157,7 @@ size_t select_workspace_bytes(const as_params* p, int n_layers) {
 
 // ---- rows cut into several shares, merged inside the slice kernel ---------------------------------
 // The last workgroup of a row to finish merges the row's per-share candidates itself (merge_row_lds below)
-// instead of a second launch doing it.  No fence with a cache write-back is involved and nobody waits for
-// anybody: candidates are stored with device-scope stores (written through to memory), every wavefront waits
-// for its own stores to complete, the workgroup meets at a barrier and then counts itself in with one
-// device-scope atomic add on the row's arrival counter; the workgroup that completes the count reads the
-// candidates back with device-scope loads (buffer loads carrying the device-scope bit, several in flight),
-// every other workgroup simply ends.  The counter is reset by the workgroup that completes it, so counters
-// are zero between launches.
-__device__ __forceinline__ void st_dev(uint32_t* p, uint32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev(int32_t* p, int32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t ld_dev(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
-  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, byte_off, 0, 16 /* device scope */);
-}
-
+// instead of a second launch doing it; the hand-over between workgroups is the one of devscope.hpp.
 // Top-C of one row from its shares' candidates (token order within and across shares), at most 8 * THREADS of
 // them in all: the candidates are compacted into LDS, marked in registers (mark_best) and compacted in order.
 //   row_key / row_idx: [nslices][ccap] candidates of the row; row_cnt: [nslices]
@@ -344,17 +329,7 @@ __global__ __launch_bounds__(FS_THREADS) void select_slice_kernel(
   // rows with several shares and an arrival counter: called by every workgroup of the row once its candidates (and
   // their count) are stored; the one that completes the count merges the row
   auto arrive_and_merge = [&]() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's device-scope stores have completed
-    __syncthreads();
-    if (tid == 0) {
-      int32_t* ctr = arrivals + crow;
-      const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int last = old == nshares - 1;
-      if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      last_sh = last;
-    }
-    __syncthreads();
-    if (!last_sh) return;
+    if (!arrive_last(arrivals + crow, nshares, &last_sh)) return;
     static_assert(BM_WORDS >= 512, "share counts and their prefixes live in the bitmap words");
     merge_row_lds<FS_THREADS, FS_B0>(cand_key + crow * nshares * (int64_t)ccap, cand_idx + crow * nshares * (int64_t)ccap,
                                      cand_cnt + crow * nshares, nshares, ccap, C, sel_idx + row * C, sel_cnt + row,

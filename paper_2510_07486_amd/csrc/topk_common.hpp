@@ -50,8 +50,9 @@ __device__ __forceinline__ uint32_t seg_wave_offsets(const uint32_t* words, int 
 // Finds the bin d (scanning from the highest bin down) with
 //   sum_{d' > d} hist[d'] < remaining <= sum_{d' >= d} hist[d'];
 // writes d and the count above it to found[0..1].  nb <= 4 * THREADS bins.
-// wave_tot: 16 words of LDS.
-template <int THREADS>
+// wave_tot: 16 words of LDS.  SPREAD = 4: a bin is the sum of four consecutive words (16-byte aligned), see
+// radix_threshold.
+template <int THREADS, int SPREAD = 1>
 __device__ __forceinline__ void find_bin(const uint32_t* hist, int nb, uint32_t remaining, uint32_t* wave_tot,
                                          uint32_t* found) {
   constexpr int WAVES = THREADS / 64;
@@ -62,7 +63,14 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, int nb, uint32_t 
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int rb = tid * per + i;  // reversed bin index
-    if (i < per && rb < nb) loc[i] = hist[nb - 1 - rb];
+    if (i < per && rb < nb) {
+      if (SPREAD == 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(hist + 4 * (nb - 1 - rb));
+        loc[i] = v.x + v.y + v.z + v.w;
+      } else {
+        loc[i] = hist[nb - 1 - rb];
+      }
+    }
     mine += loc[i];
   }
   const uint32_t inc = wave_incl_scan(mine);
@@ -206,7 +214,10 @@ __device__ __forceinline__ auto key4_from_scalar(int n, KeyFn key_of) {
 // Value of the want-th largest of the (up to NPT per thread) values held in registers, over the
 // whole workgroup: three histogram passes (B0 bits, then the rest in two halves).  Returns T;
 // `r` = how many values equal to T are still wanted, `ties` = how many values equal T.
-template <int THREADS, int B0, int NPT>
+// SPREAD = 4 (hist then has 4 << B0 words, 16-byte aligned): in the first pass, where every value is counted and
+// scores crowd into a few dozen bins (sign, exponent, three mantissa bits), a bin is four words in four LDS banks and
+// a lane adds to word lane % 4, so a wavefront's adds to one bin serialise a quarter as long.
+template <int THREADS, int B0, int NPT, int SPREAD = 1>
 __device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], const bool (&ok)[NPT], uint32_t want,
                                                     uint32_t* hist, uint32_t* xch, uint32_t& r, uint32_t& ties) {
   constexpr int B1 = (32 - B0 + 1) / 2, B2 = 32 - B0 - B1;
@@ -219,6 +230,15 @@ __device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], 
     const int width = pass == 0 ? B0 : pass == 1 ? B1 : B2;
     const int sh = pass == 0 ? 32 - B0 : pass == 1 ? B2 : 0;
     const int nb = 1 << width;
+    if (SPREAD == 4 && pass == 0) {
+      for (int i = tid; i < 4 * nb; i += THREADS) hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < NPT; ++e)
+        if (ok[e]) atomicAdd(&hist[4 * (val[e] >> sh) + (tid & 3)], 1u);
+      __syncthreads();
+      find_bin<THREADS, SPREAD>(hist, nb, remaining, wave_tot, found);
+    } else {
     for (int i = tid; i < nb; i += THREADS) hist[i] = 0;
     __syncthreads();
 #pragma unroll
@@ -226,6 +246,7 @@ __device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], 
       if (ok[e] && (val[e] & mask) == prefix) atomicAdd(&hist[(val[e] >> sh) & (nb - 1)], 1u);
     __syncthreads();
     find_bin<THREADS>(hist, nb, remaining, wave_tot, found);
+    }
     prefix |= found[0] << sh;
     mask |= (uint32_t)(nb - 1) << sh;
     remaining -= found[1];
@@ -239,12 +260,12 @@ __device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&val)[NPT], 
 // Marks, among this thread's NPT candidates, the ones that belong to the best `keep` of the `total`
 // candidates of the workgroup (keep < total).  Returns the key threshold T; tie_inv (optional) receives the
 // cut among the pairs with key == T: such a pair is kept iff ~token >= *tie_inv (0 when every one of them is).
-template <int THREADS, int B0, int NPT>
+template <int THREADS, int B0, int NPT, int SPREAD = 1>
 __device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const int32_t (&tok)[NPT],
                                               const bool (&have)[NPT], int keep, uint32_t* hist, uint32_t* xch,
                                               bool (&sel)[NPT], uint32_t* tie_inv = nullptr) {
   uint32_t r, ties;
-  const uint32_t T = radix_threshold<THREADS, B0, NPT>(key, have, (uint32_t)keep, hist, xch, r, ties);
+  const uint32_t T = radix_threshold<THREADS, B0, NPT, SPREAD>(key, have, (uint32_t)keep, hist, xch, r, ties);
   uint32_t I = 0;   // threshold on ~token among the pairs with key == T
   if (r < ties) {   // uniform: not every tie fits, the lowest tokens win
     uint32_t inv[NPT];
@@ -255,13 +276,87 @@ __device__ __forceinline__ uint32_t mark_best(const uint32_t (&key)[NPT], const 
       tie[e] = have[e] && key[e] == T;
     }
     uint32_t r2, t2;
-    I = radix_threshold<THREADS, B0, NPT>(inv, tie, r, hist, xch, r2, t2);
+    I = radix_threshold<THREADS, B0, NPT, SPREAD>(inv, tie, r, hist, xch, r2, t2);
   }
 #pragma unroll
   for (int e = 0; e < NPT; ++e)
     sel[e] = have[e] && (key[e] > T || (key[e] == T && ~(uint32_t)tok[e] >= I));
   if (tie_inv) *tie_inv = I;
   return T;
+}
+
+// Top-C of one row of at most NPT * TK_THREADS scores, by a whole workgroup of TK_THREADS threads.  The row's keys
+// are read once, coalesced, into registers (token i sits in thread i % 1024: load(i) returns its score); the best
+// min(C, N) are marked there (mark_best: radix thresholds on the key, ties by token) and put into ascending token
+// order through a bitmap of the row (rank of a token = set bits below it).  A wavefront's 64 tokens of one
+// register slot are two whole bitmap words, so the bitmap is written from ballots, without atomics.
+//   out: C token indices (-1 beyond the count); cnt_out: the count
+//   hist: 4 * TK_BINS words, 16-byte aligned; bitmap, wpre: NPT * TK_THREADS / 32 words each; xch: TK_XCH words (all LDS)
+template <int NPT, class LoadFn>
+__device__ __forceinline__ void topk_regs_row(LoadFn load, int N, int C, int32_t* __restrict__ out,
+                                              int32_t* __restrict__ cnt_out, uint32_t* hist, uint32_t* bitmap,
+                                              uint32_t* wpre, uint32_t* xch) {
+  constexpr int WORDS = NPT * TK_THREADS / 32;   // bitmap words
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int keep = N < C ? N : C;
+  if (tid == 0) *cnt_out = keep;
+  for (int i = keep + tid; i < C; i += TK_THREADS) out[i] = -1;
+  if (keep == 0) return;
+  uint32_t key[NPT];
+  int32_t tok[NPT];
+  bool have[NPT], sel[NPT];
+  // every load is issued before the first one is waited for: slots beyond the row re-read its last score (N >= 1
+  // here) instead of sitting in a branch of their own, which would serialise the NPT round trips
+  float raw[NPT];
+#pragma unroll
+  for (int e = 0; e < NPT; ++e) {
+    tok[e] = tid + e * TK_THREADS;
+    have[e] = tok[e] < N;
+    raw[e] = load(have[e] ? tok[e] : N - 1);
+  }
+#pragma unroll
+  for (int e = 0; e < NPT; ++e) {
+    key[e] = have[e] ? score_key(raw[e]) : 0u;
+    sel[e] = have[e];
+  }
+  if (keep < N) mark_best<TK_THREADS, 12, NPT, 4>(key, tok, have, keep, hist, xch, sel);
+#pragma unroll
+  for (int e = 0; e < NPT; ++e) {   // tokens e * 1024 + wave * 64 + 0..63: words e * 32 + 2 * wave and the next
+    const unsigned long long m = __ballot(sel[e]);
+    if (lane == 0) {
+      bitmap[e * (TK_THREADS / 32) + 2 * wave] = (uint32_t)m;
+      bitmap[e * (TK_THREADS / 32) + 2 * wave + 1] = (uint32_t)(m >> 32);
+    }
+  }
+  __syncthreads();
+  // exclusive prefix of the words' bit counts: a thread owns WPT consecutive words
+  constexpr int WPT = (WORDS + TK_THREADS - 1) / TK_THREADS;
+  uint32_t pc[WPT], mine = 0;
+#pragma unroll
+  for (int k = 0; k < WPT; ++k) {
+    const int wd = tid * WPT + k;
+    pc[k] = wd < WORDS ? (uint32_t)__popc(bitmap[wd]) : 0u;
+    mine += pc[k];
+  }
+  const uint32_t inc = wave_incl_scan(mine);
+  if (lane == 63) xch[wave] = inc;
+  __syncthreads();
+  uint32_t woff[1];
+  seg_wave_offsets<TK_THREADS / 64, 1>(xch, wave, woff);
+  uint32_t run = woff[0] + inc - mine;
+#pragma unroll
+  for (int k = 0; k < WPT; ++k) {
+    const int wd = tid * WPT + k;
+    if (wd < WORDS) wpre[wd] = run;
+    run += pc[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < NPT; ++e)
+    if (sel[e]) {
+      const uint32_t rank = wpre[tok[e] >> 5] + (uint32_t)__popc(bitmap[tok[e] >> 5] & ((1u << (tok[e] & 31)) - 1u));
+      out[rank] = tok[e];
+    }
 }
 
 }  // namespace asx

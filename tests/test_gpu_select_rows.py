@@ -1,0 +1,85 @@
+"""Few-row shapes: scoring and the per-row top-k in one launch (the workgroup that completes a row's arrival count
+selects it) against the two stand-alone kernels, one after the other (per-ctx development mode).  Same scores, so the
+selections must agree bit for bit, on every repetition (the arrival counters return to zero); and both against the
+oracle.  Cases: the two few-row workloads, rows shorter than the budget, empty sequences (their workgroups arrive
+too), a ragged batch, the longest rows the register top-k holds (32768 tokens), groups of 16 heads (two operand
+sets), sum aggregation, a block table wider than every sequence, a budget of 1."""
+import pytest
+import torch
+
+import oracle
+from paper_2510_07486_amd import api
+from paper_2510_07486_amd import workloads as wl
+from gpu_common import f32, params_for, to_dev
+from helpers import compare_selection
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # batch, Hq, Hkv, W, budget, ctx, ctx_min, agg
+    (1, 8, 2, 8, 256, 4096, None, 0),        # workload c1
+    (1, 32, 8, 16, 2048, 16384, None, 0),    # workload c2
+    (1, 32, 8, 16, 2048, 32768, None, 0),    # the longest rows of the register top-k: 32 keys per thread
+    (2, 8, 2, 8, 600, 500, 100, 0),          # rows shorter than the budget: everything is kept
+    (4, 8, 2, 4, 64, 3000, 0, 1),            # sum aggregation; sequences of length 0
+    (3, 32, 2, 8, 100, 5000, 1, 0),          # groups of 16 heads: two operand sets; ragged down to one token
+    (2, 4, 4, 8, 1, 1000, 300, 0),           # budget 1 (MHA)
+    (2, 16, 4, 8, 333, 7000, 2500, 0),       # odd page counts: the last iteration of a wavefront has one page
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_one_launch_equals_the_two_stand_alone_kernels(case):
+    B, Hq, Hkv, W, C, ctx_len, ctx_min, agg = case
+    print("select rows", case, flush=True)
+    w = wl.Workload("sr", B, Hq, Hkv, W, C, ctx_len, ctx_min=ctx_min, page_table="scatter", pool_slack=1.3, seed=C + B)
+    cpu = wl.make_inputs(w)
+    if ctx_min == 0:
+        cpu.ctx_lens[0] = 0
+        cpu.ctx_lens[B - 1] = 0
+    dev = to_dev(cpu)
+    p = params_for(cpu, agg=agg)
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    ctx = api.Context(p)
+    ctx.set_select_mode(1)                                    # the two stand-alone kernels
+    ri, rc = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    torch.cuda.synchronize()
+    ctx.set_select_mode(0)
+    share, shares, cand = api.select_plan(p, 1)
+    for rep in range(5):
+        gi, gc = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+        torch.cuda.synchronize()
+        assert torch.equal(gi, ri) and torch.equal(gc, rc), rep
+    q_hat = api.as_predict_query(ctx, p, dev.q_win, dev.q_cur)
+    gi2, gc2 = api.as_score_topk(ctx, p, kv, q_hat)
+    torch.cuda.synchronize()
+    assert torch.equal(gi2, ri) and torch.equal(gc2, rc)
+    assert ctx.damaged_workspace_gap(p) == -1
+    rq, rs, oidx, ocnt = oracle.select_step(cpu.k_pool, cpu.block_table, cpu.ctx_lens, cpu.q_win, cpu.q_cur, C, f32(1e-2),
+                                            agg=agg, sm_scale=p.sm_scale)
+    swaps = compare_selection(ri, rc, oidx, ocnt, rs, cpu.ctx_lens, C)
+    print(f"  plan {(share, shares, cand)}, tie swaps vs oracle {swaps}", flush=True)
+
+
+def test_one_launch_form_under_the_static_entry_and_a_wide_block_table():
+    """The entry point that allocates nothing takes the same route with the static array's counters; the block table
+    is four times wider than the longest sequence, so most workgroups of a row have no pages and only arrive."""
+    B, Hq, Hkv, W, C = 2, 8, 2, 8, 128
+    w = wl.Workload("srs", B, Hq, Hkv, W, C, 2000, ctx_min=700, page_table="scatter", pool_slack=1.3, seed=5)
+    cpu = wl.make_inputs(w)
+    wide = torch.zeros((B, cpu.block_table.shape[1] * 4), dtype=torch.int32)
+    wide[:, :cpu.block_table.shape[1]] = cpu.block_table
+    cpu.block_table = wide
+    dev = to_dev(cpu)
+    p = params_for(cpu)
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    ctx = api.Context(p)
+    ctx.set_select_mode(1)
+    ri, rc = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        gi = torch.empty_like(ri)
+        gc = torch.empty_like(rc)
+        api.as_select_step_static(p, kv, dev.q_win, dev.q_cur, gi, gc)
+        torch.cuda.synchronize()
+        assert torch.equal(gi, ri) and torch.equal(gc, rc), rep
