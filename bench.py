@@ -563,7 +563,7 @@ def main():
         "step_roofline_frac_serial": round(step_roofline_us / us_layer_serial, 4),
         "score_keys_gbs": round(achieved, 1), "score_keys_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "score_keys_gbs_while_overlapped": round(k_bytes / (score_ms_shared * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "score_keys + topk_select (stand-alone kernels)" if a.unfused else ("as_score_topk (select_slice_kernel [+ select_merge_kernel]; few-row shapes: the stand-alone kernels)"
+        "roofline": {"bound": "hbm", "kernel": "score_keys + topk_select (stand-alone kernels)" if a.unfused else ("as_score_topk (select_slice_kernel [+ select_merge_kernel]; few-row shapes: select_rows_kernel)"
                                                               if pack == 1 else
                                                               "as_select_step_pack (predict + slice [+ merge] kernels)"), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_note,
