@@ -83,3 +83,25 @@ def test_one_launch_form_under_the_static_entry_and_a_wide_block_table():
         api.as_select_step_static(p, kv, dev.q_win, dev.q_cur, gi, gc)
         torch.cuda.synchronize()
         assert torch.equal(gi, ri) and torch.equal(gc, rc), rep
+
+
+def test_two_hundred_launches_back_to_back_leave_the_counters_at_zero():
+    """No synchronisation between the launches: each one finds the arrival counters as the previous one left them
+    (zero), and every result equals the two-launch reference."""
+    B, Hq, Hkv, W, C = 2, 8, 2, 8, 200
+    w = wl.Workload("srr", B, Hq, Hkv, W, C, 6000, ctx_min=1500, page_table="scatter", pool_slack=1.3, seed=11)
+    cpu = wl.make_inputs(w)
+    dev = to_dev(cpu)
+    p = params_for(cpu)
+    kv = api.kv_view(dev.k_pool, dev.v_pool, dev.block_table, dev.ctx_lens)
+    ctx = api.Context(p)
+    ctx.set_select_mode(1)
+    ri, rc = api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur)
+    torch.cuda.synchronize()
+    ctx.set_select_mode(0)
+    outs = [(torch.empty_like(ri), torch.empty_like(rc)) for _ in range(200)]
+    for gi, gc in outs:
+        api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur, gi, gc)
+    torch.cuda.synchronize()
+    for n, (gi, gc) in enumerate(outs):
+        assert torch.equal(gi, ri) and torch.equal(gc, rc), n
