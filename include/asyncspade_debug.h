@@ -27,8 +27,9 @@ AS_API as_status as_debug_select_plan(const as_params* p, int32_t n_layers, int3
 AS_API as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_layers, int32_t* first_bad);
 
 /* Route of single-layer selections of THIS ctx: 0 = chosen from the share plan (default), 1 = always the
- * stand-alone scoring and top-k kernels through score rows in the workspace, 2 = always the fused kernels
- * (where a share plan exists). */
+ * stand-alone scoring and top-k kernels through score rows in the workspace (two launches), 2 = always the fused
+ * kernels (where a share plan exists), 3 = always through score rows, scoring and top-k in one launch where the
+ * shape allows it (what mode 0 does for few-row shapes). */
 AS_API as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode);
 
 /* How rows that the fused selection cuts into several shares are merged for THIS ctx: 0 = inside the selection kernel

@@ -213,7 +213,8 @@ class Context:
         return bad.value
 
     def set_select_mode(self, m: int):
-        """0 = as_select_step fuses scoring with top-k (default), 1 = separate kernels through HBM scores."""
+        """0 = route chosen from the share plan (default), 1 = the two stand-alone kernels through HBM scores, 2 = the fused
+        kernels, 3 = through HBM scores in one launch where the shape allows."""
         _check(lib().as_debug_set_select_mode(self.handle, m), "as_debug_set_select_mode")
 
     def set_attn_splits(self, n: int):

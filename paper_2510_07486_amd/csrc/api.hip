@@ -81,13 +81,15 @@ inline as_status hip_status(hipError_t e) { return e == hipSuccess ? AS_OK : AS_
 
 // Whether a single-layer selection runs as the two stand-alone stages (scores through the workspace) instead of
 // the fused kernels: when the fused kernels have no share plan for the shape, when the plan could not prune
-// anything, or when the development knob says so.  The softmax-normalised aggregation exists only in the fused
-// kernels.
-bool use_stages(int select_mode, const as_params* p) {
+// anything, when the one-launch form over score rows is faster for the shape, or when the development knob says so.
+// The softmax-normalised aggregation exists only in the fused kernels.
+bool use_stages(int select_mode, bool one_launch, const as_params* p) {
   if (p->agg == AS_AGG_SOFTMAX_SUM) return false;
   if (!asx::select_plan_ok(p, 1)) return true;      // more shares per row than the merge kernel indexes
   if (select_mode == 2) return false;
-  return select_mode == 1 || asx::select_prefers_stages(p);
+  if (select_mode == 1 || select_mode == 3 || asx::select_prefers_stages(p)) return true;
+  // mid-size shapes where scoring and top-k in one launch beat the fused kernels (only if that form will run)
+  return one_launch && asx::select_rows_ok(p) && asx::select_rows_preferred(p);
 }
 
 // arrivals != nullptr and a shape the one-launch form serves: scoring and the per-row top-k share a grid
@@ -283,7 +285,8 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
   if ((st = check_kv(kv, false)) != AS_OK) return st;
   if (!ctx || !q_hat || !sel_idx || !sel_cnt) return AS_ERR_INVALID_ARG;
   if (p->agg == AS_AGG_SOFTMAX_SUM && !asx::select_plan_ok(p, 1)) return AS_ERR_UNSUPPORTED;
-  const bool stages = use_stages(ctx->select_mode, p);
+  const bool one_launch = ctx->merge_mode == 0 && ctx->select_mode != 1;
+  const bool stages = use_stages(ctx->select_mode, one_launch, p);
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
@@ -293,8 +296,7 @@ as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, c
                                                ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
                                                sel_idx, sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, s));
   return hip_status(score_then_topk(p, kv, q_hat, reinterpret_cast<float*>(ws + l.scores), l.score_stride,
-                                    ctx->merge_mode == 0 && ctx->select_mode != 1
-                                        ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+                                    one_launch ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
                                     sel_idx, sel_cnt, s));
 }
 
@@ -306,9 +308,10 @@ as_status as_select_step(as_ctx* ctx, const as_params* p, const as_kv_view* kv, 
   const ws_layout l = layout_of(p, 1, ctx->attn_splits);
   if (!ctx->ws || ctx->ws_bytes < l.total) return AS_ERR_WORKSPACE;
   char* ws = static_cast<char*>(ctx->ws);
-  const bool stages = use_stages(ctx->select_mode, p);
-  const bool one_launch = ctx->merge_mode == 0 && !(stages && ctx->select_mode == 1);
-  return select_step_on(one_launch ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
+  const bool stages = use_stages(ctx->select_mode, ctx->merge_mode == 0 && ctx->select_mode != 1, p);
+  // the arrival counters serve the merge inside the fused kernel and the one-launch form over score rows alike
+  const bool counters = ctx->merge_mode == 0 && !(stages && ctx->select_mode == 1);
+  return select_step_on(counters ? reinterpret_cast<int32_t*>(ws + l.counters) : nullptr,
                         reinterpret_cast<float*>(ws + l.q_hat), reinterpret_cast<float*>(ws + l.scores), l.score_stride,
                         ws + l.cand, stages, ctx->predict_mode, p, kv, q_win, q_cur, sel_idx,
                         sel_cnt, asx::wg_timeline{ctx->timeline, ctx->timeline_cap}, static_cast<hipStream_t>(stream));
@@ -319,7 +322,7 @@ as_status as_select_step_static(const as_params* p, const as_kv_view* kv, const 
   as_status st = check_select_step(p, kv, q_win, q_cur, sel_idx, sel_cnt);
   if (st != AS_OK) return st;
   // q_hat, a gap, then the one region the route of this shape uses: score rows or candidates
-  const bool stages = use_stages(0, p);
+  const bool stages = use_stages(0, true, p);
   const int64_t score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
   const size_t q_bytes = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
   const size_t region = stages ? (size_t)p->batch * p->n_kv_heads * (size_t)score_stride * sizeof(float)
@@ -464,7 +467,7 @@ as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_lay
 }
 
 as_status as_debug_set_select_mode(as_ctx* ctx, int32_t mode) {
-  if (!ctx || mode < 0 || mode > 2) return AS_ERR_INVALID_ARG;
+  if (!ctx || mode < 0 || mode > 3) return AS_ERR_INVALID_ARG;
   ctx->select_mode = mode;
   return AS_OK;
 }

@@ -21,7 +21,8 @@ struct as_ctx {
   void* ws;
   size_t ws_bytes;
   int select_mode;   /* 0: fused score+top-k unless the share plan keeps every token (see select_prefers_stages),
-                        1: always the separate kernels via HBM scores, 2: always fused */
+                        1: always the separate kernels via HBM scores, 2: always fused, 3: always via HBM scores, in one
+                        launch where the shape allows */
   int attn_splits;   /* > 0: forced number of attention splits per (sequence, KV head) */
   int merge_mode;    /* 0: rows cut into shares are merged inside the selection kernel where its LDS holds the row's
                         candidates, 1: always by a second launch */
@@ -106,6 +107,7 @@ hipError_t launch_stream_read_flat(const void* buf, size_t nbytes, uint32_t* sin
 size_t stream_read_flat_sink_words();
 // few-row shapes: scoring and the per-row top-k in one grid (select_rows.hip)
 bool select_rows_ok(const as_params* p);
+bool select_rows_preferred(const as_params* p);
 hipError_t launch_select_rows(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
                               int64_t stride, int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,

@@ -14,12 +14,12 @@
 
 namespace asx {
 
-static constexpr int SR_PG = 2;                    // pages a wavefront has in flight per iteration
 static constexpr int SR_WAVES = TK_THREADS / 64;   // 16
-static constexpr int SR_ROUND = SR_WAVES * SR_PG;  // pages a workgroup takes per iteration
 static constexpr int SR_MAX_SHARE = 64 * SR_WAVES; // a lane holds one page id of its wavefront: 64 pages per wavefront
 
-template <int NSET, int NPT>
+// SR_PG: pages a wavefront has in flight per iteration (2: the smallest shapes, more workgroups; 4: twice the bytes
+// in flight per compute unit once a workgroup has at least two such iterations)
+template <int NSET, int NPT, int SR_PG>
 __global__ __launch_bounds__(TK_THREADS) void select_rows_kernel(
     const uint16_t* __restrict__ k_pool, const int32_t* __restrict__ block_table, const int32_t* __restrict__ ctx_lens,
     const float* __restrict__ q_hat, float* __restrict__ scores, int64_t stride, int32_t* __restrict__ arrivals,
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(TK_THREADS) void select_rows_kernel(
         res[pg] = group_max(v);
       }
       // lane group g < SR_PG writes token t of page g
-      const float outv = grp == 0 ? res[0] : res[SR_PG - 1];
+      const float outv = grp == 0 ? res[0] : grp == 1 ? res[1] : grp == 2 ? res[SR_PG > 2 ? 2 : 0] : res[SR_PG - 1];
       const int n = (pg0 + grp) * AS_PAGE + t;
       if (grp < SR_PG && pg0 + grp < p_end && n < N)
         st_dev(reinterpret_cast<uint32_t*>(srow) + n, __float_as_uint(outv + 0.0f));
@@ -100,18 +100,24 @@ __global__ __launch_bounds__(TK_THREADS) void select_rows_kernel(
                      sel_cnt + row, hist, bitmap, wpre, xch);
 }
 
-// Whether the one-launch form serves this shape: plain aggregation with at most two operand sets (groups of up to
-// 16 heads), rows that fit the register top-k, as many arrival counters as rows, and shares within what a
-// wavefront's lanes can index.
-static int rows_share_pages(const as_params* p) {
-  // about one workgroup per compute unit, in whole workgroup iterations
-  const int64_t total = (int64_t)p->batch * p->n_kv_heads * p->max_pages_per_seq;
-  int64_t sp = (total + 255) / 256;
-  sp = (sp + SR_ROUND - 1) / SR_ROUND * SR_ROUND;
-  if (sp < SR_ROUND) sp = SR_ROUND;
+static int rows_share_pages(const as_params* p, int* pg_out = nullptr) {
+  // as many shares per row as keep the whole grid within one workgroup per compute unit, in whole workgroup
+  // iterations; four pages per wavefront and iteration once a share has at least two such iterations
+  const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
+  const int64_t pages = p->max_pages_per_seq > 0 ? p->max_pages_per_seq : 1;
+  int64_t nshares = rows > 0 ? 256 / rows : 1;
+  if (nshares < 1) nshares = 1;
+  int64_t sp = (pages + nshares - 1) / nshares;
+  const int pg = 2;   // four pages per iteration were measured too (shares of 128 pages and more): no faster, and the 16- and 32-key instances spill
+  const int64_t round = SR_WAVES * pg;
+  sp = (sp + round - 1) / round * round;
+  if (pg_out) *pg_out = pg;
   return sp > SR_MAX_SHARE ? 0 : (int)sp;
 }
 
+// Whether the one-launch form serves this shape: plain aggregation with at most two operand sets (groups of up to
+// 16 heads), rows that fit the register top-k, as many arrival counters as rows, and shares within what a
+// wavefront's lanes can index.
 bool select_rows_ok(const as_params* p) {
   const int G = p->n_kv_heads > 0 ? p->n_q_heads / p->n_kv_heads : 0;
   if (p->agg == AS_AGG_SOFTMAX_SUM) return false;
@@ -122,20 +128,36 @@ bool select_rows_ok(const as_params* p) {
   return rows_share_pages(p) > 0;
 }
 
+// Shapes where this form beats the fused selection kernel even though that kernel's shares could prune: at most
+// half a chip's worth of rows (128) and at most 2^20 tokens in all (256 MiB of K).  Measured, one-launch against
+// fused, per as_score_topk call: batch 8 at 8192 tokens 35.0 / 41.8 us, batch 8 at 16384 61.2 / 64.5, batch 4 at 32768
+// 69.1 / 72.4, batch 16 at 4096 32.9 / 38.5, 64/8 heads batch 16 at 8192 58.8 / 65.1; beyond either bound the fused
+// kernel wins (batch 6 at 32768: 93.1 / 85.7, batch 32 at 4096: 56.5 / 54.0, batch 8 at 32768: 113.9 / 106.0).
+bool select_rows_preferred(const as_params* p) {
+  const int64_t rows = (int64_t)p->batch * p->n_kv_heads;
+  return rows <= 128 && rows * p->max_pages_per_seq * AS_PAGE <= ((int64_t)1 << 20);
+}
+
 hipError_t launch_select_rows(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
                               int64_t stride, int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
   if (p->batch == 0) return hipSuccess;
   const int G = p->n_q_heads / p->n_kv_heads;
-  const int sp = rows_share_pages(p);
+  int pg = 2;
+  const int sp = rows_share_pages(p, &pg);
   const int nshares = p->max_pages_per_seq > 0 ? (p->max_pages_per_seq + sp - 1) / sp : 1;   // >= 1: every row is selected
   const dim3 grid(nshares, p->n_kv_heads, p->batch);
   const int64_t longest = (int64_t)p->max_pages_per_seq * AS_PAGE;
   const int32_t last_page = (int32_t)(kv->num_pages > 0 ? kv->num_pages - 1 : 0);
-#define AS_ROWS_LAUNCH(NSET_, NPT_)                                                                               \
-  hipLaunchKernelGGL((select_rows_kernel<NSET_, NPT_>), grid, dim3(TK_THREADS), 0, s,                             \
+#define AS_ROWS_LAUNCH2(NSET_, NPT_, PG_)                                                                         \
+  hipLaunchKernelGGL((select_rows_kernel<NSET_, NPT_, PG_>), grid, dim3(TK_THREADS), 0, s,                        \
                      reinterpret_cast<const uint16_t*>(kv->k_pool), kv->block_table, kv->ctx_lens, q_hat, scores, \
                      stride, arrivals, sel_idx, sel_cnt, p->n_q_heads, p->n_kv_heads, G, p->agg, p->budget,       \
                      p->max_pages_per_seq, last_page, sp)
+#define AS_ROWS_LAUNCH(NSET_, NPT_)                        \
+  do {                                                     \
+    if (pg == 4) AS_ROWS_LAUNCH2(NSET_, NPT_, 4);          \
+    else AS_ROWS_LAUNCH2(NSET_, NPT_, 2);                  \
+  } while (0)
 #define AS_ROWS_NPT(NSET_)                                      \
   do {                                                          \
     if (longest <= 4 * TK_THREADS) AS_ROWS_LAUNCH(NSET_, 4);    \
@@ -147,6 +169,7 @@ hipError_t launch_select_rows(const as_params* p, const as_kv_view* kv, const fl
   else AS_ROWS_NPT(2);
 #undef AS_ROWS_NPT
 #undef AS_ROWS_LAUNCH
+#undef AS_ROWS_LAUNCH2
   return hipGetLastError();
 }
 

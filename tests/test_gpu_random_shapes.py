@@ -2,7 +2,8 @@
 batch, ragged lengths, budget, page-table kind, aggregation, predictor variant, sign of beta, ridge eps, a dense tail,
 single-layer against packed launches.  Every case runs predict -> select -> attend through the C ABI and is compared
 with the oracle: q_hat within tolerance, selections as sets with the tie band, attention over the GPU's own
-selection within the output tolerance, the log-sum-exp within 1e-3."""
+selection within the output tolerance, the log-sum-exp within 1e-3.  Single-layer cases are also run through every
+selection route (per-ctx development knob), which must agree bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -57,6 +58,15 @@ def test_random_shape(seed):
         api.as_select_step_pack(ctx, p, [api.layer_io(kvs[l], devs[l].q_win, devs[l].q_cur, sel[l][0], sel[l][1])
                                          for l in range(n_layers)])
     torch.cuda.synchronize()
+    if n_layers == 1:
+        # whichever route the library took by itself: the two stand-alone kernels, the fused kernels and the
+        # one-launch form over score rows give the same selection (the softmax-normalised aggregation exists only fused)
+        for mode in (1, 2, 3):
+            ctx.set_select_mode(mode)
+            oi, oc = api.as_select_step(ctx, p, kvs[0], devs[0].q_win, devs[0].q_cur)
+            torch.cuda.synchronize()
+            assert torch.equal(oi, sel[0][0]) and torch.equal(oc, sel[0][1]), mode
+        ctx.set_select_mode(0)
     swaps = 0
     for l, (c, d) in enumerate(zip(cpus, devs)):
         q_hat, sc, ridx, rcnt = oracle.select_step(c.k_pool, c.block_table, c.ctx_lens, c.q_win, c.q_cur, C, eps,
