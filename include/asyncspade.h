@@ -181,9 +181,11 @@ AS_API as_status as_dense_decode_attn(as_ctx* ctx, const as_params* p, const as_
  * (rows are scored in slices whose keys stay in LDS; only per-slice candidates, 8 B each,
  * go through the ctx workspace).  This is the kernel pair as_select_step runs.  One exception,
  * chosen on the host from the shapes: when the rows are so few that they are cut into slices
- * no longer than the budget (batch 1, short context), no slice could discard anything and the
- * call runs the two stand-alone kernels over score rows in the ctx workspace instead; the
- * result is the same.
+ * no longer than the budget (batch 1, short context), no slice could discard anything, and on
+ * small shapes in general (at most 128 rows and 2^20 tokens in all) pruning saves less than it
+ * costs: the call then scores into score rows in the ctx workspace and selects from them, in
+ * one launch where the rows fit the register top-k (32768 tokens, groups of up to 16 heads),
+ * else with the two stand-alone kernels; the result is the same.
  */
 AS_API as_status as_score_topk(as_ctx* ctx, const as_params* p, const as_kv_view* kv, const float* q_hat,
                         int32_t* sel_idx, int32_t* sel_cnt, void* stream);
