@@ -234,7 +234,9 @@ def probe_timeline(a, torch, api, wl):
         torch.cuda.synchronize()
         ctx.set_timeline(None)
         t = tb.cpu().numpy().astype(np.float64)
-        t = t[t[:, 1] > 0]
+        marked = t[:, 1] > 0
+        wg_id = np.arange(len(t))[marked]                    # consecutive ids go round-robin over the eight XCDs
+        t = t[marked]
         if len(t) == 0:                                      # this shape runs kernels that carry no marks
             out[name] = None
             continue
@@ -246,7 +248,10 @@ def probe_timeline(a, torch, api, wl):
                      "last_start_us": round(float(t[:, 0].max()), 1),
                      "end_us_p0_p10_p50_p90_p100": [round(float(x), 1) for x in np.percentile(t[:, 1], [0, 10, 50, 90, 100])],
                      "running_at_each_20th_of_span": [int(((t[:, 0] <= x) & (t[:, 1] > x)).sum())
-                                                      for x in np.linspace(0, span, 21)]}
+                                                      for x in np.linspace(0, span, 21)],
+                     # one resident round only: mean end time of the workgroups with id % 8 == 0..7
+                     "mean_end_us_by_workgroup_id_mod_8": ([round(float(t[wg_id % 8 == x, 1].mean()), 1) for x in range(8)]
+                                                           if len(t) <= 256 and len(t) >= 8 else None)}
     print(json.dumps(out))
 
 
