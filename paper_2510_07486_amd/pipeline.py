@@ -57,6 +57,10 @@ class SelectionPipeline:
             self._pack_ios = [[self._make_pack(parity, g) for g in range(self.n_packs)] for parity in range(2)]
         # recorded on a selection stream when a pack's selection into sel[parity] is complete
         self._sel_done = [[None] * self.n_packs for _ in range(2)]
+        # hand-over events, made once and recorded again every step (a wait refers to the record that precedes it in
+        # program order): creating two events per layer and step costs more host time than a small layer's kernels
+        self._ready_ev = [torch.cuda.Event() for _ in range(self.n_packs)]
+        self._done_ev = [[torch.cuda.Event() for _ in range(self.n_packs)] for _ in range(2)]
 
     # ------------------------------------------------------------------ pieces
     def _pack_range(self, g: int):
@@ -117,7 +121,7 @@ class SelectionPipeline:
                 self.s_att.wait_event(self._sel_done[cur][g])
             if l == self._pack_range(g)[-1]:           # a pack is selected once its last layer's state exists
                 lane = g % len(self.s_sel)
-                ready = torch.cuda.Event()
+                ready = self._ready_ev[g]
                 ready.record(self.s_att)               # layer l's step-t state exists from here on; every earlier
                 self.s_sel[lane].wait_event(ready)     # reader of buffer `nxt` has been enqueued before it
                 pair = None
@@ -129,7 +133,7 @@ class SelectionPipeline:
                 else:
                     self.select_layer(l, nxt, self.s_sel[lane], lane, pair)
                 if not join:
-                    done = torch.cuda.Event()
+                    done = self._done_ev[nxt][g]
                     done.record(self.s_sel[lane])
                     self._sel_done[nxt][g] = done
             self.attend(l, cur, outs[l] if per_layer else outs, self.s_att)
