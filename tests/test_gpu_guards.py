@@ -67,9 +67,14 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
     assert q_hat.intact()
 
     outs = {}
-    for name in ("select_step", "score_topk", "pack0", "pack1"):
+    for name in ("select_step", "score_topk", "pack0", "pack1", "fused", "two_launches"):
         outs[name] = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
     api.as_select_step(ctx, p, kv, dev.q_win, dev.q_cur, outs["select_step"][0].t, outs["select_step"][1].t)
+    # the routes the library did not take by itself for this shape (per-ctx development knob; same workspace layout)
+    ctx_routes = api.Context(p)
+    for name, mode in (("fused", 2), ("two_launches", 1)):
+        ctx_routes.set_select_mode(mode)
+        api.as_select_step(ctx_routes, p, kv, dev.q_win, dev.q_cur, outs[name][0].t, outs[name][1].t)
     api.as_score_topk(ctx, p, kv, q_hat.t, outs["score_topk"][0].t, outs["score_topk"][1].t)
     api.as_select_step_pack(ctx_pack, p, [api.layer_io(kv, dev.q_win, dev.q_cur, outs[n][0].t, outs[n][1].t)
                                      for n in ("pack0", "pack1")])
@@ -125,6 +130,7 @@ def test_outputs_stay_inside_their_arrays(kw, agg):
     # the regions of the context workspace (attention partials, q_hat, score rows, candidates) are separated by
     # gaps that hold the pattern as_create wrote: a kernel that outgrew the size computed for its region shows here
     assert ctx.damaged_workspace_gap(p) == -1
+    assert ctx_routes.damaged_workspace_gap(p) == -1
     assert ctx_pack.damaged_workspace_gap(p, 2) == -1
 
 
