@@ -191,6 +191,13 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
         kv = api.kv_view(clean.k_pool, clean.v_pool, bt, lens)
         sel = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
         api.as_select_step(ctx, p, kv, clean.q_win, clean.q_cur, sel[0].t, sel[1].t)
+        # the same through the routes the library does not take by itself for this shape (every route has its own clamps)
+        ctx_routes = api.Context(p)
+        sel_fused = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
+        sel_two = (Guarded((B, Hkv, C), torch.int32, -77), Guarded((B, Hkv), torch.int32, -77))
+        for mode, s_out in ((2, sel_fused), (1, sel_two)):
+            ctx_routes.set_select_mode(mode)
+            api.as_select_step(ctx_routes, p, kv, clean.q_win, clean.q_cur, s_out[0].t, s_out[1].t)
         q_hat = api.as_predict_query(ctx, p, clean.q_win, clean.q_cur)
         scores = Guarded((B, Hkv, bt.shape[1] * 16), torch.float32, 0.0)
         api.as_score_keys(ctx, p, kv, q_hat, scores.t)
@@ -223,10 +230,12 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
         api.as_kv_append(ctx, p, k_pool.t, v_pool.t, bt, lens2.t, k_new, k_new)
         torch.cuda.synchronize()
         guards = (sel[0], sel[1], scores, sel2[0], sel2[1], out, lse, dense, k_out, v_out, tab, ln, inter, k_pool,
-                  v_pool, lens2)
+                  v_pool, lens2, sel_fused[0], sel_fused[1], sel_two[0], sel_two[1])
         assert all(g.intact() for g in guards)
         assert ctx.damaged_workspace_gap(p) == -1
-        return dict(sel=sel[0].t, cnt=sel[1].t, sel2=sel2[0].t, out=out.t, lse=lse.t, dense=dense.t, k_out=k_out.t,
+        assert ctx_routes.damaged_workspace_gap(p) == -1
+        return dict(sel=sel[0].t, cnt=sel[1].t, sel2=sel2[0].t, sel_fused=sel_fused[0].t, cnt_fused=sel_fused[1].t,
+                    sel_two=sel_two[0].t, cnt_two=sel_two[1].t, out=out.t, lse=lse.t, dense=dense.t, k_out=k_out.t,
                     inter=inter.t)
 
     ref = run(clean.block_table, clean.ctx_lens, damage_selection=False)
@@ -238,7 +247,7 @@ def test_corrupt_tables_stay_inside_the_pool_and_inside_their_rows():
         lens[1] = bad_len
         print("corrupt", bad_len, flush=True)
         got = run(bt, lens, damage_selection=True)
-        for name in ("sel", "cnt", "sel2", "out", "lse", "dense", "inter"):
+        for name in ("sel", "cnt", "sel2", "sel_fused", "cnt_fused", "sel_two", "cnt_two", "out", "lse", "dense", "inter"):
             for b in (0, 2):
                 assert torch.equal(got[name][b], ref[name][b]), (name, b)
         cp = api.compact_pages(p)
