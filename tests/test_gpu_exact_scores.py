@@ -59,9 +59,12 @@ def test_exact_scores_match_oracle_bit_for_bit(pattern, shape):
     p = api.make_params(B, Hkv * G, Hkv, 4, C, bt.shape[1])
     c = api.Context(p)
     kd = k.cuda()
-    idx, cnt = api.as_score_topk(c, p, api.kv_view(kd, None, bt.cuda(), lens.cuda()), q_hat.cuda())
-    assert torch.equal(cnt.cpu(), rcnt)
-    assert torch.equal(idx.cpu(), ridx)
+    for mode in (0, 1, 2, 3):                      # the library's own route, then every route forced in turn
+        c.set_select_mode(mode)
+        idx, cnt = api.as_score_topk(c, p, api.kv_view(kd, None, bt.cuda(), lens.cuda()), q_hat.cuda())
+        assert torch.equal(cnt.cpu(), rcnt), mode
+        assert torch.equal(idx.cpu(), ridx), mode
+    c.set_select_mode(0)
     # and through the stand-alone stages
     sc = api.as_score_keys(c, p, api.kv_view(kd, None, bt.cuda(), lens.cuda()), q_hat.cuda(), fill=0.0)
     for b in range(B):
