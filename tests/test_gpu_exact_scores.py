@@ -46,6 +46,8 @@ def build(B, Hkv, G, ctx_lens, pattern, seed=0):
     dict(B=2, Hkv=2, G=4, ctx=[40000, 23457], C=2048),      # few rows: many shares per row
     dict(B=40, Hkv=8, G=4, ctx=None, C=1024),                # many rows: one share, several sub-slices
     dict(B=3, Hkv=2, G=8, ctx=[9000, 100, 33000], C=5000),  # budget above the running-set capacity
+    dict(B=2, Hkv=2, G=4, ctx=[30000, 12345], C=2048),      # rows within the register top-k: scoring and top-k in one launch
+    dict(B=5, Hkv=1, G=16, ctx=[7000, 1, 16, 4097, 2048], C=300),  # ... with two operand sets and very short rows
 ])
 def test_exact_scores_match_oracle_bit_for_bit(pattern, shape):
     print("exact", pattern, {k: (v if k != "ctx" else "...") for k, v in shape.items()}, flush=True)
