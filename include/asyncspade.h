@@ -223,11 +223,11 @@ AS_API as_status as_select_step_static(const as_params* p, const as_kv_view* kv,
                                        int32_t* sel_idx, int32_t* sel_cnt, void* stream);
 
 /*
- * Depth-wise packed selection (Sec. 4.3, "Depth-wise Parallelism on Cache Rank": several
- * consecutive decoder blocks are bundled into one unit and filtered with parallelism along
- * the depth dimension).  One call = as_select_step for n_layers layers, run as ONE predictor
- * launch and ONE scoring/top-k launch (plus one merge launch when rows are cut into shares)
- * whose grids cover every layer of the pack.  Each layer brings its own cache view, query
+ * Depth-wise packed selection (Sec. 4.3, the paragraph on depth-wise parallelism of the cache
+ * rank: the selections of several consecutive layers are made together, as one unit of work).
+ * One call = as_select_step for n_layers layers, run as ONE predictor launch and ONE
+ * scoring/top-k launch (plus one merge launch when rows are cut into more shares than the
+ * kernel merges itself) whose grids cover every layer of the pack.  Each layer brings its own cache view, query
  * window and output arrays; all layers share the shapes in `p`.  Results are identical, bit
  * for bit, to n_layers separate as_select_step calls.
  *   layers    HOST array of n_layers entries (read during the call, not kept);

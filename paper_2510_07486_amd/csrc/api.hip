@@ -31,6 +31,11 @@ struct ws_layout {
 // The attention partials come first, so that a ctx that only attends needs nothing else.  n_layers > 1: the
 // layout of a packed selection (one q_hat block per layer, candidates of the whole pack); the single-layer
 // layout also holds the score rows of the unfused path.  attn_splits: the forced split count of the ctx (0 = rule).
+// a pack whose shape the one-launch form over score rows serves and wins on (select_rows.hip)
+bool pack_rows_shape(const as_params* p, int n_layers) {
+  return p->agg != AS_AGG_SOFTMAX_SUM && asx::select_rows_ok(p, n_layers) && asx::select_rows_preferred(p, n_layers);
+}
+
 ws_layout layout_of(const as_params* p, int n_layers = 1, int attn_splits = 0) {
   ws_layout l;
   l.score_stride = (int64_t)p->max_pages_per_seq * AS_PAGE;
@@ -42,7 +47,11 @@ ws_layout layout_of(const as_params* p, int n_layers = 1, int attn_splits = 0) {
   l.q_hat_layer = align_up((size_t)p->batch * p->n_q_heads * AS_HEAD_DIM * sizeof(float));
   l.gap[1] = l.q_hat + l.q_hat_layer * n_layers;
   l.scores = l.gap[1] + WS_GAP;
-  size_t sc = n_layers > 1 ? 0 : align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
+  // score rows: of the single layer (stand-alone stages, one-launch form); of a pack only where the pack's shape
+  // can take the one-launch form
+  size_t sc = 0;
+  if (n_layers == 1) sc = align_up((size_t)p->batch * p->n_kv_heads * (size_t)l.score_stride * sizeof(float));
+  else if (pack_rows_shape(p, n_layers)) sc = align_up(asx::select_rows_score_bytes(p, n_layers));
   l.gap[2] = l.scores + sc;
   l.cand = l.gap[2] + WS_GAP;
   l.gap[3] = l.cand + align_up(asx::select_workspace_bytes(p, n_layers));
@@ -89,15 +98,24 @@ bool use_stages(int select_mode, bool one_launch, const as_params* p) {
   if (select_mode == 2) return false;
   if (select_mode == 1 || select_mode == 3 || asx::select_prefers_stages(p)) return true;
   // mid-size shapes where scoring and top-k in one launch beat the fused kernels (only if that form will run)
-  return one_launch && asx::select_rows_ok(p) && asx::select_rows_preferred(p);
+  return one_launch && asx::select_rows_ok(p, 1) && asx::select_rows_preferred(p, 1);
 }
 
 // arrivals != nullptr and a shape the one-launch form serves: scoring and the per-row top-k share a grid
 // (select_rows.hip); otherwise the two stand-alone kernels, one after the other.  Same scores, same selection.
 hipError_t score_then_topk(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores, int64_t stride,
                            int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s) {
-  if (arrivals && asx::select_rows_ok(p))
-    return asx::launch_select_rows(p, kv, q_hat, scores, stride, arrivals, sel_idx, sel_cnt, s);
+  if (arrivals && asx::select_rows_ok(p, 1)) {
+    asx::sel_tab tab = {};                       // a pack of one layer
+    tab.k_pool[0] = static_cast<const uint16_t*>(kv->k_pool);
+    tab.block_table[0] = kv->block_table;
+    tab.ctx_lens[0] = kv->ctx_lens;
+    tab.q_hat[0] = q_hat;
+    tab.sel_idx[0] = sel_idx;
+    tab.sel_cnt[0] = sel_cnt;
+    tab.last_page[0] = (int32_t)(kv->num_pages - 1);
+    return asx::launch_select_rows(p, 1, tab, scores, stride, arrivals, s);
+  }
   const hipError_t e = asx::launch_score(p, kv, q_hat, scores, stride, s);
   if (e != hipSuccess) return e;
   return asx::launch_topk(p, scores, stride, kv->ctx_lens, sel_idx, sel_cnt, s);
@@ -377,7 +395,11 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     stab.last_page[l] = (int32_t)(layers[l].kv.num_pages - 1);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool fuse = ctx->predict_mode == 1 && asx::select_can_predict(p);   // predictor in the selection kernel's prologue
+  // few rows in the whole pack: scoring and top-k over score rows in one grid (the workspace holds score rows for a
+  // pack only where pack_rows_shape says so); development routes 1 and 2 keep the fused kernels
+  const bool rows_route = n_layers > 1 && ctx->merge_mode == 0 && (ctx->select_mode == 0 || ctx->select_mode == 3) &&
+                          pack_rows_shape(p, n_layers);
+  const bool fuse = !rows_route && ctx->predict_mode == 1 && asx::select_can_predict(p);   // predictor in the selection kernel's prologue
   if (fuse) {
     for (int l = 0; l < n_layers; ++l) {
       stab.q_win[l] = pt.q_win[l];
@@ -387,6 +409,9 @@ as_status as_select_step_pack(as_ctx* ctx, const as_params* p, const as_layer_io
     hipError_t e = asx::launch_predict_pack(p, n_layers, pt, s);
     if (e != hipSuccess) return AS_ERR_HIP;
   }
+  if (rows_route)
+    return hip_status(asx::launch_select_rows(p, n_layers, stab, reinterpret_cast<float*>(ws + lay.scores),
+                                              lay.score_stride, reinterpret_cast<int32_t*>(ws + lay.counters), s));
   return hip_status(asx::launch_select_pack(p, n_layers, stab, ws + lay.cand,
                                             ctx->merge_mode == 0 ? reinterpret_cast<int32_t*>(ws + lay.counters) : nullptr,
                                             fuse, s));

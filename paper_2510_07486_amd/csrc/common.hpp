@@ -105,11 +105,12 @@ hipError_t launch_stream_read_paged(const as_params* p, const as_kv_view* kv, fl
                                     bool words_per_token, hipStream_t s);
 hipError_t launch_stream_read_flat(const void* buf, size_t nbytes, uint32_t* sink, hipStream_t s);
 size_t stream_read_flat_sink_words();
-// few-row shapes: scoring and the per-row top-k in one grid (select_rows.hip)
-bool select_rows_ok(const as_params* p);
-bool select_rows_preferred(const as_params* p);
-hipError_t launch_select_rows(const as_params* p, const as_kv_view* kv, const float* q_hat, float* scores,
-                              int64_t stride, int32_t* arrivals, int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
+// few-row shapes: scoring and the per-row top-k in one grid (select_rows.hip), over the rows of n_layers layers
+bool select_rows_ok(const as_params* p, int n_layers);
+bool select_rows_preferred(const as_params* p, int n_layers);
+size_t select_rows_score_bytes(const as_params* p, int n_layers);
+hipError_t launch_select_rows(const as_params* p, int n_layers, const sel_tab& tab, float* scores, int64_t stride,
+                              int32_t* arrivals, hipStream_t s);
 hipError_t launch_topk(const as_params* p, const float* scores, int64_t stride, const int32_t* ctx_lens,
                        int32_t* sel_idx, int32_t* sel_cnt, hipStream_t s);
 // fused scoring + top-k (select_fused.hip): rows are cut into slices of `slice_len` tokens

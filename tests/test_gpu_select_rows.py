@@ -105,3 +105,48 @@ def test_two_hundred_launches_back_to_back_leave_the_counters_at_zero():
     torch.cuda.synchronize()
     for n, (gi, gc) in enumerate(outs):
         assert torch.equal(gi, ri) and torch.equal(gc, rc), n
+
+
+@pytest.mark.parametrize("shape", [
+    (1, 8, 2, 8, 256, 4096, None, 12),      # workload c1, twelve layers per launch
+    (1, 32, 8, 16, 2048, 16384, None, 4),   # workload c2, four layers per launch
+    (3, 32, 2, 8, 100, 5000, 1, 3),         # groups of 16 heads, ragged, three layers
+    (2, 8, 2, 4, 64, 3000, 0, 5),           # empty sequences in every layer
+])
+def test_packed_one_launch_equals_the_packed_fused_kernels(shape):
+    """as_select_step_pack over few rows: the rows of all layers of the pack share one grid and one set of arrival
+    counters; same selections as the fused kernels over the same pack (development route 2), layer by layer, and as
+    single-layer calls."""
+    B, Hq, Hkv, W, C, ctx_len, ctx_min, n_layers = shape
+    print("select rows pack", shape, flush=True)
+    w = wl.Workload("srp", B, Hq, Hkv, W, C, ctx_len, ctx_min=ctx_min, page_table="scatter", pool_slack=1.3, seed=C + n_layers)
+    cpus = [wl.make_inputs(w, layer=l) for l in range(n_layers)]
+    if ctx_min == 0:
+        for c in cpus:
+            c.ctx_lens[0] = 0
+    devs = [to_dev(c) for c in cpus]
+    p = params_for(cpus[0])
+    kvs = [api.kv_view(d.k_pool, d.v_pool, d.block_table, d.ctx_lens) for d in devs]
+
+    def run(ctx):
+        sel = [(torch.empty((B, Hkv, C), dtype=torch.int32, device="cuda"),
+                torch.empty((B, Hkv), dtype=torch.int32, device="cuda")) for _ in range(n_layers)]
+        api.as_select_step_pack(ctx, p, [api.layer_io(kvs[l], devs[l].q_win, devs[l].q_cur, sel[l][0], sel[l][1])
+                                         for l in range(n_layers)])
+        torch.cuda.synchronize()
+        return sel
+
+    ctx_fused = api.Context(p, pack=n_layers)
+    ctx_fused.set_select_mode(2)
+    ref = run(ctx_fused)
+    ctx = api.Context(p, pack=n_layers)
+    for rep in range(3):
+        got = run(ctx)
+        for l in range(n_layers):
+            assert torch.equal(got[l][0], ref[l][0]) and torch.equal(got[l][1], ref[l][1]), (rep, l)
+    assert ctx.damaged_workspace_gap(p, n_layers) == -1
+    assert ctx_fused.damaged_workspace_gap(p, n_layers) == -1
+    single = api.Context(p)
+    for l in range(n_layers):
+        si, sc = api.as_select_step(single, p, kvs[l], devs[l].q_win, devs[l].q_cur)
+        assert torch.equal(si, ref[l][0]) and torch.equal(sc, ref[l][1]), l
