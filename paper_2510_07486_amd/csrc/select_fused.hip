@@ -876,9 +876,10 @@ __global__ __launch_bounds__(TK_THREADS) void select_merge_kernel(const sel_tab 
   if (tid == 0) sel_cnt[row] = keep;
 }
 
+// The prologue form keeps q_hat of the whole group in 8 KB of LDS: groups of up to 16 heads, whatever the aggregation.
 bool select_can_predict(const as_params* p) {
   const int G = p->n_q_heads / p->n_kv_heads;
-  return p->window <= 16 && p->agg != AS_AGG_SOFTMAX_SUM && (p->agg == AS_AGG_SUM || G <= 16);
+  return p->window <= 16 && p->agg != AS_AGG_SOFTMAX_SUM && G <= 16;
 }
 
 hipError_t launch_select_pack(const as_params* p, int n_layers, const sel_tab& tab_in, void* ws, int32_t* arrivals,

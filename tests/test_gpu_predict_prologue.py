@@ -20,6 +20,8 @@ CASES = [
     (3, 16, 1, 5, 128, 9000, 4000, 1, 1.0, 0),      # group of 16 (two operand sets), single-solve weights
     (4, 12, 12, 1, 64, 5000, 2000, 0, -1.0, 0),     # MHA, window of one query, the other softmax sign
     (6, 24, 4, 11, 300, 7000, 1, 1, -1.0, 1),       # sum aggregation, ragged down to one token
+    (2, 48, 2, 8, 100, 3000, 500, 0, 1.0, 1),       # sum aggregation over groups of 24 heads: more than the prologue holds, so the
+                                                    # predictor stays a launch of its own whatever the mode says
 ]
 
 

@@ -26,6 +26,7 @@ def _both(w, agg=0):
     idx = torch.full((w.batch, w.n_kv_heads, w.budget), -7, dtype=torch.int32, device="cuda")
     cnt = torch.full((w.batch, w.n_kv_heads), -7, dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
+    gc.collect()                                   # tensors of earlier cases must not be freed while we watch
     before = torch.cuda.memory_allocated()
     api.as_select_step_static(p, kv, dev.q_win, dev.q_cur, idx, cnt)
     torch.cuda.synchronize()
