@@ -6,7 +6,9 @@
 // time.  Here one grid does both: every workgroup scores its share of a row into the row's fp32 score buffer with
 // device-scope stores and counts itself in; the workgroup that completes a row's count reads the row back with
 // device-scope loads and selects (topk_regs_row).  The scores and therefore the selection are bit-identical to
-// those of the two stand-alone kernels (same operands, same MFMA order).
+// those of the two stand-alone kernels (same operands, same MFMA order).  With the launch gap gone the form also beats
+// the fused kernel on mid-size shapes whose shares could prune (select_rows_preferred), and it takes the rows of a
+// whole pack of layers in one grid (depth-wise packing, Sec. 4.3) like the fused kernel does.
 #include "common.hpp"
 #include "devscope.hpp"
 #include "score_common.hpp"
