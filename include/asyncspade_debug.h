@@ -20,6 +20,11 @@ extern "C" {
  * out[0..2] = {share length in tokens, shares per row, candidates kept per share}. */
 AS_API as_status as_debug_select_plan(const as_params* p, int32_t n_layers, int32_t* out);
 
+/* The one-launch selection over score rows (few rows) for a pack of n_layers layers:
+ * out[0..3] = {the form serves the shape (0/1), the library prefers it to the fused kernels for the shape (0/1),
+ * pages of a row one workgroup scores, workgroups per row}.  out[2] and out[3] are 0 when out[0] is. */
+AS_API as_status as_debug_rows_plan(const as_params* p, int32_t n_layers, int32_t* out);
+
 /* Checks the 256-byte gaps that separate the regions of the ctx workspace (layout of (p, n_layers)); a kernel
  * that wrote beyond its region has overwritten the pattern as_create left there.  Synchronises the device.
  * *first_bad = -1 if every gap is intact, else the index of the first damaged one (0 attention partials,

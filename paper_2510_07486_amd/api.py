@@ -25,7 +25,7 @@ EXPORTS = ["as_workspace_bytes", "as_workspace_bytes_attn", "as_create", "as_des
            "as_select_step_pack", "as_kv_append", "as_window_push", "as_gather_kv", "as_overlap_ratio",
            "as_dense_decode_attn"]
 # development / measurement entry points (include/asyncspade_debug.h)
-DEBUG_EXPORTS = ["as_debug_select_plan", "as_debug_workspace_gaps", "as_debug_set_select_mode",
+DEBUG_EXPORTS = ["as_debug_select_plan", "as_debug_rows_plan", "as_debug_workspace_gaps", "as_debug_set_select_mode",
                  "as_debug_set_attn_splits", "as_debug_set_timeline", "as_debug_set_predict_mode", "as_debug_set_merge_mode", "as_debug_attn_workspace_bytes", "as_debug_stream_read_paged",
                  "as_debug_stream_read_flat", "as_debug_stream_read_flat_sink_words"]
 AS_MAX_PACK = 16
@@ -105,6 +105,8 @@ def lib():
         L.as_overlap_ratio.argtypes = [vp, PP, vp, vp, vp, vp, vp, vp, vp]
         L.as_debug_select_plan.restype = C.c_int
         L.as_debug_select_plan.argtypes = [PP, C.c_int32, C.POINTER(C.c_int32)]
+        L.as_debug_rows_plan.restype = C.c_int
+        L.as_debug_rows_plan.argtypes = [PP, C.c_int32, C.POINTER(C.c_int32)]
         L.as_debug_workspace_gaps.restype = C.c_int
         L.as_debug_workspace_gaps.argtypes = [vp, PP, C.c_int32, C.POINTER(C.c_int32)]
         L.as_debug_set_select_mode.restype = C.c_int
@@ -165,6 +167,14 @@ def _check(code: int, where: str):
 
 def as_workspace_bytes(p: AsParams) -> int:
     return int(lib().as_workspace_bytes(C.byref(p)))
+
+
+def rows_plan(p: AsParams, n_layers: int = 1):
+    """(serves the shape, preferred to the fused kernels, pages per workgroup, workgroups per row) of the one-launch
+    selection over score rows."""
+    out = (C.c_int32 * 4)()
+    _check(lib().as_debug_rows_plan(C.byref(p), n_layers, out), "as_debug_rows_plan")
+    return tuple(out)
 
 
 def select_plan(p: AsParams, n_layers: int = 1):

@@ -471,6 +471,15 @@ as_status as_debug_select_plan(const as_params* p, int32_t n_layers, int32_t* ou
   return AS_OK;
 }
 
+as_status as_debug_rows_plan(const as_params* p, int32_t n_layers, int32_t* out) {
+  if (check_params(p) != AS_OK || !out || n_layers < 1 || n_layers > AS_MAX_PACK) return AS_ERR_INVALID_ARG;
+  out[0] = asx::select_rows_ok(p, n_layers) ? 1 : 0;
+  out[1] = out[0] && (n_layers == 1 ? use_stages(0, true, p) : pack_rows_shape(p, n_layers)) ? 1 : 0;
+  out[2] = out[0] ? asx::select_rows_share_pages(p, n_layers) : 0;
+  out[3] = out[0] ? (p->max_pages_per_seq > 0 ? (p->max_pages_per_seq + out[2] - 1) / out[2] : 1) : 0;
+  return AS_OK;
+}
+
 as_status as_debug_workspace_gaps(as_ctx* ctx, const as_params* p, int32_t n_layers, int32_t* first_bad) {
   if (!ctx || !first_bad || check_params(p) != AS_OK || n_layers < 1 || n_layers > AS_MAX_PACK)
     return AS_ERR_INVALID_ARG;

@@ -108,6 +108,7 @@ size_t stream_read_flat_sink_words();
 // few-row shapes: scoring and the per-row top-k in one grid (select_rows.hip), over the rows of n_layers layers
 bool select_rows_ok(const as_params* p, int n_layers);
 bool select_rows_preferred(const as_params* p, int n_layers);
+int select_rows_share_pages(const as_params* p, int n_layers);   // pages of a row per workgroup; 0: the form does not serve the shape
 size_t select_rows_score_bytes(const as_params* p, int n_layers);
 hipError_t launch_select_rows(const as_params* p, int n_layers, const sel_tab& tab, float* scores, int64_t stride,
                               int32_t* arrivals, hipStream_t s);

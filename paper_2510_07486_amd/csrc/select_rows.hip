@@ -110,7 +110,7 @@ __global__ __launch_bounds__(TK_THREADS) void select_rows_kernel(
                      sel_cnt + row, hist, bitmap, wpre, xch);
 }
 
-static int rows_share_pages(const as_params* p, int n_layers) {
+int select_rows_share_pages(const as_params* p, int n_layers) {
   // as many shares per row as keep the whole grid within one workgroup per compute unit, in whole workgroup
   // iterations (two pages per wavefront and iteration; four were measured too, for shares of 128 pages and more:
   // no faster, and the 16- and 32-key instances then spill)
@@ -134,7 +134,7 @@ bool select_rows_ok(const as_params* p, int n_layers) {
   if ((int64_t)p->max_pages_per_seq * AS_PAGE > 32 * TK_THREADS) return false;
   if ((int64_t)p->batch * p->n_kv_heads * n_layers > AS_SEL_COUNTERS) return false;
   if ((int64_t)p->batch * n_layers > 65535 || p->n_kv_heads > 65535) return false;
-  return rows_share_pages(p, n_layers) > 0;
+  return select_rows_share_pages(p, n_layers) > 0;
 }
 
 // Shapes where this form beats the fused selection kernel even though that kernel's shares could prune: at most
@@ -158,7 +158,7 @@ hipError_t launch_select_rows(const as_params* p, int n_layers, const sel_tab& t
                               int32_t* arrivals, hipStream_t s) {
   if (p->batch == 0) return hipSuccess;
   const int G = p->n_q_heads / p->n_kv_heads;
-  const int sp = rows_share_pages(p, n_layers);
+  const int sp = select_rows_share_pages(p, n_layers);
   const int nshares = p->max_pages_per_seq > 0 ? (p->max_pages_per_seq + sp - 1) / sp : 1;   // >= 1: every row is selected
   const dim3 grid(nshares, p->n_kv_heads, p->batch * n_layers);
   const int64_t longest = (int64_t)p->max_pages_per_seq * AS_PAGE;

@@ -152,6 +152,47 @@ def test_share_plan_invariants_over_random_shapes():
             assert api.as_workspace_bytes_pack(p, layers) >= need
 
 
+def test_one_launch_selection_plan_invariants_over_random_shapes():
+    """Host side of the one-launch selection over score rows: it serves only shapes its kernel can index (rows within
+    the register top-k, groups of up to 16 heads unless the query is pre-summed, plain aggregation, one arrival counter
+    per row); its shares are whole workgroup iterations of 32 pages, at most 1024 pages, cover the block table and keep
+    the grid within one workgroup per compute unit unless a row is a single share; it is preferred only for at most
+    128 rows and 2^20 tokens (or where no share of the fused kernel could prune); and a pack's workspace holds the
+    pack's score rows whenever the pack takes it."""
+    import random
+    rnd = random.Random(11)
+    seen_ok = seen_pref = 0
+    for _ in range(400):
+        hkv = rnd.choice([1, 2, 4, 8])
+        g = rnd.choice([1, 2, 4, 8, 16, 24, 64])
+        batch = rnd.choice([1, 2, 3, 8, 16, 32, 64, 200])
+        pages = rnd.choice([0, 1, 7, 64, 256, 1024, 2048, 2049, 4096])
+        budget = rnd.choice([1, 16, 256, 2048, 4096])
+        layers = rnd.choice([1, 1, 2, 4, 12, 16])
+        agg = rnd.choice([0, 0, 1, 2])
+        p = api.make_params(batch, hkv * g, hkv, 16, budget, pages, agg=agg)
+        ok, pref, share_pages, nshares = api.rows_plan(p, layers)
+        rows = batch * hkv * layers
+        if ok:
+            seen_ok += 1
+            assert agg != 2 and (agg == 1 or g <= 16)
+            assert pages * 16 <= 32768 and rows <= 16384 and batch * layers <= 65535
+            assert share_pages % 32 == 0 and 32 <= share_pages <= 1024
+            assert share_pages * nshares >= pages and (nshares - 1) * share_pages < max(pages, 1)
+            assert nshares == 1 or rows * nshares <= 256
+        else:
+            assert (share_pages, nshares) == (0, 0)
+            assert agg == 2 or (agg == 0 and g > 16) or pages * 16 > 32768 or rows > 16384 or \
+                (rows > 256 and pages > 1024) or (pages + max(1, 256 // rows) - 1) // max(1, 256 // rows) > 1024
+        if pref:
+            seen_pref += 1
+            assert ok
+            if layers > 1:
+                assert rows <= 128 and rows * pages * 16 <= 1 << 20
+                assert api.as_workspace_bytes_pack(p, layers) >= rows * pages * 16 * 4 + layers * batch * hkv * g * 128 * 4
+    assert seen_ok > 50 and seen_pref > 20
+
+
 def test_binding_fails_loudly_without_the_library(tmp_path, monkeypatch):
     """No CPU fallback anywhere above the C ABI: without the built library the binding raises, and neither the binding
     nor the pipeline module imports the oracle."""
